@@ -1,0 +1,233 @@
+"""Pins for the oracle's scoring half (logits, row softmax, aggregation).
+
+Each test checks the oracle against something fixed by the paper or by mathematics:
+a library softmax, closed forms, invariances, or a brute-force loop nest written
+directly from the Sec. 3.2 equation and the Sec. 3.2.2 aggregation rule.
+"""
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import specprefill_oracle as orc
+from paper_2502_02789_amd import synth
+
+
+def _bits(x):
+    return synth.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def _rand_case(seed, L, B_lens, N, H, H_kv, d):
+    g = np.random.default_rng(seed)
+    T = int(sum(B_lens))
+    q = _bits(g.standard_normal((L, len(B_lens), N, H, d)))
+    k = [_bits(g.standard_normal((T, H_kv, d))) for _ in range(L)]
+    cu = np.zeros(len(B_lens) + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(B_lens)
+    return q, k, cu
+
+
+def _brute_tensor(q_bits, k_bits, scale):
+    """[N, L, S, H] by nested Python loops straight from the equation (one sequence)."""
+    L, _, N, H, d = q_bits.shape
+    S, H_kv, _ = k_bits[0].shape
+    G = H // H_kv
+    qf = synth.bf16_bits_to_f32(q_bits).astype(float)
+    out = np.zeros((N, L, S, H))
+    for l in range(L):
+        kf = synth.bf16_bits_to_f32(k_bits[l]).astype(float)
+        for n in range(N):
+            for h in range(H):
+                logits = []
+                for i in range(S):
+                    dot = 0.0
+                    for t in range(d):
+                        dot += qf[l, 0, n, h, t] * kf[i, h // G, t]
+                    logits.append(scale * dot)
+                mx = max(logits)
+                ex = [math.exp(v - mx) for v in logits]
+                z = sum(ex)
+                for i in range(S):
+                    out[n, l, i, h] = ex[i] / z
+    return out
+
+
+def test_single_row_is_library_softmax():
+    # L = H = N = B = 1: the path is softmax(scale * K q) -- compare with scipy's routine
+    q, k, cu = _rand_case(1, 1, [257], 1, 1, 1, 64)
+    scale = 1.0 / math.sqrt(64)
+    for mode in (orc.LAYER_MAX, orc.LAYER_MEAN):
+        scores, lse = orc.token_importance(q, k, cu, scale, mode)
+        kf = synth.bf16_bits_to_f32(k[0])[:, 0, :].astype(np.float64)
+        qf = synth.bf16_bits_to_f32(q)[0, 0, 0, 0].astype(np.float64)
+        ref = scipy.special.softmax(scale * (kf @ qf))
+        np.testing.assert_allclose(scores, ref, rtol=1e-12, atol=0)
+        np.testing.assert_allclose(lse[0, 0, 0, 0], scipy.special.logsumexp(scale * (kf @ qf)), rtol=1e-12)
+
+
+def test_rows_sum_to_one_and_lse_consistent():
+    q, k, cu = _rand_case(2, 3, [40], 2, 4, 2, 16)
+    scale = 0.25
+    t = orc.attention_tensor(orc.bf16_bits_to_f64(q)[:, 0], [orc.bf16_bits_to_f64(x) for x in k], scale)
+    np.testing.assert_allclose(t.sum(axis=2), 1.0, rtol=1e-13)
+    _, lse = orc.token_importance(q, k, cu, scale)
+    # sum_i exp(s_i - lse) = 1 with logits recomputed here
+    qf = orc.bf16_bits_to_f64(q)
+    for l in range(3):
+        kf = orc.bf16_bits_to_f64(k[l])
+        for n in range(2):
+            for h in range(4):
+                s = scale * (kf[:, h // 2, :] @ qf[l, 0, n, h])
+                assert abs(np.exp(s - lse[l, 0, n, h]).sum() - 1.0) < 1e-12
+
+
+def test_brute_force_tensor_and_both_aggregations():
+    # small enough for the five-deep loop nest; H != H_kv so the head -> KV-head map matters
+    q, k, cu = _rand_case(3, 2, [13], 3, 4, 2, 8)
+    scale = 0.37
+    brute = _brute_tensor(q, k, scale)
+    t = orc.attention_tensor(orc.bf16_bits_to_f64(q)[:, 0], [orc.bf16_bits_to_f64(x) for x in k], scale)
+    np.testing.assert_allclose(t, brute, rtol=1e-12, atol=1e-300)
+    # aggregation written out by hand from Sec. 3.2.2
+    N, L, S, H = brute.shape
+    for mode in (orc.LAYER_MAX, orc.LAYER_MEAN):
+        want = np.zeros(S)
+        for i in range(S):
+            tot = 0.0
+            for n in range(N):
+                per_layer = [max(brute[n, l, i, h] for h in range(H)) for l in range(L)]
+                tot += max(per_layer) if mode == orc.LAYER_MAX else sum(per_layer) / L
+            want[i] = tot / N
+        np.testing.assert_allclose(orc.aggregate(t, mode), want, rtol=1e-13)
+        streamed, _ = orc.token_importance(q, k, cu, scale, mode)
+        np.testing.assert_allclose(streamed, want, rtol=1e-12)
+
+
+def test_kv_head_mapping_is_grouped_not_interleaved():
+    # KV head 0 makes token 0 dominant, KV head 1 makes token 1 dominant.  Query heads 0,1
+    # must follow KV head 0 and heads 2,3 KV head 1 (h // G), not h % H_kv.
+    d = 8
+    qv = np.zeros((1, 1, 1, 4, d), dtype=np.float32)
+    qv[..., 0] = 4.0
+    kv = np.zeros((3, 2, d), dtype=np.float32)
+    kv[0, 0, 0] = 4.0
+    kv[1, 1, 0] = 4.0
+    a, _ = orc.layer_attention(orc.bf16_bits_to_f64(_bits(qv))[0, 0], orc.bf16_bits_to_f64(_bits(kv)), 1.0)
+    assert a[0, :, 0].argmax() == 0 and a[0, :, 1].argmax() == 0
+    assert a[0, :, 2].argmax() == 1 and a[0, :, 3].argmax() == 1
+
+
+def test_identical_keys_give_uniform_scores():
+    g = np.random.default_rng(4)
+    L, N, H, H_kv, d, M = 3, 2, 4, 2, 16, 50
+    q = _bits(g.standard_normal((L, 1, N, H, d)))
+    k = []
+    for _ in range(L):
+        one = g.standard_normal((1, H_kv, d))
+        k.append(_bits(np.repeat(one, M, axis=0)))
+    cu = np.array([0, M], dtype=np.int32)
+    for mode in (orc.LAYER_MAX, orc.LAYER_MEAN):
+        s, _ = orc.token_importance(q, k, cu, 0.25, mode)
+        np.testing.assert_allclose(s, 1.0 / M, rtol=1e-13)
+
+
+def test_adding_a_vector_to_every_key_changes_nothing():
+    # exact in bf16: small integers
+    g = np.random.default_rng(5)
+    L, N, H, H_kv, d, M = 2, 2, 4, 2, 8, 21
+    q = _bits(g.integers(-3, 4, size=(L, 1, N, H, d)))
+    kf = [g.integers(-3, 4, size=(M, H_kv, d)).astype(np.float32) for _ in range(L)]
+    u = g.integers(-2, 3, size=(1, H_kv, d)).astype(np.float32)
+    cu = np.array([0, M], dtype=np.int32)
+    for mode in (orc.LAYER_MAX, orc.LAYER_MEAN):
+        s0, lse0 = orc.token_importance(q, [_bits(x) for x in kf], cu, 0.125, mode)
+        s1, lse1 = orc.token_importance(q, [_bits(x + u) for x in kf], cu, 0.125, mode)
+        np.testing.assert_allclose(s1, s0, rtol=1e-12)
+        assert not np.allclose(lse0, lse1)  # the rows did shift
+
+
+def test_aggregation_bounds_and_symmetries():
+    q, k, cu = _rand_case(6, 3, [33], 2, 4, 2, 16)
+    L, H = 3, 4
+    scale = 0.25
+    p, _ = orc.token_importance(q, k, cu, scale, orc.LAYER_MAX)
+    m, _ = orc.token_importance(q, k, cu, scale, orc.LAYER_MEAN)
+    assert 1.0 - 1e-12 <= m.sum() <= H + 1e-12
+    assert 1.0 - 1e-12 <= p.sum() <= H * L + 1e-12
+    assert (p >= m - 1e-15).all()
+    # permuting layers / queries changes nothing
+    perm = [2, 0, 1]
+    p2, _ = orc.token_importance(q[perm], [k[i] for i in perm], cu, scale, orc.LAYER_MAX)
+    m2, _ = orc.token_importance(q[perm], [k[i] for i in perm], cu, scale, orc.LAYER_MEAN)
+    np.testing.assert_allclose(p2, p, rtol=1e-13)
+    np.testing.assert_allclose(m2, m, rtol=1e-13)
+    p3, _ = orc.token_importance(q[:, :, ::-1], k, cu, scale, orc.LAYER_MAX)
+    np.testing.assert_allclose(p3, p, rtol=1e-13)
+    # permuting whole KV groups (query heads together with their KV head) changes nothing
+    qg = q.reshape(3, 1, 2, 2, 2, 16)[:, :, :, ::-1].reshape(q.shape)
+    kg = [x[:, ::-1] for x in k]
+    p4, _ = orc.token_importance(qg, kg, cu, scale, orc.LAYER_MAX)
+    np.testing.assert_allclose(p4, p, rtol=1e-13)
+    # duplicating every query head (G -> 2G) changes nothing
+    qd = np.repeat(q, 2, axis=3)
+    p5, _ = orc.token_importance(qd, k, cu, scale, orc.LAYER_MAX)
+    np.testing.assert_allclose(p5, p, rtol=1e-13)
+
+
+def test_all_heads_and_layers_identical_sum_to_one():
+    g = np.random.default_rng(7)
+    L, N, H, H_kv, d, M = 3, 1, 4, 2, 16, 30
+    q1 = g.standard_normal((1, 1, N, 1, d))
+    k1 = g.standard_normal((M, 1, d))
+    q = _bits(np.broadcast_to(q1, (L, 1, N, H, d)))
+    k = [_bits(np.broadcast_to(k1, (M, H_kv, d))) for _ in range(L)]
+    cu = np.array([0, M], dtype=np.int32)
+    for mode in (orc.LAYER_MAX, orc.LAYER_MEAN):
+        s, _ = orc.token_importance(q, k, cu, 0.25, mode)
+        assert abs(s.sum() - 1.0) < 1e-12
+
+
+def test_ragged_batch_equals_each_sequence_alone():
+    lens = [17, 1, 40, 0, 9]
+    q, k, cu = _rand_case(8, 2, lens, 2, 4, 2, 16)
+    s, lse = orc.token_importance(q, k, cu, 0.25, orc.LAYER_MAX)
+    for b, M in enumerate(lens):
+        if M == 0:
+            continue
+        lo, hi = cu[b], cu[b + 1]
+        sb, lb = orc.token_importance(q[:, b:b + 1], [x[lo:hi] for x in k], np.array([0, M], dtype=np.int32),
+                                      0.25, orc.LAYER_MAX)
+        np.testing.assert_allclose(s[lo:hi], sb, rtol=1e-13)
+        np.testing.assert_allclose(lse[:, b], lb[:, 0], rtol=1e-13)
+    # a one-token prompt scores exactly 1
+    assert s[cu[1]] == 1.0
+
+
+def test_only_valid_queries_are_averaged():
+    q, k, cu = _rand_case(9, 2, [20, 12], 4, 4, 2, 16)
+    nv = np.array([3, 1], dtype=np.int32)
+    s, _ = orc.token_importance(q, k, cu, 0.25, orc.LAYER_MEAN, n_valid=nv)
+    s_a, _ = orc.token_importance(q[:, 0:1, :3], [x[:20] for x in k], np.array([0, 20], dtype=np.int32),
+                                  0.25, orc.LAYER_MEAN)
+    s_b, _ = orc.token_importance(q[:, 1:2, :1], [x[20:] for x in k], np.array([0, 12], dtype=np.int32),
+                                  0.25, orc.LAYER_MEAN)
+    np.testing.assert_allclose(s[:20], s_a, rtol=1e-13)
+    np.testing.assert_allclose(s[20:], s_b, rtol=1e-13)
+
+
+def test_bf16_widening_is_exact():
+    bits = np.array([0x3F80, 0xBF80, 0x4049, 0x0000, 0x3DCD], dtype=np.uint16)
+    want = [1.0, -1.0, 3.140625, 0.0, 0.10009765625]
+    assert orc.bf16_bits_to_f64(bits).tolist() == want
+
+
+def test_planted_salient_tokens_score_high_on_the_tiny_workload():
+    # sanity of the input recipe + oracle together: the planted tokens dominate
+    w = synth.workload(1)
+    inp = synth.make_qk(w)
+    s, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], 1.0 / math.sqrt(w.d))
+    sal = inp["salient"]
+    assert sal.sum() == 20
+    top = np.argsort(-s)[: int(sal.sum())]
+    assert len(set(top.tolist()) & set(np.flatnonzero(sal).tolist())) >= 18
