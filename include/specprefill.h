@@ -1,0 +1,178 @@
+/*
+ * specprefill.h -- C ABI of the SpecPrefill token-importance path for AMD MI355X (gfx950).
+ *
+ * Method: "Speculative Prefill" (arXiv 2502.02789).  A draft model's stored queries
+ * (the last prompt token and/or N look-ahead tokens) score every prompt token by
+ * attention against the draft's K cache (Sec. 3.2 equation); scores are aggregated
+ * over heads, layers and queries (Sec. 3.2.2), smoothed by 1-D average pooling and
+ * cut to the top-k contiguous chunks (Sec. 3.2.3); kept tokens travel to the base
+ * model with their ORIGINAL position ids (Sec. 3.2.4).  Algorithm 1 names these
+ * steps compute_attention_score, aggregate_attention_score,
+ * chunk_select_from_smoothed_attention and restore_pos_ids.
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; everything else
+ *     (the structs themselves, k_layers[], h_* arrays) is HOST memory.
+ *   - The library allocates and frees no device memory; scratch space is the
+ *     caller's workspace (size from the *_workspace_bytes query).  It never
+ *     synchronises the stream: all work is enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream).
+ *   - Return value: SP_OK (0) or a negative sp_status.  On an argument error
+ *     nothing is launched and no output is written.
+ *   - Sequence b owns prompt tokens [cu_seqlens[b], cu_seqlens[b+1]) of the flat
+ *     token axis of length T = cu_seqlens[B]; empty sequences are allowed.
+ *   - NaN/Inf in Q or K, and token ids outside [0, V), are precondition violations
+ *     (undefined values, no fault for NaN/Inf; ids are NOT range-checked on device).
+ *   - Calls that share a workspace must not overlap in time.
+ */
+#ifndef SPECPREFILL_H
+#define SPECPREFILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SP_API __attribute__((visibility("default")))
+
+typedef enum {
+  SP_OK = 0,
+  SP_EINVAL = -1,       /* a size, rate or enum is out of range                  */
+  SP_ENULL = -2,        /* a required pointer is NULL                            */
+  SP_EALIGN = -3,       /* a pointer or stride breaks the 16-byte alignment rule */
+  SP_EWORKSPACE = -4,   /* workspace missing or smaller than *_workspace_bytes   */
+  SP_EUNSUPPORTED = -5, /* valid request this build has no kernel for            */
+  SP_ELAUNCH = -6       /* the HIP runtime refused a launch                      */
+} sp_status;
+
+/* How per-layer values are combined (Sec. 3.2.2).  The paper takes the maximum over
+ * heads AND layers; the alternative keeps the maximum over heads but averages layers. */
+typedef enum { SP_LAYER_MAX = 0, SP_LAYER_MEAN = 1 } sp_layer_reduce;
+
+#define SP_MAX_LAYERS 128
+#define SP_MAX_QUERIES 16
+
+/* ---------------------------------------------------------------------------
+ * sp_score: compute_attention_score + aggregate_attention_score (Algorithm 1),
+ * i.e. for every prompt token i of sequence b
+ *     s[l,h,n,i] = scale * <Q[l,b,n,h,:], K_l[i, h / (H/H_kv), :]>
+ *     a[l,h,n,i] = exp(s[l,h,n,i] - logsumexp_{i' in sequence b} s[l,h,n,i'])   (Sec. 3.2 eq.)
+ *     SP_LAYER_MAX : score[i] = mean_{n < n_valid[b]} max_{l,h} a               (Sec. 3.2.2)
+ *     SP_LAYER_MEAN: score[i] = mean_{n < n_valid[b]} mean_l max_h a
+ * The softmax runs over the prompt keys of the token's own sequence only.
+ * Q and K are taken as stored by the draft model (already position-encoded).
+ * --------------------------------------------------------------------------- */
+typedef struct {
+  int32_t B;                 /* sequences, >= 1                                           */
+  int32_t N;                 /* query rows per sequence, 1..SP_MAX_QUERIES                */
+  int32_t L;                 /* layers, 1..SP_MAX_LAYERS                                  */
+  int32_t H;                 /* query heads                                               */
+  int32_t H_kv;              /* key heads; H % H_kv == 0, H / H_kv <= 8                   */
+  int32_t d;                 /* head dim: 64 or 128                                       */
+  int64_t T;                 /* total prompt tokens = cu_seqlens[B], < 2^31               */
+  const void* d_q;           /* bf16 [L, B, N, H, d] contiguous, 16-byte aligned          */
+  const void* const* k_layers; /* HOST array of L device pointers; layer l holds bf16
+                                  K_l[i, g, t] at element offset i*k_token_stride +
+                                  g*k_head_stride + t (t contiguous); 16-byte aligned     */
+  int64_t k_token_stride;    /* elements, multiple of 8                                   */
+  int64_t k_head_stride;     /* elements, multiple of 8                                   */
+  const int32_t* d_cu_seqlens; /* int32 [B+1], cu[0] = 0, non-decreasing, cu[B] = T       */
+  const int32_t* d_n_valid;  /* int32 [B] with 1 <= n_valid[b] <= N, or NULL (= N): only the
+                                first n_valid[b] query rows count (EOS validity, Sec. 3.3)  */
+  float scale;               /* logit scale; the model's own attention uses 1/sqrt(d)     */
+  int32_t layer_reduce;      /* sp_layer_reduce                                           */
+  float rope_theta;          /* must be 0: Q and K are already rotated                    */
+  const int32_t* d_q_pos;    /* reserved for in-kernel rotation; must be NULL             */
+  float* d_scores;           /* out fp32 [T]                                              */
+  float* d_lse;              /* out fp32 [L, B, N, H] row log-sum-exp, or NULL            */
+  void* d_workspace;         /* device scratch, 256-byte aligned                          */
+  size_t workspace_bytes;
+} sp_score_args;
+
+/* Bytes of workspace sp_score needs for these shapes (pointers are not read).
+ * Returns 0 if the shape fields are invalid. */
+SP_API size_t sp_score_workspace_bytes(const sp_score_args* args);
+
+/* Enqueue the scoring on hip_stream.  Errors: SP_ENULL, SP_EINVAL (shape limits above),
+ * SP_EALIGN, SP_EWORKSPACE, SP_EUNSUPPORTED (rope_theta != 0), SP_ELAUNCH. */
+SP_API sp_status sp_score(const sp_score_args* args, void* hip_stream);
+
+/* Same contract and results as sp_score, but always runs the general two-pass kernels
+ * (sp_score picks a faster single-pass kernel when the shape allows).  Meant for
+ * cross-checking the two implementations of the Sec. 3.2 / 3.2.2 arithmetic. */
+SP_API sp_status sp_score_general(const sp_score_args* args, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * sp_pool_select: chunk_select_from_smoothed_attention (Algorithm 1, Sec. 3.2.3).
+ * Per sequence (length M): average-pool the scores with an odd window clipped to the
+ * sequence (divisor = in-range count); split into ceil(M/chunk) contiguous chunks and
+ * take each chunk's mean over its actual length; keep the
+ * k = clamp(ceil(keep_rate * n_chunks - 1e-9), 1, n_chunks) best chunks (keep rate =
+ * ratio of chunks, Sec. 4.1), equal scores resolved to the lower chunk index; emit the
+ * tokens of the kept chunks in ascending order.  Arithmetic is fp64 on the fp32 input.
+ * --------------------------------------------------------------------------- */
+typedef struct {
+  int32_t B;
+  int64_t T;
+  const int32_t* d_cu_seqlens;  /* int32 [B+1]                                             */
+  const float* d_scores;        /* fp32 [T]                                                */
+  int32_t chunk;                /* >= 1                                                    */
+  int32_t pool_window;          /* odd, >= 1 (1 = no smoothing)                            */
+  double keep_rate;             /* in (0, 1]                                               */
+  int32_t* d_kept_idx;          /* out int32 [kept_capacity]: flat token indices, ascending;
+                                   entries at and beyond cu_keep[B] are left untouched     */
+  int64_t kept_capacity;        /* >= number of kept tokens; T always suffices, see
+                                   sp_keep_upper_bound.  Writes beyond it are suppressed.  */
+  int32_t* d_cu_keep;           /* out int32 [B+1]: kept tokens of sequence b are
+                                   kept_idx[cu_keep[b] .. cu_keep[b+1])                    */
+  float* d_chunk_scores;        /* optional out fp32 [sum_b ceil(M_b/chunk)], NULL to skip */
+  void* d_workspace;
+  size_t workspace_bytes;
+} sp_pool_select_args;
+
+/* Host helper: an upper bound on the kept-token count from HOST sequence lengths
+ * (sum over sequences of min(M_b, k_b * chunk)); -1 on invalid arguments. */
+SP_API int64_t sp_keep_upper_bound(int32_t B, const int32_t* h_seqlens, int32_t chunk, double keep_rate);
+
+SP_API size_t sp_pool_select_workspace_bytes(const sp_pool_select_args* args);
+SP_API sp_status sp_pool_select(const sp_pool_select_args* args, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * sp_gather: restore_pos_ids (Algorithm 1, Sec. 3.2.4) plus the gathers the base
+ * model's prefill needs.  For kept slot s of sequence b:
+ *     kept_pos[s]  = kept_idx[s] - cu_seqlens[b]      (position in the ORIGINAL prompt)
+ *     kept_ids[s]  = token_ids[kept_idx[s]]
+ *     out_embed[s] = embed[kept_ids[s], :]
+ *     decode_pos[b] = M_b   (the first decoded token sits at the full prompt length)
+ * Integer outputs and copied rows are exact.
+ * --------------------------------------------------------------------------- */
+typedef struct {
+  int32_t B;
+  const int32_t* d_cu_seqlens;  /* int32 [B+1]                                            */
+  const int32_t* d_cu_keep;     /* int32 [B+1] from sp_pool_select                        */
+  const int32_t* d_kept_idx;    /* int32 [>= cu_keep[B]]                                  */
+  const int32_t* d_token_ids;   /* int32 [T], or NULL (then d_kept_ids/d_embed unused)    */
+  const void* d_embed;          /* bf16 [V, D] row-major, 16-byte aligned, or NULL        */
+  int32_t V;
+  int32_t D;                    /* multiple of 8 when d_embed != NULL                     */
+  int32_t* d_kept_ids;          /* out int32 [kept_capacity], NULL iff d_token_ids NULL   */
+  int32_t* d_kept_pos;          /* out int32 [kept_capacity]                              */
+  int32_t* d_decode_pos;        /* out int32 [B]                                          */
+  void* d_out_embed;            /* out bf16 [kept_capacity, D] or NULL to skip the rows   */
+  int64_t kept_capacity;        /* slots at and beyond min(cu_keep[B], capacity) untouched */
+} sp_gather_args;
+
+SP_API sp_status sp_gather(const sp_gather_args* args, void* hip_stream);
+
+/* Static, never-NULL description of a status code. */
+SP_API const char* sp_strerror(sp_status status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+SP_API int32_t sp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECPREFILL_H */

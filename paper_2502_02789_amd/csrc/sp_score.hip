@@ -1,0 +1,289 @@
+// sp_score: attention scores of the stored queries against the K cache, row softmax over
+// the prompt keys (Sec. 3.2 equation of arXiv 2502.02789) and the max/mean aggregation
+// over heads, layers and queries (Sec. 3.2.2).
+//
+// This file holds the argument checks, the dispatcher and the GENERAL kernels, which accept
+// every shape the header allows (ragged batches, any G = H/H_kv <= 8, N <= 16, d in {64,128}).
+// They read the K cache twice (once for the row statistics, once for the probabilities) and
+// use plain fp32 FMAs.  The single-pass MFMA kernel for one long prompt lives in
+// sp_score_stream.hip and is chosen by the dispatcher when the shape fits it.
+#include "sp_common.h"
+#include "sp_score_internal.h"
+
+namespace sp {
+
+constexpr int kTileKeys = 64;  // keys per tile of the general kernels (one per lane)
+
+// ---------------------------------------------------------------------------------------
+// tile table: tile_cu[b] = number of 64-key tiles in sequences before b
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void tile_table_kernel(int B, const int32_t* __restrict__ cu,
+                                                          int32_t* __restrict__ tile_cu) {
+  block_prefix_table(B, [&](int b) { return (cu[b + 1] - cu[b] + kTileKeys - 1) / kTileKeys; }, tile_cu);
+}
+
+template <int D>
+__device__ __forceinline__ void load_k_row(const uint16_t* __restrict__ kp, bool valid, float (&kf)[D]) {
+  const uint4* p4 = reinterpret_cast<const uint4*>(kp);
+#pragma unroll
+  for (int c = 0; c < D / 8; ++c) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (valid) v = p4[c];
+    kf[8 * c + 0] = bf16_lo(v.x); kf[8 * c + 1] = bf16_hi(v.x);
+    kf[8 * c + 2] = bf16_lo(v.y); kf[8 * c + 3] = bf16_hi(v.y);
+    kf[8 * c + 4] = bf16_lo(v.z); kf[8 * c + 5] = bf16_hi(v.z);
+    kf[8 * c + 6] = bf16_lo(v.w); kf[8 * c + 7] = bf16_hi(v.w);
+  }
+}
+
+// <q row, k row> with the q row at a wave-uniform address
+template <int D>
+__device__ __forceinline__ float dot_row(const uint16_t* __restrict__ qp, const float (&kf)[D]) {
+  const uint4* q4 = reinterpret_cast<const uint4*>(qp);
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll
+  for (int c = 0; c < D / 8; ++c) {
+    const uint4 v = q4[c];
+    a0 = fmaf(bf16_lo(v.x), kf[8 * c + 0], a0); a1 = fmaf(bf16_hi(v.x), kf[8 * c + 1], a1);
+    a2 = fmaf(bf16_lo(v.y), kf[8 * c + 2], a2); a3 = fmaf(bf16_hi(v.y), kf[8 * c + 3], a3);
+    a0 = fmaf(bf16_lo(v.z), kf[8 * c + 4], a0); a1 = fmaf(bf16_hi(v.z), kf[8 * c + 5], a1);
+    a2 = fmaf(bf16_lo(v.w), kf[8 * c + 6], a2); a3 = fmaf(bf16_hi(v.w), kf[8 * c + 7], a3);
+  }
+  return (a0 + a1) + (a2 + a3);
+}
+
+// ---------------------------------------------------------------------------------------
+// pass 1: per (tile, kv head, layer) the partial (max, sum exp) of every query row
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void lse_partial_kernel(const ScoreDev p) {
+  const int tile = blockIdx.x;
+  const int n_tiles = p.tile_cu[p.B];
+  if (tile >= n_tiles) return;
+  const int g = blockIdx.y, l = blockIdx.z;
+  const int lane = threadIdx.x;
+  const int b = upper_segment(p.tile_cu, p.B, tile);
+  const int seq0 = p.cu[b];
+  const int M = p.cu[b + 1] - seq0;
+  const int key = (tile - p.tile_cu[b]) * kTileKeys + lane;
+  const bool valid = key < M;
+  float kf[D];
+  load_k_row<D>(p.k[l] + (int64_t)(seq0 + (valid ? key : 0)) * p.k_token_stride + (int64_t)g * p.k_head_stride,
+                valid, kf);
+  for (int n = 0; n < p.N; ++n) {
+    for (int j = 0; j < p.G; ++j) {
+      const int h = g * p.G + j;
+      const uint16_t* qp = p.q + ((((int64_t)l * p.B + b) * p.N + n) * p.H + h) * D;
+      const float s = valid ? p.scale * dot_row<D>(qp, kf) : -INFINITY;
+      const float m = wave_max(s);                       // finite: lane 0 of a tile is always valid
+      const float e = valid ? expf(s - m) : 0.f;
+      const float z = wave_sum(e);
+      if (lane == 0) p.part[((int64_t)(l * p.N + n) * p.H + h) * p.max_tiles + tile] = make_float2(m, z);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// pass 1b: combine the tile partials of a row into its log-sum-exp
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void lse_combine_kernel(const ScoreDev p) {
+  const int row = blockIdx.x;  // ((l*B + b)*N + n)*H + h
+  const int lane = threadIdx.x;
+  const int h = row % p.H;
+  const int n = (row / p.H) % p.N;
+  const int b = (row / (p.H * p.N)) % p.B;
+  const int l = row / (p.H * p.N * p.B);
+  const int t0 = p.tile_cu[b], t1 = p.tile_cu[b + 1];
+  const float2* part = p.part + ((int64_t)(l * p.N + n) * p.H + h) * p.max_tiles;
+  float m = -INFINITY, z = 0.f;
+  for (int t = t0 + lane; t < t1; t += kWave) {
+    const float2 v = part[t];
+    const float mn = fmaxf(m, v.x);
+    z = z * expf(m - mn) + v.y * expf(v.x - mn);  // first step: z = 0 * exp(-inf) = 0
+    m = mn;
+  }
+  const float mw = wave_max(m);
+  const float zw = wave_sum(m == -INFINITY ? 0.f : z * expf(m - mw));
+  if (lane == 0) {
+    const float lse = (t1 > t0) ? mw + logf(zw) : 0.f;
+    p.ws_lse[row] = lse;
+    if (p.lse_out) p.lse_out[row] = lse;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// pass 2: probabilities, max over heads, max/mean over layers, mean over valid queries
+// one block = one 64-key tile; its 4 waves split the KV heads
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void score_accum_kernel(const ScoreDev p) {
+  __shared__ float red[2][4][SP_MAX_QUERIES][kWave];
+  const int tile = blockIdx.x;
+  const int n_tiles = p.tile_cu[p.B];
+  if (tile >= n_tiles) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int b = upper_segment(p.tile_cu, p.B, tile);
+  const int seq0 = p.cu[b];
+  const int M = p.cu[b + 1] - seq0;
+  const int key = (tile - p.tile_cu[b]) * kTileKeys + lane;
+  const bool valid = key < M;
+  const int64_t tok = seq0 + (valid ? key : 0);
+
+  float tot[SP_MAX_QUERIES];
+#pragma unroll
+  for (int n = 0; n < SP_MAX_QUERIES; ++n) tot[n] = (p.layer_reduce == SP_LAYER_MAX) ? -INFINITY : 0.f;
+
+  for (int l = 0; l < p.L; ++l) {
+    float nmax[SP_MAX_QUERIES];
+#pragma unroll
+    for (int n = 0; n < SP_MAX_QUERIES; ++n) nmax[n] = -INFINITY;
+    for (int g = wave; g < p.H_kv; g += 4) {
+      float kf[D];
+      load_k_row<D>(p.k[l] + tok * p.k_token_stride + (int64_t)g * p.k_head_stride, valid, kf);
+#pragma unroll
+      for (int n = 0; n < SP_MAX_QUERIES; ++n) {
+        if (n < p.N) {
+          float mx = nmax[n];
+          for (int j = 0; j < p.G; ++j) {
+            const int h = g * p.G + j;
+            const int64_t row = (((int64_t)l * p.B + b) * p.N + n) * p.H + h;
+            const float s = p.scale * dot_row<D>(p.q + row * D, kf);
+            mx = fmaxf(mx, s - p.ws_lse[row]);
+          }
+          nmax[n] = mx;
+        }
+      }
+    }
+    const int buf = l & 1;
+#pragma unroll
+    for (int n = 0; n < SP_MAX_QUERIES; ++n)
+      if (n < p.N) red[buf][wave][n][lane] = nmax[n];
+    __syncthreads();  // one barrier per layer: the buffers alternate
+#pragma unroll
+    for (int n = 0; n < SP_MAX_QUERIES; ++n) {
+      if (n < p.N) {
+        const float x = fmaxf(fmaxf(red[buf][0][n][lane], red[buf][1][n][lane]),
+                              fmaxf(red[buf][2][n][lane], red[buf][3][n][lane]));
+        if (p.layer_reduce == SP_LAYER_MAX) tot[n] = fmaxf(tot[n], x);
+        else tot[n] += expf(x);
+      }
+    }
+  }
+  if (wave == 0 && valid) {
+    int nv = p.n_valid ? p.n_valid[b] : p.N;
+    nv = max(1, min(nv, p.N));
+    float acc = 0.f;
+#pragma unroll
+    for (int n = 0; n < SP_MAX_QUERIES; ++n)
+      if (n < nv) acc += (p.layer_reduce == SP_LAYER_MAX) ? expf(tot[n]) : tot[n];
+    const float denom = (p.layer_reduce == SP_LAYER_MAX) ? (float)nv : (float)nv * (float)p.L;
+    p.scores[tok] = acc / denom;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+static bool shape_ok(const sp_score_args* a) {
+  if (a->B < 1 || a->N < 1 || a->N > SP_MAX_QUERIES || a->L < 1 || a->L > SP_MAX_LAYERS) return false;
+  if (a->H < 1 || a->H_kv < 1 || a->H % a->H_kv != 0 || a->H / a->H_kv > 8) return false;
+  if (a->d != 64 && a->d != 128) return false;
+  if (a->T < 0 || a->T >= (int64_t)INT32_MAX) return false;
+  if ((int64_t)a->L * a->B * a->N * a->H >= (int64_t)INT32_MAX) return false;
+  if (a->layer_reduce != SP_LAYER_MAX && a->layer_reduce != SP_LAYER_MEAN) return false;
+  return true;
+}
+
+static int general_max_tiles(const sp_score_args* a) { return (int)(a->T / kTileKeys) + a->B; }
+
+size_t general_workspace_bytes(const sp_score_args* a) {
+  size_t bytes = align_up(sizeof(int32_t) * ((size_t)a->B + 1), 256);
+  bytes += align_up(sizeof(float) * (size_t)a->L * a->B * a->N * a->H, 256);
+  bytes += align_up(sizeof(float2) * (size_t)a->L * a->N * a->H * general_max_tiles(a), 256);
+  return bytes;
+}
+
+sp_status general_score(const sp_score_args* a, hipStream_t stream) {
+  ScoreDev p;
+  fill_score_dev(a, &p);
+  p.max_tiles = general_max_tiles(a);
+  char* ws = static_cast<char*>(a->d_workspace);
+  p.tile_cu = reinterpret_cast<int32_t*>(ws);
+  ws += align_up(sizeof(int32_t) * ((size_t)a->B + 1), 256);
+  p.ws_lse = reinterpret_cast<float*>(ws);
+  ws += align_up(sizeof(float) * (size_t)a->L * a->B * a->N * a->H, 256);
+  p.part = reinterpret_cast<float2*>(ws);
+
+  hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(1024), 0, stream, p.B, p.cu, p.tile_cu);
+  const dim3 grid1(p.max_tiles, p.H_kv, p.L);
+  const int rows = p.L * p.B * p.N * p.H;
+  if (p.d == 64) {
+    hipLaunchKernelGGL(lse_partial_kernel<64>, grid1, dim3(64), 0, stream, p);
+    hipLaunchKernelGGL(lse_combine_kernel, dim3(rows), dim3(64), 0, stream, p);
+    hipLaunchKernelGGL(score_accum_kernel<64>, dim3(p.max_tiles), dim3(256), 0, stream, p);
+  } else {
+    hipLaunchKernelGGL(lse_partial_kernel<128>, grid1, dim3(64), 0, stream, p);
+    hipLaunchKernelGGL(lse_combine_kernel, dim3(rows), dim3(64), 0, stream, p);
+    hipLaunchKernelGGL(score_accum_kernel<128>, dim3(p.max_tiles), dim3(256), 0, stream, p);
+  }
+  return launch_status();
+}
+
+void fill_score_dev(const sp_score_args* a, ScoreDev* p) {
+  p->B = a->B; p->N = a->N; p->L = a->L; p->H = a->H; p->H_kv = a->H_kv; p->G = a->H / a->H_kv; p->d = a->d;
+  p->T = (int)a->T;
+  p->max_tiles = 0;
+  p->layer_reduce = a->layer_reduce;
+  p->scale = a->scale;
+  p->k_token_stride = a->k_token_stride;
+  p->k_head_stride = a->k_head_stride;
+  p->q = static_cast<const uint16_t*>(a->d_q);
+  p->cu = a->d_cu_seqlens;
+  p->n_valid = a->d_n_valid;
+  p->tile_cu = nullptr; p->ws_lse = nullptr; p->part = nullptr;
+  p->scores = a->d_scores;
+  p->lse_out = a->d_lse;
+  for (int l = 0; l < SP_MAX_LAYERS; ++l)
+    p->k[l] = l < a->L ? static_cast<const uint16_t*>(a->k_layers[l]) : nullptr;
+}
+
+}  // namespace sp
+
+extern "C" size_t sp_score_workspace_bytes(const sp_score_args* a) {
+  if (!a || !sp::shape_ok(a)) return 0;
+  size_t general = sp::general_workspace_bytes(a);
+  size_t stream = sp::stream_workspace_bytes(a);
+  return general > stream ? general : stream;
+}
+
+static sp_status check_score_args(const sp_score_args* a) {
+  if (!a) return SP_ENULL;
+  if (!sp::shape_ok(a)) return SP_EINVAL;
+  if (!a->d_q || !a->k_layers || !a->d_cu_seqlens || !a->d_scores) return SP_ENULL;
+  for (int l = 0; l < a->L; ++l)
+    if (!a->k_layers[l]) return SP_ENULL;
+  if (a->rope_theta != 0.f || a->d_q_pos != nullptr) return SP_EUNSUPPORTED;
+  if (!(a->scale == a->scale) || a->scale <= 0.f) return SP_EINVAL;
+  if (a->k_token_stride < 0 || a->k_head_stride < 0) return SP_EINVAL;
+  if ((a->k_token_stride & 7) || (a->k_head_stride & 7) || !sp::aligned16(a->d_q)) return SP_EALIGN;
+  for (int l = 0; l < a->L; ++l)
+    if (!sp::aligned16(a->k_layers[l])) return SP_EALIGN;
+  if (!a->d_workspace || a->workspace_bytes < sp_score_workspace_bytes(a)) return SP_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(a->d_workspace) & 255u) return SP_EALIGN;
+  return SP_OK;
+}
+
+extern "C" sp_status sp_score(const sp_score_args* a, void* hip_stream) {
+  const sp_status st = check_score_args(a);
+  if (st != SP_OK) return st;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (sp::stream_supported(a)) return sp::stream_score(a, stream);
+  return sp::general_score(a, stream);
+}
+
+extern "C" sp_status sp_score_general(const sp_score_args* a, void* hip_stream) {
+  const sp_status st = check_score_args(a);
+  if (st != SP_OK) return st;
+  return sp::general_score(a, static_cast<hipStream_t>(hip_stream));
+}

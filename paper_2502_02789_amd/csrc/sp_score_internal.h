@@ -1,0 +1,38 @@
+// Declarations shared by the two scoring translation units.
+#pragma once
+
+#include "sp_common.h"
+
+namespace sp {
+
+// Kernel-side view of sp_score_args (passed by value).
+struct ScoreDev {
+  int B, N, L, H, H_kv, G, d;
+  int T;
+  int max_tiles;
+  int layer_reduce;
+  float scale;
+  int64_t k_token_stride, k_head_stride;
+  const uint16_t* q;
+  const int32_t* cu;
+  const int32_t* n_valid;
+  int32_t* tile_cu;
+  float* ws_lse;
+  float2* part;
+  float* scores;
+  float* lse_out;
+  const uint16_t* k[SP_MAX_LAYERS];
+};
+
+void fill_score_dev(const sp_score_args* a, ScoreDev* p);
+
+// general two-pass kernels (sp_score.hip)
+size_t general_workspace_bytes(const sp_score_args* a);
+sp_status general_score(const sp_score_args* a, hipStream_t stream);
+
+// single-pass streaming kernel (sp_score_stream.hip)
+bool stream_supported(const sp_score_args* a);
+size_t stream_workspace_bytes(const sp_score_args* a);
+sp_status stream_score(const sp_score_args* a, hipStream_t stream);
+
+}  // namespace sp

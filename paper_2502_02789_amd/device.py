@@ -1,0 +1,99 @@
+"""Device-memory plumbing around the binding: allocate outputs and workspaces with torch,
+fill the argument structs, call the C entry points.  No arithmetic of the method happens here."""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as sp
+
+
+def bf16_from_bits(bits: np.ndarray, device="cuda") -> torch.Tensor:
+    """numpy uint16 bit patterns -> torch.bfloat16 tensor on the device (bit-exact)."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.to(device).view(torch.bfloat16)
+
+
+def bits_from_bf16(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class Scorer:
+    """Holds the argument struct, outputs and workspace of one sp_score problem."""
+
+    def __init__(self, q: torch.Tensor, k_layers: Sequence[torch.Tensor], cu_seqlens: torch.Tensor, *,
+                 H_kv: int, scale: float, layer_reduce: int = sp.SP_LAYER_MAX,
+                 n_valid: Optional[torch.Tensor] = None, want_lse: bool = False):
+        L, B, N, H, d = q.shape
+        T = int(k_layers[0].shape[0])
+        dev = q.device
+        self.q, self.k_layers, self.cu, self.n_valid = q, list(k_layers), cu_seqlens, n_valid
+        self.scores = torch.empty(T, dtype=torch.float32, device=dev)
+        self.lse = torch.empty((L, B, N, H), dtype=torch.float32, device=dev) if want_lse else None
+        probe = sp.make_score_args(q, self.k_layers, cu_seqlens, self.scores, H_kv=H_kv, scale=scale,
+                                   layer_reduce=layer_reduce, n_valid=n_valid, lse=self.lse)
+        need = sp.sp_score_workspace_bytes(probe)
+        if need == 0:
+            raise sp.SpError("sp_score_workspace_bytes", sp.SP_EINVAL)
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        self.args = sp.make_score_args(q, self.k_layers, cu_seqlens, self.scores, H_kv=H_kv, scale=scale,
+                                       layer_reduce=layer_reduce, n_valid=n_valid, lse=self.lse,
+                                       workspace=self.workspace)
+
+    def run(self, stream=None, general: bool = False) -> torch.Tensor:
+        (sp.sp_score_general if general else sp.sp_score)(self.args, stream)
+        return self.scores
+
+
+class Selector:
+    """Outputs and workspace of one sp_pool_select (+ optional sp_gather) problem."""
+
+    def __init__(self, scores: torch.Tensor, cu_seqlens: torch.Tensor, *, chunk: int, pool_window: int,
+                 keep_rate: float, capacity: Optional[int] = None, want_chunk_scores: bool = False):
+        dev = scores.device
+        T = int(scores.numel())
+        B = int(cu_seqlens.numel()) - 1
+        cap = T if capacity is None else int(capacity)
+        self.scores, self.cu = scores, cu_seqlens
+        self.kept_idx = torch.full((max(cap, 1),), -1, dtype=torch.int32, device=dev)
+        self.cu_keep = torch.zeros(B + 1, dtype=torch.int32, device=dev)
+        self.chunk_scores = (torch.zeros(T // chunk + B, dtype=torch.float32, device=dev)
+                             if want_chunk_scores else None)
+        probe = sp.make_pool_select_args(scores, cu_seqlens, self.kept_idx, self.cu_keep, chunk=chunk,
+                                         pool_window=pool_window, keep_rate=keep_rate, kept_capacity=cap)
+        need = sp.sp_pool_select_workspace_bytes(probe)
+        if need == 0:
+            raise sp.SpError("sp_pool_select_workspace_bytes", sp.SP_EINVAL)
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        self.args = sp.make_pool_select_args(scores, cu_seqlens, self.kept_idx, self.cu_keep, chunk=chunk,
+                                             pool_window=pool_window, keep_rate=keep_rate,
+                                             chunk_scores=self.chunk_scores, workspace=self.workspace,
+                                             kept_capacity=cap)
+        self.capacity = cap
+
+    def run(self, stream=None):
+        sp.sp_pool_select(self.args, stream)
+        return self.kept_idx, self.cu_keep
+
+
+class Gatherer:
+    def __init__(self, sel: Selector, *, token_ids: Optional[torch.Tensor] = None,
+                 embed: Optional[torch.Tensor] = None):
+        dev = sel.kept_idx.device
+        cap = sel.capacity
+        B = int(sel.cu.numel()) - 1
+        self.kept_pos = torch.full((max(cap, 1),), -1, dtype=torch.int32, device=dev)
+        self.kept_ids = torch.full((max(cap, 1),), -1, dtype=torch.int32, device=dev) if token_ids is not None else None
+        self.decode_pos = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.out_embed = (torch.zeros((max(cap, 1), embed.shape[1]), dtype=torch.bfloat16, device=dev)
+                          if embed is not None else None)
+        self.token_ids, self.embed = token_ids, embed
+        self.args = sp.make_gather_args(sel.cu, sel.cu_keep, sel.kept_idx, self.kept_pos, self.decode_pos,
+                                        token_ids=token_ids, kept_ids=self.kept_ids, embed=embed,
+                                        out_embed=self.out_embed, kept_capacity=cap)
+
+    def run(self, stream=None):
+        sp.sp_gather(self.args, stream)
+        return self.kept_ids, self.kept_pos, self.decode_pos, self.out_embed

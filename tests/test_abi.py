@@ -1,0 +1,64 @@
+"""The C-ABI library loads without a GPU and exports every symbol the header declares;
+argument checks that launch nothing run here too."""
+import ctypes as C
+import os
+import re
+
+from paper_2502_02789_amd import binding as sp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "specprefill.h")).read()
+    return re.findall(r"^SP_API\s+[\w\s\*]+?\b(sp_\w+)\s*\(", text, flags=re.M)
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert set(names) == set(sp.EXPORTS) and len(names) == len(sp.EXPORTS)
+    lib = C.CDLL(sp.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_layouts_match_the_header_field_order():
+    text = open(os.path.join(ROOT, "include", "specprefill.h")).read()
+    for cname, cls in (("sp_score_args", sp.ScoreArgs), ("sp_pool_select_args", sp.PoolSelectArgs),
+                       ("sp_gather_args", sp.GatherArgs)):
+        body = re.search(r"typedef struct \{([^}]*)\}\s*" + cname + ";", text).group(1)
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        fields = [re.search(r"(\w+)\s*$", decl.strip()).group(1) for decl in body.split(";") if decl.strip()]
+        assert fields == [f[0] for f in cls._fields_], cname
+
+
+def test_version_and_messages():
+    assert sp.sp_version() >= 100
+    for code in range(0, -7, -1):
+        assert sp.strerror(code) and sp.strerror(code) != "unknown status"
+    assert sp.strerror(-99) == "unknown status"
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    lib = sp.load_library()
+    assert lib.sp_score(None, None) == sp.SP_ENULL
+    assert lib.sp_score(C.byref(sp.ScoreArgs()), None) == sp.SP_EINVAL
+    assert lib.sp_score_workspace_bytes(C.byref(sp.ScoreArgs())) == 0
+    assert lib.sp_pool_select(None, None) == sp.SP_ENULL
+    assert lib.sp_pool_select(C.byref(sp.PoolSelectArgs()), None) == sp.SP_EINVAL
+    assert lib.sp_gather(None, None) == sp.SP_ENULL
+    a = sp.ScoreArgs()
+    a.B, a.N, a.L, a.H, a.H_kv, a.d, a.T = 1, 8, 32, 32, 8, 128, 32768
+    assert lib.sp_score_workspace_bytes(C.byref(a)) > 0
+    assert lib.sp_score(C.byref(a), None) == sp.SP_ENULL
+
+
+def test_keep_upper_bound_follows_the_chunk_ratio_rule():
+    assert sp.sp_keep_upper_bound([1024], 32, 0.25) == 256
+    assert sp.sp_keep_upper_bound([8192], 32, 0.1) == 26 * 32
+    assert sp.sp_keep_upper_bound([32768], 32, 0.1) == 103 * 32
+    assert sp.sp_keep_upper_bound([131072], 64, 0.05) == 103 * 64
+    assert sp.sp_keep_upper_bound([10], 1, 0.3) == 3
+    assert sp.sp_keep_upper_bound([10, 0, 5], 4, 1.0) == 15
+    assert sp.sp_keep_upper_bound([10], 0, 0.3) == -1
+    assert sp.sp_keep_upper_bound([10], 4, 0.0) == -1
