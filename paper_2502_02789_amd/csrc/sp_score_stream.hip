@@ -6,30 +6,33 @@
 //
 // Why one pass is hard: the probability of key i in row (layer, head, query) needs that row's
 // log-sum-exp over ALL keys, and the max over heads has to be taken on probabilities.  So the
-// logits of a whole layer must stay somewhere until the row statistics are known.  Here they
-// stay in registers:
+// logits must stay somewhere until the row statistics are known.  Here they stay in registers:
 //
-//   * one persistent workgroup per CU owns a fixed slice of the prompt (KPW keys) for the
-//     whole call; the work is cut into "slabs" = (layer, group of S KV heads), S chosen so
-//     that a slab's logits (KPW keys x S heads x 32 query rows, fp32) fit in the accumulator
-//     registers of the 8 waves, twice (two slabs are alive at any time);
-//   * each wave streams the K rows of its own (KV head, key blocks) through a private
-//     two-tile LDS ring with direct global->LDS loads, in an XOR-swizzled layout that makes
-//     the MFMA operand reads conflict-free, and runs v_mfma_f32_32x32x16_bf16 with the keys
-//     as matrix rows and the (query, head-in-group) pairs as columns;
-//   * per slab every workgroup publishes, for each row, (max, sum 2^(x-max)) over its keys;
-//     one designated workgroup per row folds the 256 partials into the row's log-sum-exp and
-//     publishes it; these two hops overlap with the next slab's streaming (the exchange for
-//     slab s-1 happens while slab s is being computed, which is why two logit sets are kept);
-//   * with the row's log-sum-exp known, a slab's logits become log-probabilities; the max over
-//     the heads of a KV group is a quad DPP max, the max over KV heads / layers an LDS float
-//     atomic max per (query, key); the mean over layers (if asked) and queries is taken at the
+//   * one persistent workgroup per CU owns a fixed slice of the prompt (KPW keys) for the whole
+//     call; the work is cut into "slabs" = (layer, group of S KV heads).  A slab's logits are
+//     TPW accumulator tiles (32 keys x 32 query rows, fp32) per wave; the register file holds
+//     NSETS = 8 / TPW slabs at once, so a slab's logits survive NSETS-1 further slabs of
+//     streaming -- the window in which the cross-workgroup exchange below has to finish;
+//   * every wave streams its own sequence of 32-row tiles through a private two-slot LDS ring
+//     with direct global->LDS loads: per slab one tile of query rows (its KV head's 32
+//     (query, head-in-group) rows) followed by TPW tiles of keys.  Tiles are stored with an
+//     XOR swizzle that makes the MFMA operand reads bank-conflict free; the MFMA is
+//     v_mfma_f32_32x32x16_bf16 with keys as matrix rows and query rows as columns.  All vector
+//     memory traffic of the steady state is these fixed-size load groups, which is what lets a
+//     constant "s_waitcnt vmcnt(LOADS)" stand for "the older tile has landed";
+//   * per slab every wave publishes, for each of its rows, (max, sum 2^(x-max)) over its keys;
+//     a designated workgroup per group of 8 rows folds all partials into the rows' log-sum-exp
+//     and publishes them; one wave per workgroup (rotating) fetches a slab's log-sum-exps into
+//     an LDS mailbox for the other waves;
+//   * with the log-sum-exp known a slab's logits become log2-probabilities; the max over the
+//     heads of a KV group is a quad DPP max, the max over KV heads / layers an LDS float
+//     atomic max per (query, key); the layer mean (if asked) and the query mean are taken at
 //     layer end / kernel end.
 //
-// Cross-workgroup exchange uses 64-bit (max,sum) words and 32-bit log-sum-exp words that are
-// "empty" (all ones) until written, written and polled with agent-scope atomics; the
-// workspace is re-filled with the empty pattern by a small kernel at the start of each call.
-// Every wait is bounded; the launch is cooperative so all workgroups are co-resident.
+// Cross-workgroup words are "empty" (all ones) until written, and are written and polled with
+// agent-scope atomics; a small kernel refills the workspace with the empty pattern at the
+// start of each call.  Every wait is bounded (a status word records an expired wait) and the
+// launch is cooperative, so all workgroups are co-resident and every wait ends.
 #include "sp_score_internal.h"
 
 namespace sp {
@@ -43,14 +46,15 @@ constexpr int kMaxWG = 256;
 constexpr uint64_t kEmpty64 = ~0ull;
 constexpr uint32_t kEmpty32 = ~0u;
 constexpr int kSpinBudget = 1 << 22;  // polls per wave over the whole call before giving up
+constexpr int kMailSlotsMax = 16;
 
 struct StreamDev {
-  int M, L, N, H, G, S, slabs_per_layer, n_slabs, KPW, nwg, wpr, layer_reduce;
+  int M, L, N, H, G, lgG, S, slabs_per_layer, n_slabs, KPW, nwg, wpr, layer_reduce;
   float c;  // scale * log2(e): logits are handled in the base-2 domain
   int64_t ts, hs;
   const uint16_t* q;
   const int32_t* n_valid;
-  uint64_t* partial;  // [rows][nwg][wpr]
+  uint64_t* partial;  // [row / 8][nwg * wpr][row % 8]
   uint32_t* lse2;     // [rows]
   uint32_t* status;   // [0] != 0: a bounded wait ran out (results invalid)
   float* scores;
@@ -91,40 +95,68 @@ __device__ __forceinline__ uint32_t poll32(const uint32_t* p, int& budget) {
   return v;
 }
 
-__device__ __forceinline__ float quad_xor1(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
+// A 32-bit LDS read the compiler does not see as one.  The mailbox words read this way are never
+// the target of a direct-to-LDS tile load, so there is no reason to wait for the tile loads in
+// flight before reading them -- which an ordinary LDS read would be made to do.
+__device__ __forceinline__ uint32_t lds_peek(uint32_t lds_addr) {
+  uint32_t v;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
+  return v;
 }
-__device__ __forceinline__ float quad_xor2(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));
+
+// LDS float atomic max at lds_addr + OFF, likewise invisible to the compiler's bookkeeping
+template <int OFF>
+__device__ __forceinline__ void lds_fmax(uint32_t lds_addr, float v) {
+  asm volatile("ds_max_f32 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
+}
+// register i of a 32x32 accumulator tile holds key (i / 4) * 8 + (i % 4) (+ 4 for the upper half-wave)
+template <int... I>
+__device__ __forceinline__ void lds_fmax_tile(uint32_t lds_addr, const float (&x)[16], std::integer_sequence<int, I...>) {
+  (lds_fmax<((I >> 2) * 8 + (I & 3)) * 4>(lds_addr, x[I]), ...);
+}
+
+// max with the value of lane ^ 1 / lane ^ 2 (inside the quad)
+__device__ __forceinline__ float max_quad_xor1(float v) {
+  return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true)));
+}
+__device__ __forceinline__ float max_quad_xor2(float v) {
+  return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true)));
 }
 
 template <int D, int TPW>
 struct Streamer {
-  static constexpr int KS = D / 16;          // MFMA k-steps per tile
-  static constexpr int ROW_B = D * 2;        // bytes of one (token, KV head) row
-  static constexpr int TILE_B = 32 * ROW_B;  // one 32-key tile of one KV head
-  static constexpr int UNITS = ROW_B / 16;   // 16-byte units per row
+  static constexpr int NSETS = 8 / TPW;        // slabs of logits alive in registers
+  static constexpr int TPS = TPW + 1;          // stream tiles per slab: query tile + key tiles
+  static constexpr int KS = D / 16;            // MFMA k-steps per tile
+  static constexpr int ROW_B = D * 2;          // bytes of one row (one key / one query row)
+  static constexpr int TILE_B = 32 * ROW_B;    // 32 rows
+  static constexpr int UNITS = ROW_B / 16;     // 16-byte units per row
   static constexpr int LOADS = TILE_B / 1024;  // wave-wide 16-byte loads per tile
-  static constexpr int RPI = 64 / UNITS;     // rows covered by one such load
+  static constexpr int RPI = 64 / UNITS;       // rows covered by one such load
+  static constexpr int FIN_LAG = NSETS - 1;    // slab s is finished while slab s + FIN_LAG streams
+  static constexpr int RED_LAG = NSETS >= 4 ? NSETS / 2 : 1;  // slab s is reduced while slab s + RED_LAG streams
+  static constexpr int RED_KB = NSETS >= 4 ? 0 : (TPW >= 2 ? TPW / 2 - 1 : 0);
+  static constexpr int MAIL_SLOTS = 2 * NSETS;
 
   const StreamDev& p;
   float* smax;           // [N][KPW] running max of log2-probabilities
+  float* mail;           // [MAIL_SLOTS][S*32] log-sum-exps fetched for the workgroup
+  int* mail_flag;        // [MAIL_SLOTS] slab + 1 whose values the slot holds
   int wave, lane, half, col, wg;
   int kvh_local, kbg;
   int keys_wg;           // valid keys owned by this workgroup
-  int n_tiles;           // tiles this wave streams over the whole call
   int budget;
-  uint32_t ring_lds;     // LDS byte address of this wave's two-tile ring
-  uint32_t rd0;          // LDS byte address of this lane's operand unit for k-step 0 in buffer 0
-  uint32_t ld_off[4];    // per-lane global byte offset of load j (depends on j & 3 only)
+  uint32_t ring_lds;     // LDS byte address of this wave's two-slot ring
+  uint32_t rd0;          // LDS byte address of this lane's operand unit for k-step 0 in slot 0
+  uint32_t ld_off[4];    // per-lane global byte offset of key load j (depends on j & 3 only)
   bf16x8 qf[KS];
-  f32x16 acc[2][TPW];
+  f32x16 acc[NSETS][TPW];
   float run_m, run_s;    // running (max of raw logits, sum of 2^((x-max)*c)) of this lane's row
 
-  // LDS layout of a tile: row r (one key) at r*ROW_B; inside a row the 16-byte unit holding
-  // head-dim elements [8u, 8u+8) sits at position u ^ key(r), key(r) = r & 15 (D=128) or
-  // (r >> 1) & 7 (D=64).  With it the 16 lanes of an operand read hit 16 distinct bank groups,
-  // and a wave-wide direct load still fills 1 KiB of consecutive LDS.
+  // LDS layout of a tile: row r at r*ROW_B; inside a row the 16-byte unit holding head-dim
+  // elements [8u, 8u+8) sits at position u ^ key(r), key(r) = r & 15 (D=128) or (r >> 1) & 7
+  // (D=64).  With it the 16 lanes of an operand read hit 16 distinct bank groups, and a
+  // wave-wide direct load still fills 1 KiB of consecutive LDS.
   __device__ __forceinline__ Streamer(const StreamDev& p_, unsigned char* smem) : p(p_) {
     wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     lane = threadIdx.x & 63;
@@ -135,8 +167,9 @@ struct Streamer {
     kbg = wave / p.S;
     ring_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem) + wave * 2 * TILE_B;
     smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B);
+    mail = smax + p.N * p.KPW;
+    mail_flag = reinterpret_cast<int*>(mail + MAIL_SLOTS * p.S * 32);
     keys_wg = max(0, min(p.KPW, p.M - wg * p.KPW));
-    n_tiles = p.n_slabs * TPW;
     budget = kSpinBudget;
     // operand read: unit (2t + half) of row col lives at position (2t + half) ^ key(col)
     //             = 2 * (t ^ (key >> 1)) + (half ^ (key & 1)), so the address is rd0 ^ (t << 5)
@@ -155,22 +188,26 @@ struct Streamer {
   __device__ __forceinline__ static __attribute__((address_space(3))) void* lds_ptr(uint32_t addr) {
     return reinterpret_cast<__attribute__((address_space(3))) void*>(addr);
   }
+  __device__ __forceinline__ static uint32_t lds_addr_of(const void* generic) {
+    return (uint32_t)reinterpret_cast<uintptr_t>(generic);
+  }
 
-  // direct global->LDS load of tile f (flattened slab*TPW + kb) into ring buffer `buf`.
-  // Always issues exactly LOADS wave-wide loads (the vmcnt bookkeeping counts on it): rows
-  // beyond the prompt re-read row 0 of the last in-range tile and are masked later.
-  __device__ __forceinline__ void issue_tile(int f, int buf) {
-    const int slab = f / TPW, kb = f % TPW;
-    const int l = slab / p.slabs_per_layer;
-    const int kvh = (slab % p.slabs_per_layer) * p.S + kvh_local;
+  __device__ __forceinline__ int layer_of(int slab) const { return slab / p.slabs_per_layer; }
+  __device__ __forceinline__ int kvh_of(int slab) const { return (slab % p.slabs_per_layer) * p.S + kvh_local; }
+  __device__ __forceinline__ int row_base(int slab) const { return (slab * p.S + kvh_local) * 32; }
+
+  // Direct global->LDS load of one key tile into ring slot `slot`.  Always exactly LOADS
+  // wave-wide loads (the vmcnt bookkeeping counts on it): rows beyond the prompt re-read row 0
+  // of the last in-range tile and are masked later.
+  __device__ __forceinline__ void issue_keys(int slab, int kb, int slot) {
     int key_start = wg * p.KPW + (kbg * TPW + kb) * 32;
-    // keep the address arithmetic below at its point of use: hoisted out of the slab loop it
-    // would pin dozens of registers for the whole kernel
+    // keep the address arithmetic at its point of use: hoisted out of the slab loop it would
+    // pin dozens of registers for the whole kernel
     asm volatile("" : "+s"(key_start));
-    const uint32_t dst = ring_lds + buf * TILE_B;
+    const uint32_t dst = ring_lds + slot * TILE_B;
     const int start_eff = min(key_start, (p.M - 1) & ~31);
-    const unsigned char* base = reinterpret_cast<const unsigned char*>(p.k[l]) +
-                                2 * ((int64_t)kvh * p.hs + (int64_t)start_eff * p.ts);
+    const unsigned char* base = reinterpret_cast<const unsigned char*>(p.k[layer_of(slab)]) +
+                                2 * ((int64_t)kvh_of(slab) * p.hs + (int64_t)start_eff * p.ts);
     if (start_eff + 32 <= p.M) {  // whole tile inside the prompt
 #pragma unroll
       for (int j = 0; j < LOADS; ++j) {
@@ -190,32 +227,55 @@ struct Streamer {
     }
   }
 
-  // query fragments of this wave's KV head for slab `slab` (B operand: column = query row)
-  __device__ __forceinline__ void load_q(int slab) {
-    const int l = slab / p.slabs_per_layer;
-    const int kvh = (slab % p.slabs_per_layer) * p.S + kvh_local;
-    const bool real = col < p.G * p.N;
-    const int n = col / p.G, g = col % p.G;
-    const uint16_t* row = p.q + (((int64_t)l * p.N + (real ? n : 0)) * p.H + kvh * p.G + (real ? g : 0)) * D +
-                          half * 8;
+  // Direct global->LDS load of the slab's query tile: row r = n*G + g holds Q[layer, n, kvh*G + g, :]
+  // (rows beyond G*N repeat row 0; their columns of the logit tiles are never used).
+  __device__ __forceinline__ void issue_queries(int slab, int slot) {
+    int rows = p.G * p.N;
+    asm volatile("" : "+s"(rows));
+    const uint32_t dst = ring_lds + slot * TILE_B;
+    const unsigned char* base = reinterpret_cast<const unsigned char*>(p.q) +
+                                2 * (((int64_t)layer_of(slab) * p.N * p.H + kvh_of(slab) * p.G) * D);
+    const int i = lane / UNITS;
 #pragma unroll
-    for (int t = 0; t < KS; ++t) {
-      bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (real) v = *reinterpret_cast<const bf16x8*>(row + t * 16);
-      qf[t] = v;
+    for (int j = 0; j < LOADS; ++j) {
+      const int r = j * RPI + i;
+      const int key = (D == 128) ? (r & 15) : ((r >> 1) & 7);
+      const int unit = (lane % UNITS) ^ key;
+      const int rr = r < rows ? r : 0;
+      const uint32_t off = (uint32_t)((rr >> p.lgG) * p.H * ROW_B + (rr & (p.G - 1)) * ROW_B + unit * 16);
+      __builtin_amdgcn_global_load_lds(base + off, lds_ptr(dst + j * 1024), 16, 0, 0);
     }
   }
 
-  template <int CUR>
-  __device__ __forceinline__ void mfma_tile(int kb, int buf) {
+  // issue stream tile number IDX counted from the start of slab `slab` (0 = its queries,
+  // 1..TPW = its keys, TPW+1 = the next slab's queries, ...); past the end of the call the
+  // last slab is read again (nobody consumes it)
+  template <int IDX>
+  __device__ __forceinline__ void issue_stream(int slab, int slot) {
+    constexpr int ADV = IDX / TPS, I = IDX % TPS;
+    // the slot is about to be overwritten: every LDS read of its previous tile must have been
+    // performed (a freshly issued read could otherwise lose the race against an L2-hit load)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    const int s = min(slab + ADV, p.n_slabs - 1);
+    if (I == 0) issue_queries(s, slot); else issue_keys(s, I - 1, slot);
+  }
+
+  __device__ __forceinline__ bf16x8 read_unit(int t, int slot) const {
+    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+        lds_ptr((rd0 ^ (uint32_t)(t << 5)) + slot * TILE_B));
+  }
+
+  __device__ __forceinline__ void read_queries(int slot) {
+#pragma unroll
+    for (int t = 0; t < KS; ++t) qf[t] = read_unit(t, slot);
+  }
+
+  template <int SET>
+  __device__ __forceinline__ void mfma_tile(int kb, int slot) {
     f32x16 a = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-    for (int t = 0; t < KS; ++t) {
-      const bf16x8 kfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-          lds_ptr((rd0 ^ (uint32_t)(t << 5)) + buf * TILE_B));
-      a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[t], a, 0, 0, 0);
-    }
-    acc[CUR][kb] = a;
+    for (int t = 0; t < KS; ++t) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_unit(t, slot), qf[t], a, 0, 0, 0);
+    acc[SET][kb] = a;
   }
 
   // key (within the workgroup's slice) held by accumulator register i of tile kb in this lane
@@ -223,9 +283,9 @@ struct Streamer {
     return (kbg * TPW + kb) * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
   }
 
-  template <int CUR>
+  template <int SET>
   __device__ __forceinline__ void stats_tile(int kb) {
-    f32x16& a = acc[CUR][kb];
+    f32x16& a = acc[SET][kb];
     const int first = (kbg * TPW + kb) * 32;
     if (first + 32 > keys_wg) {  // ragged tail: keys beyond the prompt do not count
 #pragma unroll
@@ -245,9 +305,8 @@ struct Streamer {
     run_s = s;
   }
 
-  __device__ __forceinline__ int row_base(int slab) const { return (slab * p.S + kvh_local) * 32; }
-
-  // publish this wave's (max, sum) of every row of the slab over the keys it has seen
+  // publish this wave's (max, sum) of every row of the slab over the keys it has seen;
+  // 8 consecutive rows of one (workgroup, wave) form one 64-byte chunk
   __device__ __forceinline__ void publish(int slab) {
     const float m_o = __shfl_xor(run_m, 32, kWave);
     const float s_o = __shfl_xor(run_s, 32, kWave);
@@ -256,68 +315,96 @@ struct Streamer {
     const float ss = run_s * fast_exp2((run_m - ref) * p.c) + s_o * fast_exp2((m_o - ref) * p.c);
     if (half == 0) {
       const uint64_t word = ((uint64_t)__float_as_uint(ss) << 32) | __float_as_uint(mm);
-      uint64_t* dst = p.partial + ((int64_t)(row_base(slab) + col) * p.nwg + wg) * p.wpr + kbg;
+      const int row = row_base(slab) + col;
+      const int entries = p.nwg * p.wpr;
+      uint64_t* dst = p.partial + ((int64_t)(row >> 3) * entries + wg * p.wpr + kbg) * 8 + (row & 7);
       __hip_atomic_store(dst, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 
-  // fold all workgroups' partials of the rows this workgroup is responsible for (one wave)
+  // If this workgroup is responsible for a group of 8 rows of the slab, fold all workgroups'
+  // partials of those rows (one row per wave) into the rows' log-sum-exp and publish them.
   __device__ __forceinline__ void reduce_rows(int slab) {
-    const int rows = p.S * 32;
-    const int base = slab * rows;
-    const int per_row = p.nwg * p.wpr;
-    int first = base + ((wg - base) % p.nwg + p.nwg) % p.nwg;
-    for (int row = first; row < base + rows; row += p.nwg) {
-      const uint64_t* src = p.partial + (int64_t)row * per_row;
-      float m = -INFINITY, s = 0.f;
-      for (int e = lane; e < per_row; e += kWave) {
-        const uint64_t w = poll64(src + e, budget);
-        const float pm = __uint_as_float((uint32_t)w), ps = __uint_as_float((uint32_t)(w >> 32));
-        const float mn = fmaxf(m, pm);
-        const float ref = (mn == -INFINITY) ? 0.f : mn;
-        s = s * fast_exp2((m - ref) * p.c) + ps * fast_exp2((pm - ref) * p.c);
-        m = mn;
-      }
-      const float mw = wave_max(m);
-      const float zw = wave_sum(s * fast_exp2((m - mw) * p.c));  // mw is finite: the prompt is not empty
-      if (lane == 0) {
-        const float lse2 = fmaf(mw, p.c, __builtin_amdgcn_logf(zw));  // v_log_f32 is log2
-        __hip_atomic_store(p.lse2 + row, __float_as_uint(lse2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (p.lse_out) {
-          const int in_slab = row - base;
-          const int qrow = in_slab & 31;
-          if (qrow < p.G * p.N) {
-            const int l = slab / p.slabs_per_layer;
-            const int kvh = (slab % p.slabs_per_layer) * p.S + (in_slab >> 5);
-            const int n = qrow / p.G, g = qrow % p.G;
-            p.lse_out[((int64_t)l * p.N + n) * p.H + kvh * p.G + g] = lse2 * 0.6931471805599453f;
-          }
+    const int groups = p.S * 4;  // row groups per slab
+    const int base = slab * groups;
+    const int rg = base + ((wg - base) % p.nwg + p.nwg) % p.nwg;
+    if (rg >= base + groups) return;
+    const int entries = p.nwg * p.wpr;
+    const int row = rg * 8 + wave;
+    const uint64_t* src = p.partial + (int64_t)rg * entries * 8 + wave;
+    float m = -INFINITY, s = 0.f;
+    for (int e = lane; e < entries; e += kWave) {
+      const uint64_t w = poll64(src + (int64_t)e * 8, budget);
+      const float pm = __uint_as_float((uint32_t)w), ps = __uint_as_float((uint32_t)(w >> 32));
+      const float mn = fmaxf(m, pm);
+      const float ref = (mn == -INFINITY) ? 0.f : mn;
+      s = s * fast_exp2((m - ref) * p.c) + ps * fast_exp2((pm - ref) * p.c);
+      m = mn;
+    }
+    const float mw = wave_max(m);  // finite: the prompt is not empty
+    const float zw = wave_sum(s * fast_exp2((m - mw) * p.c));
+    if (lane == 0) {
+      const float lse2 = fmaf(mw, p.c, __builtin_amdgcn_logf(zw));  // v_log_f32 is log2
+      __hip_atomic_store(p.lse2 + row, __float_as_uint(lse2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (p.lse_out) {
+        const int in_slab = row - slab * p.S * 32;
+        const int qrow = in_slab & 31;
+        if (qrow < p.G * p.N) {
+          const int kvh = (slab % p.slabs_per_layer) * p.S + (in_slab >> 5);
+          p.lse_out[((int64_t)layer_of(slab) * p.N + (qrow >> p.lgG)) * p.H + kvh * p.G + (qrow & (p.G - 1))] =
+              lse2 * 0.6931471805599453f;
         }
       }
     }
   }
 
-  // turn the stored logits of slab `slab` (set PREV) into log2-probabilities and max them
-  // into smax over the heads of the KV group (cross-lane) and over KV heads / layers (LDS)
-  template <int PREV>
+  // one wave fetches the slab's log-sum-exps (S*32 words) into the LDS mailbox
+  __device__ __forceinline__ void fetch_lse(int slab) {
+    const int words = p.S * 32;
+    const int slot = slab % MAIL_SLOTS;
+    for (int i = lane; i < words; i += kWave) {
+      const uint32_t bits = poll32(p.lse2 + (int64_t)slab * words + i, budget);
+      mail[slot * words + i] = __uint_as_float(bits);
+    }
+    // LDS operations of one wave complete in order: once the value writes are done the flag may
+    // go (no memory fence here: it would also wait for the tile loads in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (lane == 0) __hip_atomic_store(mail_flag + slot, slab + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+
+  // Turn the stored logits of slab `slab` (set SET) into log2-probabilities and max them into
+  // smax: over the heads of the KV group across lanes, over KV heads / layers in LDS.
+  template <int SET>
   __device__ __forceinline__ void finish_slab(int slab) {
-    const uint32_t bits = poll32(p.lse2 + row_base(slab) + col, budget);
-    const float neg_lse = -__uint_as_float(bits);
-    const bool real = col < p.G * p.N;
-    const int n = col / p.G, g = col % p.G;
-    float* dst_row = smax + n * p.KPW;
+    const int slot = slab % MAIL_SLOTS;
+    const uint32_t flag_addr = lds_addr_of(mail_flag + slot);
+    while ((int)lds_peek(flag_addr) != slab + 1 && budget > 0) {
+      __builtin_amdgcn_s_sleep(1);
+      --budget;
+    }
+    // the value is read after the flag: same wave, same in-order LDS queue
+    const float neg_lse = -__uint_as_float(lds_peek(lds_addr_of(mail + slot * p.S * 32 + kvh_local * 32 + col)));
+    const bool writer = col < p.G * p.N && (col & (p.G - 1)) == 0;
+    // LDS address of this lane's first key of tile 0 in its query's row of smax
+    const uint32_t dst0 = lds_addr_of(smax + (col >> p.lgG) * p.KPW + kbg * TPW * 32 + half * 4);
 #pragma unroll
     for (int kb = 0; kb < TPW; ++kb) {
+      float x[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        float x = real ? fmaf(acc[PREV][kb][i], p.c, neg_lse) : -INFINITY;
-        if (p.G >= 2) x = fmaxf(x, quad_xor1(x));
-        if (p.G >= 4) x = fmaxf(x, quad_xor2(x));
-        if (p.G >= 8) x = fmaxf(x, __shfl_xor(x, 4, kWave));
-        const int key = key_of(kb, i);
-        if (real && g == 0 && key < keys_wg)
-          __hip_atomic_fetch_max(dst_row + key, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        float v = fmaf(acc[SET][kb][i], p.c, neg_lse);
+        if (p.G >= 2) v = max_quad_xor1(v);
+        if (p.G >= 4) v = max_quad_xor2(v);
+        if (p.G >= 8) v = fmaxf(v, __shfl_xor(v, 4, kWave));
+        x[i] = v;
       }
+      const int first = (kbg * TPW + kb) * 32;
+      if (first + 32 > keys_wg) {  // ragged tail: keys beyond the prompt never beat the -inf start value
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (key_of(kb, i) >= keys_wg) x[i] = -INFINITY;
+      }
+      if (writer) lds_fmax_tile(dst0 + kb * 128, x, std::make_integer_sequence<int, 16>{});
     }
   }
 };
@@ -326,59 +413,109 @@ template <int D, int TPW>
 __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev p) {
   extern __shared__ __align__(1024) unsigned char smem[];
   using St = Streamer<D, TPW>;
+  constexpr int NSETS = St::NSETS, TPS = St::TPS;
   St st(p, smem);
   const int cells = p.N * p.KPW;  // (query, key) cells of this workgroup
   float tot[8];                   // layer-mean mode: sum over layers, cell = threadIdx + 512*j
 #pragma unroll
   for (int j = 0; j < 8; ++j) tot[j] = 0.f;
   for (int i = threadIdx.x; i < cells; i += kThreads) st.smax[i] = -INFINITY;
+  if (threadIdx.x < kMailSlotsMax) st.mail_flag[threadIdx.x] = 0;
   __syncthreads();
 
-  st.load_q(0);
-  st.issue_tile(0, 0);
-  if (st.n_tiles > 1) st.issue_tile(1, 1);
+  // layer-mean mode: slab `done` was just finished by this wave; if it closes a layer (other
+  // than the last), fold the layer's maxima into the running sums.  Needs every wave's
+  // contribution, hence the workgroup barriers; the condition is the same in every wave.
+  auto close_layer = [&](int done) {
+    if (p.layer_reduce == SP_LAYER_MEAN && (done + 1) % p.slabs_per_layer == 0 && done + 1 < p.n_slabs) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int cell = threadIdx.x + kThreads * j;
+        if (cell < cells) {
+          tot[j] += fast_exp2(__uint_as_float(lds_peek(St::lds_addr_of(st.smax + cell))));
+          st.smax[cell] = -INFINITY;
+        }
+      }
+      __syncthreads();
+    }
+  };
 
-  auto body = [&](auto cur_tag, int slab) {
-    constexpr int CUR = decltype(cur_tag)::value;
+  st.template issue_stream<0>(0, 0);
+  st.template issue_stream<1>(0, 1);
+
+  // One slab: read its query fragments, stream its TPW key tiles (MFMA + row statistics),
+  // publish the statistics; in between serve the exchange of older slabs; at the end turn the
+  // slab that is FIN_LAG behind into probabilities.  Stream tile x of the slab sits in ring
+  // slot (SET*TPS + x) & 1 (NSETS is even, so the slab's parity is SET's).
+  auto body = [&](auto set_tag, int slab) {
+    constexpr int SET = decltype(set_tag)::value;
+    constexpr int SLOT0 = (SET * TPS) & 1;
+    // before every use of a stream tile: the LOADS loads of the one younger tile are the only
+    // ones that may still be in flight
+    wait_vmcnt<St::LOADS>();
+    st.read_queries(SLOT0);
+    st.template issue_stream<2>(slab, SLOT0);
     st.run_m = -INFINITY;
     st.run_s = 0.f;
 #pragma unroll
     for (int kb = 0; kb < TPW; ++kb) {
-      const int f = slab * TPW + kb;
-      if (f + 1 < st.n_tiles) wait_vmcnt<St::LOADS>(); else wait_vmcnt<0>();
-      st.template mfma_tile<CUR>(kb, f & 1);
-      if (kb == TPW - 1 && slab + 1 < p.n_slabs) st.load_q(slab + 1);  // next slab's queries, behind this slab's MFMAs
-      if (f + 2 < st.n_tiles) st.issue_tile(f + 2, f & 1);
-      if (kb == (TPW >= 2 ? TPW / 2 - 1 : 0) && slab >= 1 && st.wave == ((slab - 1) & 7)) st.reduce_rows(slab - 1);
-      st.template stats_tile<CUR>(kb);
+      const int slot = (SLOT0 + 1 + kb) & 1;
+      wait_vmcnt<St::LOADS>();
+      st.template mfma_tile<SET>(kb, slot);
+      switch (kb) {  // a compile-time constant after unrolling
+        case 0: st.template issue_stream<3>(slab, slot); break;
+        case 1: st.template issue_stream<4>(slab, slot); break;
+        case 2: st.template issue_stream<5>(slab, slot); break;
+        default: st.template issue_stream<6>(slab, slot); break;
+      }
+      if (kb == St::RED_KB && slab >= St::RED_LAG) st.reduce_rows(slab - St::RED_LAG);
+      if (kb == TPW - 1 && slab >= St::FIN_LAG && st.wave == ((slab - St::FIN_LAG) & 7))
+        st.fetch_lse(slab - St::FIN_LAG);
+      st.template stats_tile<SET>(kb);
     }
     st.publish(slab);
-    if (slab >= 1) {
-      st.template finish_slab<1 - CUR>(slab - 1);
-      if (p.layer_reduce == SP_LAYER_MEAN && slab % p.slabs_per_layer == 0) {  // slab-1 closed a layer
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int cell = threadIdx.x + kThreads * j;
-          if (cell < cells) {
-            const float v = st.smax[cell];
-            tot[j] += fast_exp2(v);
-            st.smax[cell] = -INFINITY;
-          }
-        }
-        __syncthreads();
-      }
+    if (slab >= St::FIN_LAG) {
+      st.template finish_slab<(SET + 1) % NSETS>(slab - St::FIN_LAG);
+      close_layer(slab - St::FIN_LAG);
     }
   };
 
-  for (int slab = 0; slab < p.n_slabs; slab += 2) {
-    body(std::integral_constant<int, 0>{}, slab);
-    if (slab + 1 < p.n_slabs) body(std::integral_constant<int, 1>{}, slab + 1);
+  for (int s0 = 0; s0 < p.n_slabs; s0 += NSETS) {
+    body(std::integral_constant<int, 0>{}, s0);
+    if (s0 + 1 < p.n_slabs) body(std::integral_constant<int, 1>{}, s0 + 1);
+    if (NSETS > 2) {
+      if (s0 + 2 < p.n_slabs) body(std::integral_constant<int, 2 % NSETS>{}, s0 + 2);
+      if (s0 + 3 < p.n_slabs) body(std::integral_constant<int, 3 % NSETS>{}, s0 + 3);
+    }
+    if (NSETS > 4) {
+      if (s0 + 4 < p.n_slabs) body(std::integral_constant<int, 4 % NSETS>{}, s0 + 4);
+      if (s0 + 5 < p.n_slabs) body(std::integral_constant<int, 5 % NSETS>{}, s0 + 5);
+      if (s0 + 6 < p.n_slabs) body(std::integral_constant<int, 6 % NSETS>{}, s0 + 6);
+      if (s0 + 7 < p.n_slabs) body(std::integral_constant<int, 7 % NSETS>{}, s0 + 7);
+    }
   }
-  // last slab: the exchange cannot hide behind further streaming
-  const int last = p.n_slabs - 1;
-  if (st.wave == (last & 7)) st.reduce_rows(last);
-  if (last & 1) st.template finish_slab<1>(last); else st.template finish_slab<0>(last);
+
+  // drain: the exchange of the last slabs cannot hide behind further streaming
+  wait_vmcnt<0>();
+  for (int s = max(0, p.n_slabs - St::RED_LAG); s < p.n_slabs; ++s) st.reduce_rows(s);
+  for (int s = max(0, p.n_slabs - St::FIN_LAG); s < p.n_slabs; ++s)
+    if (st.wave == (s & 7)) st.fetch_lse(s);
+  for (int s = max(0, p.n_slabs - St::FIN_LAG); s < p.n_slabs; ++s) {
+    switch (s % NSETS) {
+      case 0: st.template finish_slab<0>(s); break;
+      case 1: st.template finish_slab<1 % NSETS>(s); break;
+      case 2: st.template finish_slab<2 % NSETS>(s); break;
+      case 3: st.template finish_slab<3 % NSETS>(s); break;
+      case 4: st.template finish_slab<4 % NSETS>(s); break;
+      case 5: st.template finish_slab<5 % NSETS>(s); break;
+      case 6: st.template finish_slab<6 % NSETS>(s); break;
+      default: st.template finish_slab<7 % NSETS>(s); break;
+    }
+    close_layer(s);
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
   __syncthreads();
 
   int nv = p.n_valid ? p.n_valid[0] : p.N;
@@ -425,6 +562,10 @@ static int device_cu_count() {
   return cached;
 }
 
+#ifndef SP_STREAM_TPW_PREF
+#define SP_STREAM_TPW_PREF 2  // preferred key tiles per wave per slab (smaller = longer exchange window)
+#endif
+
 static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   StreamPlan pl{};
   pl.ok = false;
@@ -433,20 +574,30 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   if (G != 1 && G != 2 && G != 4 && G != 8) return pl;
   if (G * a->N > 32 || a->N > 8) return pl;
   nwg = std::min(nwg, kMaxWG);
-  int kb = (int)((a->T + (int64_t)nwg * 32 - 1) / ((int64_t)nwg * 32));
+  const int kb = (int)((a->T + (int64_t)nwg * 32 - 1) / ((int64_t)nwg * 32));
   int kb2 = 1;
   while (kb2 < kb) kb2 <<= 1;
   if (kb2 > 16) return pl;  // beyond 16 key blocks per workgroup the slabs no longer fit
+  // S * kb2 = 8 * TPW with S in {2,4,8} (S = 1 would need 8 partial words per row and
+  // workgroup) and TPW in {1,2,4}: start from the preferred TPW and move it into range
+  int tpw = SP_STREAM_TPW_PREF;
+  while (tpw < 4 && 8 * tpw / kb2 < 2) tpw <<= 1;
+  while (tpw > 1 && 8 * tpw / kb2 > 8) tpw >>= 1;
+  const int S = 8 * tpw / kb2;
+  if (S < 1 || S > 8 || S * kb2 != 8 * tpw) return pl;
   pl.nwg = nwg;
   pl.KPW = kb2 * 32;
-  if (kb2 <= 4) { pl.S = 8; pl.TPW = kb2; } else { pl.S = 32 / kb2; pl.TPW = 4; }
+  pl.TPW = tpw;
+  pl.S = S;
   pl.wpr = kWaves / pl.S;
   pl.slabs_per_layer = a->H_kv / pl.S;
   pl.n_slabs = a->L * pl.slabs_per_layer;
   pl.rows = (size_t)a->L * a->H_kv * 32;
   pl.partial_bytes = align_up(pl.rows * nwg * pl.wpr * sizeof(uint64_t), 256);
   pl.lse_bytes = align_up(pl.rows * sizeof(uint32_t), 256);
-  pl.smem_bytes = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)a->N * pl.KPW * sizeof(float);
+  const size_t mail_floats = (size_t)2 * (8 / tpw) * S * 32;
+  pl.smem_bytes = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)a->N * pl.KPW * sizeof(float) +
+                  mail_floats * sizeof(float) + kMailSlotsMax * sizeof(int);
   if (pl.smem_bytes > 160 * 1024) return pl;
   if ((size_t)a->N * pl.KPW > 8 * kThreads) return pl;
   pl.ok = true;
@@ -480,6 +631,7 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   if (!pl.ok) return SP_EUNSUPPORTED;
   StreamDev dev;
   dev.M = (int)a->T; dev.L = a->L; dev.N = a->N; dev.H = a->H; dev.G = a->H / a->H_kv; dev.S = pl.S;
+  dev.lgG = dev.G == 1 ? 0 : dev.G == 2 ? 1 : dev.G == 4 ? 2 : 3;
   dev.slabs_per_layer = pl.slabs_per_layer; dev.n_slabs = pl.n_slabs; dev.KPW = pl.KPW; dev.nwg = pl.nwg;
   dev.wpr = pl.wpr; dev.layer_reduce = a->layer_reduce;
   dev.c = a->scale * 1.4426950408889634f;
