@@ -44,7 +44,8 @@ typedef enum {
   SP_EALIGN = -3,       /* a pointer or stride breaks the 16-byte alignment rule */
   SP_EWORKSPACE = -4,   /* workspace missing or smaller than *_workspace_bytes   */
   SP_EUNSUPPORTED = -5, /* valid request this build has no kernel for            */
-  SP_ELAUNCH = -6       /* the HIP runtime refused a launch                      */
+  SP_ELAUNCH = -6,      /* the HIP runtime refused a launch                      */
+  SP_ETIMEOUT = -7      /* a bounded device-side wait expired (see sp_score_check) */
 } sp_status;
 
 /* How per-layer values are combined (Sec. 3.2.2).  The paper takes the maximum over
@@ -103,6 +104,14 @@ SP_API sp_status sp_score(const sp_score_args* args, void* hip_stream);
  * (sp_score picks a faster single-pass kernel when the shape allows).  Meant for
  * cross-checking the two implementations of the Sec. 3.2 / 3.2.2 arithmetic. */
 SP_API sp_status sp_score_general(const sp_score_args* args, void* hip_stream);
+
+/* Optional post-check of the most recent sp_score call that used args->d_workspace.  The
+ * single-pass kernel exchanges row statistics between workgroups that must all be resident
+ * on the device at once; that holds when nothing else occupies the GPU.  Its waits are
+ * bounded, and an expired wait is recorded in the workspace instead of hanging.  This call
+ * SYNCHRONISES hip_stream (the only entry point that does), reads that record and returns
+ * SP_ETIMEOUT if a wait expired (the scores are then invalid), SP_OK otherwise. */
+SP_API sp_status sp_score_check(const sp_score_args* args, void* hip_stream);
 
 /* ---------------------------------------------------------------------------
  * sp_pool_select: chunk_select_from_smoothed_attention (Algorithm 1, Sec. 3.2.3).

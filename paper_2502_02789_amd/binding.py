@@ -12,14 +12,14 @@ import os
 from typing import List, Optional, Sequence
 
 SP_OK = 0
-SP_EINVAL, SP_ENULL, SP_EALIGN, SP_EWORKSPACE, SP_EUNSUPPORTED, SP_ELAUNCH = -1, -2, -3, -4, -5, -6
+SP_EINVAL, SP_ENULL, SP_EALIGN, SP_EWORKSPACE, SP_EUNSUPPORTED, SP_ELAUNCH, SP_ETIMEOUT = -1, -2, -3, -4, -5, -6, -7
 SP_LAYER_MAX, SP_LAYER_MEAN = 0, 1
 SP_MAX_LAYERS, SP_MAX_QUERIES = 128, 16
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecprefill.so")
 
 EXPORTS = (
-    "sp_score_workspace_bytes", "sp_score", "sp_score_general",
+    "sp_score_workspace_bytes", "sp_score", "sp_score_general", "sp_score_check",
     "sp_keep_upper_bound", "sp_pool_select_workspace_bytes", "sp_pool_select",
     "sp_gather", "sp_strerror", "sp_version",
 )
@@ -78,6 +78,8 @@ def load_library() -> C.CDLL:
     lib.sp_score.argtypes = [C.POINTER(ScoreArgs), C.c_void_p]
     lib.sp_score_general.restype = C.c_int
     lib.sp_score_general.argtypes = [C.POINTER(ScoreArgs), C.c_void_p]
+    lib.sp_score_check.restype = C.c_int
+    lib.sp_score_check.argtypes = [C.POINTER(ScoreArgs), C.c_void_p]
     lib.sp_keep_upper_bound.restype = C.c_int64
     lib.sp_keep_upper_bound.argtypes = [C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.c_double]
     lib.sp_pool_select_workspace_bytes.restype = C.c_size_t
@@ -154,6 +156,11 @@ def sp_score_workspace_bytes(args: ScoreArgs) -> int:
 
 def sp_score(args: ScoreArgs, stream=None) -> None:
     _check("sp_score", load_library().sp_score(C.byref(args), _stream_handle(stream)))
+
+
+def sp_score_check(args: ScoreArgs, stream=None) -> None:
+    """Synchronises the stream; raises SpError(SP_ETIMEOUT) if a device-side wait expired."""
+    _check("sp_score_check", load_library().sp_score_check(C.byref(args), _stream_handle(stream)))
 
 
 def sp_score_general(args: ScoreArgs, stream=None) -> None:

@@ -87,6 +87,7 @@ extern "C" const char* sp_strerror(sp_status status) {
     case SP_EWORKSPACE: return "workspace missing or too small";
     case SP_EUNSUPPORTED: return "request not supported by this build";
     case SP_ELAUNCH: return "the HIP runtime refused a kernel launch";
+    case SP_ETIMEOUT: return "a bounded device-side wait expired; results are invalid";
   }
   return "unknown status";
 }

@@ -182,6 +182,8 @@ __global__ __launch_bounds__(256) void score_accum_kernel(const ScoreDev p) {
   }
 }
 
+__global__ void clear_word_kernel(uint32_t* word) { *word = 0; }
+
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
@@ -227,6 +229,11 @@ sp_status general_score(const sp_score_args* a, hipStream_t stream) {
     hipLaunchKernelGGL(lse_combine_kernel, dim3(rows), dim3(64), 0, stream, p);
     hipLaunchKernelGGL(score_accum_kernel<128>, dim3(p.max_tiles), dim3(256), 0, stream, p);
   }
+  // these kernels have no bounded waits: leave "no wait expired" where sp_score_check looks
+  const size_t status_off = stream_supported(a) ? stream_status_offset(a) : 0;
+  if (status_off)
+    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, stream,
+                       reinterpret_cast<uint32_t*>(static_cast<char*>(a->d_workspace) + status_off));
   return launch_status();
 }
 
@@ -280,6 +287,20 @@ extern "C" sp_status sp_score(const sp_score_args* a, void* hip_stream) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (sp::stream_supported(a)) return sp::stream_score(a, stream);
   return sp::general_score(a, stream);
+}
+
+extern "C" sp_status sp_score_check(const sp_score_args* a, void* hip_stream) {
+  const sp_status st = check_score_args(a);
+  if (st != SP_OK) return st;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (hipStreamSynchronize(stream) != hipSuccess) return SP_ELAUNCH;
+  const size_t off = sp::stream_supported(a) ? sp::stream_status_offset(a) : 0;
+  if (off == 0) return SP_OK;
+  uint32_t word = 0;
+  if (hipMemcpy(&word, static_cast<const char*>(a->d_workspace) + off, sizeof(word), hipMemcpyDeviceToHost) !=
+      hipSuccess)
+    return SP_ELAUNCH;
+  return word == 0 ? SP_OK : SP_ETIMEOUT;
 }
 
 extern "C" sp_status sp_score_general(const sp_score_args* a, void* hip_stream) {

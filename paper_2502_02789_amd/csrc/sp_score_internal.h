@@ -34,5 +34,6 @@ sp_status general_score(const sp_score_args* a, hipStream_t stream);
 bool stream_supported(const sp_score_args* a);
 size_t stream_workspace_bytes(const sp_score_args* a);
 sp_status stream_score(const sp_score_args* a, hipStream_t stream);
+size_t stream_status_offset(const sp_score_args* a);
 
 }  // namespace sp

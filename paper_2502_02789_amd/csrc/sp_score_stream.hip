@@ -11,28 +11,32 @@
 //   * one persistent workgroup per CU owns a fixed slice of the prompt (KPW keys) for the whole
 //     call; the work is cut into "slabs" = (layer, group of S KV heads).  A slab's logits are
 //     TPW accumulator tiles (32 keys x 32 query rows, fp32) per wave; the register file holds
-//     NSETS = 8 / TPW slabs at once, so a slab's logits survive NSETS-1 further slabs of
+//     NSETS = 8 / TPW slabs at once, so a slab's logits survive NSETS further slabs of
 //     streaming -- the window in which the cross-workgroup exchange below has to finish;
 //   * every wave streams its own sequence of 32-row tiles through a private two-slot LDS ring
 //     with direct global->LDS loads: per slab one tile of query rows (its KV head's 32
 //     (query, head-in-group) rows) followed by TPW tiles of keys.  Tiles are stored with an
 //     XOR swizzle that makes the MFMA operand reads bank-conflict free; the MFMA is
 //     v_mfma_f32_32x32x16_bf16 with keys as matrix rows and query rows as columns.  All vector
-//     memory traffic of the steady state is these fixed-size load groups, which is what lets a
-//     constant "s_waitcnt vmcnt(LOADS)" stand for "the older tile has landed";
-//   * per slab every wave publishes, for each of its rows, (max, sum 2^(x-max)) over its keys;
-//     a designated workgroup per group of 8 rows folds all partials into the rows' log-sum-exp
-//     and publishes them; one wave per workgroup (rotating) fetches a slab's log-sum-exps into
-//     an LDS mailbox for the other waves;
+//     memory traffic of a wave's steady state is direct-to-LDS loads in fixed-size groups, which
+//     is what lets a constant "s_waitcnt vmcnt(LOADS)" stand for "everything older than the
+//     youngest tile has landed" (plain loads and stores would force full drains);
+//   * exchange, hop 1: per slab every wave deposits, for each of its rows, (max, sum 2^(x-max))
+//     over its keys in LDS; the wave that deposits last merges the workgroup's rows and
+//     publishes them (64-byte chunks of 8 rows).  A designated workgroup per group of 8 rows
+//     polls all workgroups' chunks, folds them into the rows' log-sum-exp and publishes that;
+//   * exchange, hop 2: each wave fetches the 32 log-sum-exps of its rows with one more
+//     direct-to-LDS load, issued one tile ahead so that the ordinary tile wait covers it;
 //   * with the log-sum-exp known a slab's logits become log2-probabilities; the max over the
 //     heads of a KV group is a quad DPP max, the max over KV heads / layers an LDS float
 //     atomic max per (query, key); the layer mean (if asked) and the query mean are taken at
 //     layer end / kernel end.
 //
-// Cross-workgroup words are "empty" (all ones) until written, and are written and polled with
-// agent-scope atomics; a small kernel refills the workspace with the empty pattern at the
-// start of each call.  Every wait is bounded (a status word records an expired wait) and the
-// launch is cooperative, so all workgroups are co-resident and every wait ends.
+// Cross-workgroup words are "empty" (all ones) until written, and are written and read with
+// agent-scope coherence; a small kernel refills the workspace with the empty pattern at the
+// start of each call.  Every wait is bounded (a status word records an expired wait).  The grid
+// is one workgroup per CU, each needing more than half of a CU's LDS, so all of them are
+// resident together on an otherwise idle device; that residency is what every wait relies on.
 #include "sp_score_internal.h"
 
 namespace sp {
@@ -46,7 +50,7 @@ constexpr int kMaxWG = 256;
 constexpr uint64_t kEmpty64 = ~0ull;
 constexpr uint32_t kEmpty32 = ~0u;
 constexpr int kSpinBudget = 1 << 22;  // polls per wave over the whole call before giving up
-constexpr int kMailSlotsMax = 16;
+constexpr int kDepSlotBytes = 8 * 32 * 8;  // one slab's deposits: 8 waves x 32 rows x (max, sum)
 
 struct StreamDev {
   int M, L, N, H, G, lgG, S, slabs_per_layer, n_slabs, KPW, nwg, wpr, layer_reduce;
@@ -54,7 +58,7 @@ struct StreamDev {
   int64_t ts, hs;
   const uint16_t* q;
   const int32_t* n_valid;
-  uint64_t* partial;  // [row / 8][nwg * wpr][row % 8]
+  uint64_t* partial;  // [row / 8][nwg][row % 8]
   uint32_t* lse2;     // [rows]
   uint32_t* status;   // [0] != 0: a bounded wait ran out (results invalid)
   float* scores;
@@ -95,16 +99,28 @@ __device__ __forceinline__ uint32_t poll32(const uint32_t* p, int& budget) {
   return v;
 }
 
-// A 32-bit LDS read the compiler does not see as one.  The mailbox words read this way are never
-// the target of a direct-to-LDS tile load, so there is no reason to wait for the tile loads in
-// flight before reading them -- which an ordinary LDS read would be made to do.
+// LDS accesses the compiler does not see as such.  The words touched this way (deposits, counters,
+// fetched log-sum-exps, the running maxima) are never the target of a direct-to-LDS TILE load, so
+// there is no reason to wait for the tile loads in flight before touching them -- which an
+// ordinary LDS access would be made to do.  LDS operations of one wave are performed in order.
 __device__ __forceinline__ uint32_t lds_peek(uint32_t lds_addr) {
   uint32_t v;
   asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
   return v;
 }
-
-// LDS float atomic max at lds_addr + OFF, likewise invisible to the compiler's bookkeeping
+__device__ __forceinline__ uint64_t lds_peek64(uint32_t lds_addr) {
+  uint64_t v;
+  asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
+  return v;
+}
+__device__ __forceinline__ void lds_poke64(uint32_t lds_addr, uint64_t v) {
+  asm volatile("ds_write_b64 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_add_rtn(uint32_t lds_addr, uint32_t v) {
+  uint32_t old;
+  asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(old) : "v"(lds_addr), "v"(v) : "memory");
+  return old;
+}
 template <int OFF>
 __device__ __forceinline__ void lds_fmax(uint32_t lds_addr, float v) {
   asm volatile("ds_max_f32 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
@@ -115,12 +131,16 @@ __device__ __forceinline__ void lds_fmax_tile(uint32_t lds_addr, const float (&x
   (lds_fmax<((I >> 2) * 8 + (I & 3)) * 4>(lds_addr, x[I]), ...);
 }
 
-// max with the value of lane ^ 1 / lane ^ 2 (inside the quad)
+// max with the value of lane ^ 1 / lane ^ 2 (inside the quad); folds into v_max_f32_dpp
 __device__ __forceinline__ float max_quad_xor1(float v) {
-  return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true)));
+  return fmaxf(v, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true)));
 }
 __device__ __forceinline__ float max_quad_xor2(float v) {
-  return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true)));
+  return fmaxf(v, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x4E, 0xF, 0xF, true)));
+}
+
+__device__ __forceinline__ uint64_t pack_stat(float m, float s) {
+  return ((uint64_t)__float_as_uint(s) << 32) | __float_as_uint(m);
 }
 
 template <int D, int TPW>
@@ -133,20 +153,22 @@ struct Streamer {
   static constexpr int UNITS = ROW_B / 16;     // 16-byte units per row
   static constexpr int LOADS = TILE_B / 1024;  // wave-wide 16-byte loads per tile
   static constexpr int RPI = 64 / UNITS;       // rows covered by one such load
-  static constexpr int FIN_LAG = NSETS - 1;    // slab s is finished while slab s + FIN_LAG streams
-  static constexpr int RED_LAG = NSETS >= 4 ? NSETS / 2 : 1;  // slab s is reduced while slab s + RED_LAG streams
+  // slab s: published at the end of its own streaming, reduced while slab s + RED_LAG streams,
+  // its log-sum-exps requested at the end of slab s + NSETS - 1, finished at the start of
+  // slab s + NSETS (just before its register set is reused)
+  static constexpr int RED_LAG = NSETS >= 4 ? NSETS / 2 : 1;
   static constexpr int RED_KB = NSETS >= 4 ? 0 : (TPW >= 2 ? TPW / 2 - 1 : 0);
-  static constexpr int MAIL_SLOTS = 2 * NSETS;
 
   const StreamDev& p;
   float* smax;           // [N][KPW] running max of log2-probabilities
-  float* mail;           // [MAIL_SLOTS][S*32] log-sum-exps fetched for the workgroup
-  int* mail_flag;        // [MAIL_SLOTS] slab + 1 whose values the slot holds
   int wave, lane, half, col, wg;
   int kvh_local, kbg;
   int keys_wg;           // valid keys owned by this workgroup
   int budget;
   uint32_t ring_lds;     // LDS byte address of this wave's two-slot ring
+  uint32_t dep_lds;      // LDS: [NSETS][8 waves][32 rows] (max, sum) deposits
+  uint32_t cnt_lds;      // LDS: [NSETS] arrival counters
+  uint32_t lse_lds;      // LDS: this wave's [2][64] fetched log-sum-exps
   uint32_t rd0;          // LDS byte address of this lane's operand unit for k-step 0 in slot 0
   uint32_t ld_off[4];    // per-lane global byte offset of key load j (depends on j & 3 only)
   bf16x8 qf[KS];
@@ -165,10 +187,12 @@ struct Streamer {
     wg = blockIdx.x;
     kvh_local = wave % p.S;
     kbg = wave / p.S;
-    ring_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem) + wave * 2 * TILE_B;
-    smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B);
-    mail = smax + p.N * p.KPW;
-    mail_flag = reinterpret_cast<int*>(mail + MAIL_SLOTS * p.S * 32);
+    const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+    ring_lds = smem_lds + wave * 2 * TILE_B;
+    dep_lds = smem_lds + kWaves * 2 * TILE_B;
+    cnt_lds = dep_lds + NSETS * kDepSlotBytes;
+    lse_lds = cnt_lds + 64 + wave * 512;
+    smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 512);
     keys_wg = max(0, min(p.KPW, p.M - wg * p.KPW));
     budget = kSpinBudget;
     // operand read: unit (2t + half) of row col lives at position (2t + half) ^ key(col)
@@ -183,6 +207,11 @@ struct Streamer {
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj)
       ld_off[jj] = (uint32_t)((int64_t)i * p.ts * 2) + (uint32_t)((u0 ^ ((4 * jj) & (UNITS - 1))) << 4);
+  }
+
+  static size_t smem_bytes(int n_queries, int kpw) {
+    return (size_t)kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 512 +
+           (size_t)n_queries * kpw * sizeof(float);
   }
 
   __device__ __forceinline__ static __attribute__((address_space(3))) void* lds_ptr(uint32_t addr) {
@@ -305,41 +334,55 @@ struct Streamer {
     run_s = s;
   }
 
-  // publish this wave's (max, sum) of every row of the slab over the keys it has seen;
-  // 8 consecutive rows of one (workgroup, wave) form one 64-byte chunk
-  __device__ __forceinline__ void publish(int slab) {
-    const float m_o = __shfl_xor(run_m, 32, kWave);
-    const float s_o = __shfl_xor(run_s, 32, kWave);
-    const float mm = fmaxf(run_m, m_o);
-    const float ref = (mm == -INFINITY) ? 0.f : mm;
-    const float ss = run_s * fast_exp2((run_m - ref) * p.c) + s_o * fast_exp2((m_o - ref) * p.c);
-    if (half == 0) {
-      const uint64_t word = ((uint64_t)__float_as_uint(ss) << 32) | __float_as_uint(mm);
-      const int row = row_base(slab) + col;
-      const int entries = p.nwg * p.wpr;
-      uint64_t* dst = p.partial + ((int64_t)(row >> 3) * entries + wg * p.wpr + kbg) * 8 + (row & 7);
-      __hip_atomic_store(dst, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // fold two (max, sum) pairs
+  __device__ __forceinline__ void fold(float& m, float& s, float pm, float ps) const {
+    const float mn = fmaxf(m, pm);
+    const float ref = (mn == -INFINITY) ? 0.f : mn;
+    s = s * fast_exp2((m - ref) * p.c) + ps * fast_exp2((pm - ref) * p.c);
+    m = mn;
+  }
+
+  // Hop 1, sending side.  Deposit this wave's (max, sum) of each of its 32 rows in LDS; the wave
+  // that arrives last merges the waves that share rows and publishes the workgroup's S*32 rows
+  // (so seven of eight waves issue no global store, which would linger in their vmcnt).
+  __device__ __forceinline__ void deposit_and_publish(int slab) {
+    float m = run_m, s = run_s;
+    fold(m, s, __shfl_xor(run_m, 32, kWave), __shfl_xor(run_s, 32, kWave));
+    const int set = slab % NSETS;
+    const uint32_t dep = dep_lds + set * kDepSlotBytes;
+    if (half == 0) lds_poke64(dep + (wave * 32 + col) * 8, pack_stat(m, s));
+    uint32_t old = 0;
+    if (lane == 0) old = lds_add_rtn(cnt_lds + set * 4, 1);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if ((old & 7) != 7) return;
+    // last of the 8 waves: rows of the slab are (kvh_local, qrow); wave w = kbg * S + kvh_local
+    const int rows = p.S * 32;
+    for (int r = lane; r < rows; r += kWave) {
+      float mm = -INFINITY, ss = 0.f;
+      for (int g = 0; g < p.wpr; ++g) {
+        const uint64_t w = lds_peek64(dep + ((g * p.S + (r >> 5)) * 32 + (r & 31)) * 8);
+        fold(mm, ss, __uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32)));
+      }
+      const int row = slab * rows + r;
+      uint64_t* dst = p.partial + ((int64_t)(row >> 3) * p.nwg + wg) * 8 + (row & 7);
+      __hip_atomic_store(dst, pack_stat(mm, ss), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 
-  // If this workgroup is responsible for a group of 8 rows of the slab, fold all workgroups'
-  // partials of those rows (one row per wave) into the rows' log-sum-exp and publish them.
+  // Hop 1, receiving side.  If this workgroup is responsible for a group of 8 rows of the slab,
+  // fold all workgroups' (max, sum) of those rows (one row per wave) into the rows' log-sum-exp
+  // and publish them.
   __device__ __forceinline__ void reduce_rows(int slab) {
     const int groups = p.S * 4;  // row groups per slab
     const int base = slab * groups;
     const int rg = base + ((wg - base) % p.nwg + p.nwg) % p.nwg;
     if (rg >= base + groups) return;
-    const int entries = p.nwg * p.wpr;
     const int row = rg * 8 + wave;
-    const uint64_t* src = p.partial + (int64_t)rg * entries * 8 + wave;
+    const uint64_t* src = p.partial + (int64_t)rg * p.nwg * 8 + wave;
     float m = -INFINITY, s = 0.f;
-    for (int e = lane; e < entries; e += kWave) {
+    for (int e = lane; e < p.nwg; e += kWave) {
       const uint64_t w = poll64(src + (int64_t)e * 8, budget);
-      const float pm = __uint_as_float((uint32_t)w), ps = __uint_as_float((uint32_t)(w >> 32));
-      const float mn = fmaxf(m, pm);
-      const float ref = (mn == -INFINITY) ? 0.f : mn;
-      s = s * fast_exp2((m - ref) * p.c) + ps * fast_exp2((pm - ref) * p.c);
-      m = mn;
+      fold(m, s, __uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32)));
     }
     const float mw = wave_max(m);  // finite: the prompt is not empty
     const float zw = wave_sum(s * fast_exp2((m - mw) * p.c));
@@ -358,32 +401,25 @@ struct Streamer {
     }
   }
 
-  // one wave fetches the slab's log-sum-exps (S*32 words) into the LDS mailbox
-  __device__ __forceinline__ void fetch_lse(int slab) {
-    const int words = p.S * 32;
-    const int slot = slab % MAIL_SLOTS;
-    for (int i = lane; i < words; i += kWave) {
-      const uint32_t bits = poll32(p.lse2 + (int64_t)slab * words + i, budget);
-      mail[slot * words + i] = __uint_as_float(bits);
-    }
-    // LDS operations of one wave complete in order: once the value writes are done the flag may
-    // go (no memory fence here: it would also wait for the tile loads in flight)
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (lane == 0) __hip_atomic_store(mail_flag + slot, slab + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  // Hop 2.  Request the log-sum-exps of this wave's 32 rows of the slab with one direct-to-LDS
+  // load (agent-coherent); it is older than the tile loads issued after it, so the next tile
+  // wait covers it.
+  __device__ __forceinline__ void request_lse(int slab) {
+    const uint32_t* src = p.lse2 + row_base(slab) + col;
+    __builtin_amdgcn_global_load_lds(src, lds_ptr(lse_lds + (slab & 1) * 256), 4, 0, /*sc1*/ 16);
+  }
+  // The requested words have landed: take this lane's; if the exchange is late, poll for it.
+  __device__ __forceinline__ float take_lse(int slab) {
+    uint32_t bits = lds_peek(lse_lds + (slab & 1) * 256 + lane * 4);
+    if (__builtin_expect(__any(bits == kEmpty32), 0)) bits = poll32(p.lse2 + row_base(slab) + col, budget);
+    return __uint_as_float(bits);
   }
 
-  // Turn the stored logits of slab `slab` (set SET) into log2-probabilities and max them into
-  // smax: over the heads of the KV group across lanes, over KV heads / layers in LDS.
+  // Turn the stored logits of set SET into log2-probabilities and max them into smax: over the
+  // heads of the KV group across lanes, over KV heads / layers in LDS.
   template <int SET>
-  __device__ __forceinline__ void finish_slab(int slab) {
-    const int slot = slab % MAIL_SLOTS;
-    const uint32_t flag_addr = lds_addr_of(mail_flag + slot);
-    while ((int)lds_peek(flag_addr) != slab + 1 && budget > 0) {
-      __builtin_amdgcn_s_sleep(1);
-      --budget;
-    }
-    // the value is read after the flag: same wave, same in-order LDS queue
-    const float neg_lse = -__uint_as_float(lds_peek(lds_addr_of(mail + slot * p.S * 32 + kvh_local * 32 + col)));
+  __device__ __forceinline__ void finish_set(float lse) {
+    const float neg_lse = -lse;
     const bool writer = col < p.G * p.N && (col & (p.G - 1)) == 0;
     // LDS address of this lane's first key of tile 0 in its query's row of smax
     const uint32_t dst0 = lds_addr_of(smax + (col >> p.lgG) * p.KPW + kbg * TPW * 32 + half * 4);
@@ -420,7 +456,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
 #pragma unroll
   for (int j = 0; j < 8; ++j) tot[j] = 0.f;
   for (int i = threadIdx.x; i < cells; i += kThreads) st.smax[i] = -INFINITY;
-  if (threadIdx.x < kMailSlotsMax) st.mail_flag[threadIdx.x] = 0;
+  if (threadIdx.x < 16) *reinterpret_cast<uint32_t*>(smem + kWaves * 2 * St::TILE_B + NSETS * kDepSlotBytes + threadIdx.x * 4) = 0;
   __syncthreads();
 
   // layer-mean mode: slab `done` was just finished by this wave; if it closes a layer (other
@@ -445,16 +481,17 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
   st.template issue_stream<0>(0, 0);
   st.template issue_stream<1>(0, 1);
 
-  // One slab: read its query fragments, stream its TPW key tiles (MFMA + row statistics),
-  // publish the statistics; in between serve the exchange of older slabs; at the end turn the
-  // slab that is FIN_LAG behind into probabilities.  Stream tile x of the slab sits in ring
-  // slot (SET*TPS + x) & 1 (NSETS is even, so the slab's parity is SET's).
+  // One slab.  Stream tile x of the slab sits in ring slot (SET*TPS + x) & 1 (NSETS is even, so
+  // the slab's parity is SET's).  Before every use of a stream tile, "vmcnt <= LOADS" means: the
+  // LOADS loads of the one younger tile are the only ones that may still be in flight.
   auto body = [&](auto set_tag, int slab) {
     constexpr int SET = decltype(set_tag)::value;
     constexpr int SLOT0 = (SET * TPS) & 1;
-    // before every use of a stream tile: the LOADS loads of the one younger tile are the only
-    // ones that may still be in flight
     wait_vmcnt<St::LOADS>();
+    if (slab >= NSETS) {  // set SET still holds slab - NSETS, whose log-sum-exps were requested a tile ago
+      st.template finish_set<SET>(st.take_lse(slab - NSETS));
+      close_layer(slab - NSETS);
+    }
     st.read_queries(SLOT0);
     st.template issue_stream<2>(slab, SLOT0);
     st.run_m = -INFINITY;
@@ -464,6 +501,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
       const int slot = (SLOT0 + 1 + kb) & 1;
       wait_vmcnt<St::LOADS>();
       st.template mfma_tile<SET>(kb, slot);
+      if (kb == TPW - 1 && slab + 1 >= NSETS) st.request_lse(slab + 1 - NSETS);
       switch (kb) {  // a compile-time constant after unrolling
         case 0: st.template issue_stream<3>(slab, slot); break;
         case 1: st.template issue_stream<4>(slab, slot); break;
@@ -471,15 +509,9 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
         default: st.template issue_stream<6>(slab, slot); break;
       }
       if (kb == St::RED_KB && slab >= St::RED_LAG) st.reduce_rows(slab - St::RED_LAG);
-      if (kb == TPW - 1 && slab >= St::FIN_LAG && st.wave == ((slab - St::FIN_LAG) & 7))
-        st.fetch_lse(slab - St::FIN_LAG);
       st.template stats_tile<SET>(kb);
     }
-    st.publish(slab);
-    if (slab >= St::FIN_LAG) {
-      st.template finish_slab<(SET + 1) % NSETS>(slab - St::FIN_LAG);
-      close_layer(slab - St::FIN_LAG);
-    }
+    st.deposit_and_publish(slab);
   };
 
   for (int s0 = 0; s0 < p.n_slabs; s0 += NSETS) {
@@ -500,18 +532,17 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
   // drain: the exchange of the last slabs cannot hide behind further streaming
   wait_vmcnt<0>();
   for (int s = max(0, p.n_slabs - St::RED_LAG); s < p.n_slabs; ++s) st.reduce_rows(s);
-  for (int s = max(0, p.n_slabs - St::FIN_LAG); s < p.n_slabs; ++s)
-    if (st.wave == (s & 7)) st.fetch_lse(s);
-  for (int s = max(0, p.n_slabs - St::FIN_LAG); s < p.n_slabs; ++s) {
+  for (int s = max(0, p.n_slabs - NSETS); s < p.n_slabs; ++s) {
+    const float lse = __uint_as_float(poll32(p.lse2 + st.row_base(s) + st.col, st.budget));
     switch (s % NSETS) {
-      case 0: st.template finish_slab<0>(s); break;
-      case 1: st.template finish_slab<1 % NSETS>(s); break;
-      case 2: st.template finish_slab<2 % NSETS>(s); break;
-      case 3: st.template finish_slab<3 % NSETS>(s); break;
-      case 4: st.template finish_slab<4 % NSETS>(s); break;
-      case 5: st.template finish_slab<5 % NSETS>(s); break;
-      case 6: st.template finish_slab<6 % NSETS>(s); break;
-      default: st.template finish_slab<7 % NSETS>(s); break;
+      case 0: st.template finish_set<0>(lse); break;
+      case 1: st.template finish_set<1 % NSETS>(lse); break;
+      case 2: st.template finish_set<2 % NSETS>(lse); break;
+      case 3: st.template finish_set<3 % NSETS>(lse); break;
+      case 4: st.template finish_set<4 % NSETS>(lse); break;
+      case 5: st.template finish_set<5 % NSETS>(lse); break;
+      case 6: st.template finish_set<6 % NSETS>(lse); break;
+      default: st.template finish_set<7 % NSETS>(lse); break;
     }
     close_layer(s);
   }
@@ -578,10 +609,10 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   int kb2 = 1;
   while (kb2 < kb) kb2 <<= 1;
   if (kb2 > 16) return pl;  // beyond 16 key blocks per workgroup the slabs no longer fit
-  // S * kb2 = 8 * TPW with S in {2,4,8} (S = 1 would need 8 partial words per row and
-  // workgroup) and TPW in {1,2,4}: start from the preferred TPW and move it into range
+  // S * kb2 = 8 * TPW with S in {1,2,4,8} and TPW in {1,2,4}: start from the preferred TPW and
+  // move it into range
   int tpw = SP_STREAM_TPW_PREF;
-  while (tpw < 4 && 8 * tpw / kb2 < 2) tpw <<= 1;
+  while (tpw < 4 && 8 * tpw < kb2) tpw <<= 1;
   while (tpw > 1 && 8 * tpw / kb2 > 8) tpw >>= 1;
   const int S = 8 * tpw / kb2;
   if (S < 1 || S > 8 || S * kb2 != 8 * tpw) return pl;
@@ -593,11 +624,10 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   pl.slabs_per_layer = a->H_kv / pl.S;
   pl.n_slabs = a->L * pl.slabs_per_layer;
   pl.rows = (size_t)a->L * a->H_kv * 32;
-  pl.partial_bytes = align_up(pl.rows * nwg * pl.wpr * sizeof(uint64_t), 256);
+  pl.partial_bytes = align_up(pl.rows * nwg * sizeof(uint64_t), 256);
   pl.lse_bytes = align_up(pl.rows * sizeof(uint32_t), 256);
-  const size_t mail_floats = (size_t)2 * (8 / tpw) * S * 32;
-  pl.smem_bytes = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)a->N * pl.KPW * sizeof(float) +
-                  mail_floats * sizeof(float) + kMailSlotsMax * sizeof(int);
+  pl.smem_bytes = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)(8 / tpw) * kDepSlotBytes + 64 + kWaves * 512 +
+                  (size_t)a->N * pl.KPW * sizeof(float);
   if (pl.smem_bytes > 160 * 1024) return pl;
   if ((size_t)a->N * pl.KPW > 8 * kThreads) return pl;
   pl.ok = true;
@@ -612,18 +642,29 @@ size_t stream_workspace_bytes(const sp_score_args* a) {
   return pl.partial_bytes + pl.lse_bytes + 256;
 }
 
+// byte offset of the status word inside the workspace, or 0 if the shape does not use this kernel
+size_t stream_status_offset(const sp_score_args* a) {
+  const StreamPlan pl = make_plan(a, device_cu_count());
+  return pl.ok ? pl.partial_bytes + pl.lse_bytes : 0;
+}
+
 template <int D, int TPW>
 static sp_status launch_stream(const StreamDev& dev, const StreamPlan& pl, hipStream_t stream) {
   auto kernel = stream_score_kernel<D, TPW>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          (int)pl.smem_bytes) != hipSuccess)
-    return SP_ELAUNCH;
-  StreamDev copy = dev;
-  void* args[] = {&copy};
-  if (hipLaunchCooperativeKernel(reinterpret_cast<const void*>(kernel), dim3(pl.nwg), dim3(kThreads), args,
-                                 (unsigned)pl.smem_bytes, stream) != hipSuccess)
-    return SP_ELAUNCH;
-  return SP_OK;
+  // once per kernel: allow the large dynamic LDS size and make sure one workgroup fits on a CU
+  static int prepared_for = -1;
+  if (prepared_for < (int)pl.smem_bytes) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            160 * 1024) != hipSuccess)
+      return SP_ELAUNCH;
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kernel), kThreads,
+                                                     pl.smem_bytes) != hipSuccess || per_cu < 1)
+      return SP_ELAUNCH;
+    prepared_for = 160 * 1024;
+  }
+  hipLaunchKernelGGL(kernel, dim3(pl.nwg), dim3(kThreads), pl.smem_bytes, stream, dev);
+  return launch_status();
 }
 
 sp_status stream_score(const sp_score_args* a, hipStream_t stream) {

@@ -14,7 +14,7 @@ TIE_RTOL = 1e-6            # stage-isolated selection: chunks this close to the 
 def gpu_score(q_bits, k_bits_layers, cu, H_kv, scale, mode, n_valid=None, general=False, want_lse=True,
               head_major=False):
     import torch
-    from paper_2502_02789_amd import device as dev
+    from paper_2502_02789_amd import binding as sp_binding, device as dev
     q = dev.bf16_from_bits(q_bits)
     if head_major:
         ks = [dev.bf16_from_bits(np.ascontiguousarray(k.transpose(1, 0, 2))).permute(1, 0, 2) for k in k_bits_layers]
@@ -25,7 +25,7 @@ def gpu_score(q_bits, k_bits_layers, cu, H_kv, scale, mode, n_valid=None, genera
     s = dev.Scorer(q, ks, cu_d, H_kv=H_kv, scale=scale, layer_reduce=mode, n_valid=nv_d, want_lse=want_lse)
     s.scores.fill_(float("nan"))
     s.run(general=general)
-    torch.cuda.synchronize()
+    sp_binding.sp_score_check(s.args)          # synchronises; raises if a device-side wait expired
     return s.scores.cpu().numpy(), (s.lse.cpu().numpy() if want_lse else None)
 
 

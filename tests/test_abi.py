@@ -34,7 +34,7 @@ def test_struct_layouts_match_the_header_field_order():
 
 def test_version_and_messages():
     assert sp.sp_version() >= 100
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         assert sp.strerror(code) and sp.strerror(code) != "unknown status"
     assert sp.strerror(-99) == "unknown status"
 
