@@ -22,9 +22,10 @@
 //     is what lets a constant "s_waitcnt vmcnt(LOADS)" stand for "everything older than the
 //     youngest tile has landed" (plain loads and stores would force full drains);
 //   * exchange, hop 1: per slab every wave deposits, for each of its rows, (max, sum 2^(x-max))
-//     over its keys in LDS; the wave that deposits last merges the workgroup's rows and
-//     publishes them (64-byte chunks of 8 rows).  A designated workgroup per group of 8 rows
-//     polls all workgroups' chunks, folds them into the rows' log-sum-exp and publishes that;
+//     over its keys in LDS; one wave (rotating) merges the workgroup's rows once all eight
+//     deposits are in and publishes them (64-byte chunks of 8 rows).  A designated workgroup per
+//     group of 8 rows reads all workgroups' chunks, folds them into the rows' log-sum-exp and
+//     publishes that;
 //   * exchange, hop 2: each wave fetches the 32 log-sum-exps of its rows with one more
 //     direct-to-LDS load, issued one tile ahead so that the ordinary tile wait covers it;
 //   * with the log-sum-exp known a slab's logits become log2-probabilities; the max over the
@@ -49,7 +50,7 @@ constexpr int kThreads = kWaves * kWave;
 constexpr int kMaxWG = 256;
 constexpr uint64_t kEmpty64 = ~0ull;
 constexpr uint32_t kEmpty32 = ~0u;
-constexpr int kSpinBudget = 1 << 22;  // polls per wave over the whole call before giving up
+constexpr int kSpinBudget = 1 << 16;  // polls per wave over the whole call before giving up (~0.1 s)
 constexpr int kDepSlotBytes = 8 * 32 * 8;  // one slab's deposits: 8 waves x 32 rows x (max, sum)
 
 struct StreamDev {
@@ -116,10 +117,8 @@ __device__ __forceinline__ uint64_t lds_peek64(uint32_t lds_addr) {
 __device__ __forceinline__ void lds_poke64(uint32_t lds_addr, uint64_t v) {
   asm volatile("ds_write_b64 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
 }
-__device__ __forceinline__ uint32_t lds_add_rtn(uint32_t lds_addr, uint32_t v) {
-  uint32_t old;
-  asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(old) : "v"(lds_addr), "v"(v) : "memory");
-  return old;
+__device__ __forceinline__ void lds_add(uint32_t lds_addr, uint32_t v) {
+  asm volatile("ds_add_u32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
 }
 template <int OFF>
 __device__ __forceinline__ void lds_fmax(uint32_t lds_addr, float v) {
@@ -165,6 +164,7 @@ struct Streamer {
   int kvh_local, kbg;
   int keys_wg;           // valid keys owned by this workgroup
   int budget;
+  int pub_next;          // next slab this wave has to publish (slab % 8 == wave)
   uint32_t ring_lds;     // LDS byte address of this wave's two-slot ring
   uint32_t dep_lds;      // LDS: [NSETS][8 waves][32 rows] (max, sum) deposits
   uint32_t cnt_lds;      // LDS: [NSETS] arrival counters
@@ -195,6 +195,7 @@ struct Streamer {
     smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 512);
     keys_wg = max(0, min(p.KPW, p.M - wg * p.KPW));
     budget = kSpinBudget;
+    pub_next = wave;
     // operand read: unit (2t + half) of row col lives at position (2t + half) ^ key(col)
     //             = 2 * (t ^ (key >> 1)) + (half ^ (key & 1)), so the address is rd0 ^ (t << 5)
     const int key = (D == 128) ? (col & 15) : ((col >> 1) & 7);
@@ -342,30 +343,47 @@ struct Streamer {
     m = mn;
   }
 
-  // Hop 1, sending side.  Deposit this wave's (max, sum) of each of its 32 rows in LDS; the wave
-  // that arrives last merges the waves that share rows and publishes the workgroup's S*32 rows
-  // (so seven of eight waves issue no global store, which would linger in their vmcnt).
-  __device__ __forceinline__ void deposit_and_publish(int slab) {
+  // Hop 1, sending side.  Deposit this wave's (max, sum) of each of its 32 rows in LDS and count
+  // the arrival.
+  __device__ __forceinline__ void deposit(int slab) {
     float m = run_m, s = run_s;
     fold(m, s, __shfl_xor(run_m, 32, kWave), __shfl_xor(run_s, 32, kWave));
     const int set = slab % NSETS;
-    const uint32_t dep = dep_lds + set * kDepSlotBytes;
-    if (half == 0) lds_poke64(dep + (wave * 32 + col) * 8, pack_stat(m, s));
-    uint32_t old = 0;
-    if (lane == 0) old = lds_add_rtn(cnt_lds + set * 4, 1);
-    old = __builtin_amdgcn_readfirstlane(old);
-    if ((old & 7) != 7) return;
-    // last of the 8 waves: rows of the slab are (kvh_local, qrow); wave w = kbg * S + kvh_local
-    const int rows = p.S * 32;
-    for (int r = lane; r < rows; r += kWave) {
-      float mm = -INFINITY, ss = 0.f;
-      for (int g = 0; g < p.wpr; ++g) {
-        const uint64_t w = lds_peek64(dep + ((g * p.S + (r >> 5)) * 32 + (r & 31)) * 8);
-        fold(mm, ss, __uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32)));
+    if (half == 0) lds_poke64(dep_lds + set * kDepSlotBytes + (wave * 32 + col) * 8, pack_stat(m, s));
+    if (lane == 0) lds_add(cnt_lds + set * 4, 1);
+  }
+
+  // Slab t is published by wave t % 8 once all 8 waves have deposited it: the rows shared by
+  // several waves are merged and the workgroup's S*32 rows go out as 64-byte chunks.  A fixed
+  // rotation (rather than "whoever deposits last") keeps the job off the wave that is already
+  // behind, and seven of eight waves issue no global store, which would linger in their vmcnt.
+  // Called at tile boundaries with `upto` = newest slab this wave has deposited; slabs up to
+  // `must` are waited for: this wave is about to block on something (a log-sum-exp, other
+  // workgroups' statistics) that cannot arrive before its own workgroup has published them.
+  __device__ __forceinline__ void service_publish(int upto, int must) {
+    while (pub_next <= upto) {
+      const int set = pub_next % NSETS;
+      const uint32_t need = 8u * (uint32_t)(pub_next / NSETS + 1);
+      uint32_t cnt = __builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + set * 4));
+      while (pub_next <= must && cnt < need && budget > 0) {
+        __builtin_amdgcn_s_sleep(1);
+        --budget;
+        cnt = __builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + set * 4));
       }
-      const int row = slab * rows + r;
-      uint64_t* dst = p.partial + ((int64_t)(row >> 3) * p.nwg + wg) * 8 + (row & 7);
-      __hip_atomic_store(dst, pack_stat(mm, ss), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (cnt < need) return;
+      const uint32_t dep = dep_lds + set * kDepSlotBytes;
+      const int rows = p.S * 32;
+      for (int r = lane; r < rows; r += kWave) {  // deposits are indexed [kbg * S + kvh_local][qrow]
+        float mm = -INFINITY, ss = 0.f;
+        for (int g = 0; g < p.wpr; ++g) {
+          const uint64_t w = lds_peek64(dep + ((g * p.S + (r >> 5)) * 32 + (r & 31)) * 8);
+          fold(mm, ss, __uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32)));
+        }
+        const int row = pub_next * rows + r;
+        uint64_t* dst = p.partial + ((int64_t)(row >> 3) * p.nwg + wg) * 8 + (row & 7);
+        __hip_atomic_store(dst, pack_stat(mm, ss), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      pub_next += kWaves;
     }
   }
 
@@ -380,9 +398,17 @@ struct Streamer {
     const int row = rg * 8 + wave;
     const uint64_t* src = p.partial + (int64_t)rg * p.nwg * 8 + wave;
     float m = -INFINITY, s = 0.f;
-    for (int e = lane; e < p.nwg; e += kWave) {
-      const uint64_t w = poll64(src + (int64_t)e * 8, budget);
-      fold(m, s, __uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32)));
+    uint64_t w[kMaxWG / kWave];
+#pragma unroll
+    for (int j = 0; j < kMaxWG / kWave; ++j) {  // all of a lane's loads go out before any is looked at
+      const int e = lane + j * kWave;
+      w[j] = e < p.nwg ? __hip_atomic_load(src + (int64_t)e * 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                       : pack_stat(-INFINITY, 0.f);
+    }
+#pragma unroll
+    for (int j = 0; j < kMaxWG / kWave; ++j) {
+      if (w[j] == kEmpty64) w[j] = poll64(src + (int64_t)(lane + j * kWave) * 8, budget);
+      fold(m, s, __uint_as_float((uint32_t)w[j]), __uint_as_float((uint32_t)(w[j] >> 32)));
     }
     const float mw = wave_max(m);  // finite: the prompt is not empty
     const float zw = wave_sum(s * fast_exp2((m - mw) * p.c));
@@ -416,23 +442,30 @@ struct Streamer {
   }
 
   // Turn the stored logits of set SET into log2-probabilities and max them into smax: over the
-  // heads of the KV group across lanes, over KV heads / layers in LDS.
-  template <int SET>
-  __device__ __forceinline__ void finish_set(float lse) {
-    const float neg_lse = -lse;
+  // heads of the KV group across lanes, over KV heads / layers in LDS.  LG = log2(group size).
+  template <int SET, int LG>
+  __device__ __forceinline__ void finish_tiles(float neg_lse) {
     const bool writer = col < p.G * p.N && (col & (p.G - 1)) == 0;
     // LDS address of this lane's first key of tile 0 in its query's row of smax
-    const uint32_t dst0 = lds_addr_of(smax + (col >> p.lgG) * p.KPW + kbg * TPW * 32 + half * 4);
+    const uint32_t dst0 = lds_addr_of(smax + (col >> LG) * p.KPW + kbg * TPW * 32 + half * 4);
 #pragma unroll
     for (int kb = 0; kb < TPW; ++kb) {
       float x[16];
+      // step by step over all 16 registers: a DPP read right after the write of its source
+      // register would cost wait states
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float v = fmaf(acc[SET][kb][i], p.c, neg_lse);
-        if (p.G >= 2) v = max_quad_xor1(v);
-        if (p.G >= 4) v = max_quad_xor2(v);
-        if (p.G >= 8) v = fmaxf(v, __shfl_xor(v, 4, kWave));
-        x[i] = v;
+      for (int i = 0; i < 16; ++i) x[i] = fmaf(acc[SET][kb][i], p.c, neg_lse);
+      if (LG >= 1) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = max_quad_xor1(x[i]);
+      }
+      if (LG >= 2) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = max_quad_xor2(x[i]);
+      }
+      if (LG >= 3) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = fmaxf(x[i], __shfl_xor(x[i], 4, kWave));
       }
       const int first = (kbg * TPW + kb) * 32;
       if (first + 32 > keys_wg) {  // ragged tail: keys beyond the prompt never beat the -inf start value
@@ -441,6 +474,15 @@ struct Streamer {
           if (key_of(kb, i) >= keys_wg) x[i] = -INFINITY;
       }
       if (writer) lds_fmax_tile(dst0 + kb * 128, x, std::make_integer_sequence<int, 16>{});
+    }
+  }
+  template <int SET>
+  __device__ __forceinline__ void finish_set(float lse) {
+    switch (p.lgG) {
+      case 0: finish_tiles<SET, 0>(-lse); break;
+      case 1: finish_tiles<SET, 1>(-lse); break;
+      case 2: finish_tiles<SET, 2>(-lse); break;
+      default: finish_tiles<SET, 3>(-lse); break;
     }
   }
 };
@@ -488,6 +530,9 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
     constexpr int SET = decltype(set_tag)::value;
     constexpr int SLOT0 = (SET * TPS) & 1;
     wait_vmcnt<St::LOADS>();
+    // everything this wave may block on below (log-sum-exps of slab - NSETS, statistics of slab -
+    // RED_LAG) needs this workgroup's publications up to slab - RED_LAG
+    st.service_publish(slab - 1, slab - St::RED_LAG);
     if (slab >= NSETS) {  // set SET still holds slab - NSETS, whose log-sum-exps were requested a tile ago
       st.template finish_set<SET>(st.take_lse(slab - NSETS));
       close_layer(slab - NSETS);
@@ -508,10 +553,11 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
         case 2: st.template issue_stream<5>(slab, slot); break;
         default: st.template issue_stream<6>(slab, slot); break;
       }
+      if (kb == 0 && TPW > 1) st.service_publish(slab - 1, -1);
       if (kb == St::RED_KB && slab >= St::RED_LAG) st.reduce_rows(slab - St::RED_LAG);
       st.template stats_tile<SET>(kb);
     }
-    st.deposit_and_publish(slab);
+    st.deposit(slab);
   };
 
   for (int s0 = 0; s0 < p.n_slabs; s0 += NSETS) {
@@ -531,6 +577,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
 
   // drain: the exchange of the last slabs cannot hide behind further streaming
   wait_vmcnt<0>();
+  st.service_publish(p.n_slabs - 1, p.n_slabs - 1);
   for (int s = max(0, p.n_slabs - St::RED_LAG); s < p.n_slabs; ++s) st.reduce_rows(s);
   for (int s = max(0, p.n_slabs - NSETS); s < p.n_slabs; ++s) {
     const float lse = __uint_as_float(poll32(p.lse2 + st.row_base(s) + st.col, st.budget));
