@@ -22,6 +22,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
 
+def measured_traffic(workload, general):
+    """HBM bytes per sp_score launch as read from the FETCH_SIZE / WRITE_SIZE counter runs whose
+    summaries sit under profiles/ (counters cannot be collected from inside this process)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if general or not os.path.exists(path):
+        return None
+    with open(path) as f:
+        entry = json.load(f).get(f"workload{workload}:stream_score_kernel")
+    return None if entry is None else entry["traffic_bytes_per_launch"]
+
+
 def cpu_baseline(w, inp, layer_reduce, sample_layers):
     """Times the fp64 oracle, unchanged, on a layer subset of the same inputs (full prompt,
     all heads and queries) plus selection and gather on its scores; cost is linear in layers."""
@@ -59,6 +70,9 @@ def main():
     ap.add_argument("--general", action="store_true", help="force the general two-pass scoring kernels")
     ap.add_argument("--cpu-sample-layers", type=int, default=4)
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="also launch a plain device copy of MIB MiB three times outside the timed region, so a "
+                         "counter run of this command shows what FETCH_SIZE/WRITE_SIZE read for known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives are part of it); use --gpus 1",
@@ -108,6 +122,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.empty(args.calibrate_copy << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -140,7 +161,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+            "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(args.workload, args.general),
             "kernel": "sp_score (all its launches)", "avg_ms": score_avg_ms, "median_ms": score_ms[len(score_ms) // 2],
             "algorithmic_bytes": algo_bytes,
         },
