@@ -54,7 +54,7 @@ constexpr int kSpinBudget = 1 << 16;  // polls per wave over the whole call befo
 constexpr int kDepSlotBytes = 8 * 32 * 8;  // one slab's deposits: 8 waves x 32 rows x (max, sum)
 
 struct StreamDev {
-  int M, L, N, H, G, lgG, S, slabs_per_layer, n_slabs, KPW, nwg, wpr, layer_reduce;
+  int M, L, N, H, G, lgG, S, slabs_per_layer, n_slabs, KPW, lgKPW, nwg, wpr, layer_reduce;
   float c;  // scale * log2(e): logits are handled in the base-2 domain
   int64_t ts, hs;
   const uint16_t* q;
@@ -114,8 +114,9 @@ __device__ __forceinline__ uint64_t lds_peek64(uint32_t lds_addr) {
   asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
   return v;
 }
+template <int OFF>
 __device__ __forceinline__ void lds_poke64(uint32_t lds_addr, uint64_t v) {
-  asm volatile("ds_write_b64 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
+  asm volatile("ds_write_b64 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
 }
 __device__ __forceinline__ void lds_add(uint32_t lds_addr, uint32_t v) {
   asm volatile("ds_add_u32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
@@ -124,10 +125,17 @@ template <int OFF>
 __device__ __forceinline__ void lds_fmax(uint32_t lds_addr, float v) {
   asm volatile("ds_max_f32 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
 }
-// register i of a 32x32 accumulator tile holds key (i / 4) * 8 + (i % 4) (+ 4 for the upper half-wave)
+// Register i of a 32x32 accumulator tile holds key (i / 4) * 8 + (i % 4) (+ 4 for the upper
+// half-wave).  In the running-max array that key sits at cell (i / 4) * 8 + (i % 4) * 2 (+ 1 for
+// the upper half-wave) of its tile, and query rows are kSmaxPad cells apart modulo 32: the 16
+// lanes of one atomic (8 queries x 2 half-waves) then fall into 16 different LDS banks.
+constexpr int kSmaxPad = 2;
+__device__ __forceinline__ int smax_cell(int key) {  // key within the workgroup's slice -> cell in a row
+  return (key & ~7) | ((key & 3) << 1) | ((key >> 2) & 1);
+}
 template <int... I>
 __device__ __forceinline__ void lds_fmax_tile(uint32_t lds_addr, const float (&x)[16], std::integer_sequence<int, I...>) {
-  (lds_fmax<((I >> 2) * 8 + (I & 3)) * 4>(lds_addr, x[I]), ...);
+  (lds_fmax<((I >> 2) * 8 + (I & 3) * 2) * 4>(lds_addr, x[I]), ...);
 }
 
 // max with the value of lane ^ 1 / lane ^ 2 (inside the quad); folds into v_max_f32_dpp
@@ -159,7 +167,7 @@ struct Streamer {
   static constexpr int RED_KB = NSETS >= 4 ? 0 : (TPW >= 2 ? TPW / 2 - 1 : 0);
 
   const StreamDev& p;
-  float* smax;           // [N][KPW] running max of log2-probabilities
+  float* smax;           // [N][KPW + kSmaxPad] running max of log2-probabilities (cells: smax_cell)
   int wave, lane, half, col, wg;
   int kvh_local, kbg;
   int keys_wg;           // valid keys owned by this workgroup
@@ -212,7 +220,7 @@ struct Streamer {
 
   static size_t smem_bytes(int n_queries, int kpw) {
     return (size_t)kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 512 +
-           (size_t)n_queries * kpw * sizeof(float);
+           (size_t)n_queries * (kpw + kSmaxPad) * sizeof(float);
   }
 
   __device__ __forceinline__ static __attribute__((address_space(3))) void* lds_ptr(uint32_t addr) {
@@ -291,8 +299,10 @@ struct Streamer {
   }
 
   __device__ __forceinline__ bf16x8 read_unit(int t, int slot) const {
+    uint32_t base = rd0;
+    asm volatile("" : "+v"(base));  // one XOR per read beats KS addresses held in registers all along
     return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-        lds_ptr((rd0 ^ (uint32_t)(t << 5)) + slot * TILE_B));
+        lds_ptr((base ^ (uint32_t)(t << 5)) + slot * TILE_B));
   }
 
   __device__ __forceinline__ void read_queries(int slot) {
@@ -303,8 +313,20 @@ struct Streamer {
   template <int SET>
   __device__ __forceinline__ void mfma_tile(int kb, int slot) {
     f32x16 a = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    bf16x8 kf[KS];
 #pragma unroll
-    for (int t = 0; t < KS; ++t) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_unit(t, slot), qf[t], a, 0, 0, 0);
+    for (int t = 0; t < KS; ++t) kf[t] = read_unit(t, slot);
+#pragma unroll
+    for (int t = 0; t < KS; ++t) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], a, 0, 0, 0);
+    // operand reads run kAhead steps ahead of the matrix instructions that use them
+    constexpr int kAhead = KS < 4 ? KS : 4;
+    __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+    for (int t = 0; t < KS - kAhead; ++t) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
     acc[SET][kb] = a;
   }
 
@@ -328,11 +350,18 @@ struct Streamer {
     const float m_new = fmaxf(run_m, tm);
     const float ref = (m_new == -INFINITY) ? 0.f : m_new;
     const float off = -ref * p.c;
-    float s = run_s * fast_exp2(fmaf(run_m, p.c, off));
+    // four independent chains: the exponentials are long-latency and a single chain would
+    // serialise on them
+    float s0 = run_s * fast_exp2(fmaf(run_m, p.c, off)), s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s += fast_exp2(fmaf(a[i], p.c, off));
+    for (int i = 0; i < 16; i += 4) {
+      s0 += fast_exp2(fmaf(a[i], p.c, off));
+      s1 += fast_exp2(fmaf(a[i + 1], p.c, off));
+      s2 += fast_exp2(fmaf(a[i + 2], p.c, off));
+      s3 += fast_exp2(fmaf(a[i + 3], p.c, off));
+    }
     run_m = m_new;
-    run_s = s;
+    run_s = (s0 + s1) + (s2 + s3);
   }
 
   // fold two (max, sum) pairs
@@ -345,12 +374,14 @@ struct Streamer {
 
   // Hop 1, sending side.  Deposit this wave's (max, sum) of each of its 32 rows in LDS and count
   // the arrival.
-  __device__ __forceinline__ void deposit(int slab) {
+  template <int SET>
+  __device__ __forceinline__ void deposit() {
     float m = run_m, s = run_s;
     fold(m, s, __shfl_xor(run_m, 32, kWave), __shfl_xor(run_s, 32, kWave));
-    const int set = slab % NSETS;
-    if (half == 0) lds_poke64(dep_lds + set * kDepSlotBytes + (wave * 32 + col) * 8, pack_stat(m, s));
-    if (lane == 0) lds_add(cnt_lds + set * 4, 1);
+    uint32_t dst = dep_lds + (wave * 32 + col) * 8;
+    asm volatile("" : "+v"(dst));  // one address plus an immediate per set, not NSETS addresses kept alive
+    if (half == 0) lds_poke64<SET * kDepSlotBytes>(dst, pack_stat(m, s));
+    if (lane == 0) lds_add(cnt_lds + SET * 4, 1);
   }
 
   // Slab t is published by wave t % 8 once all 8 waves have deposited it: the rows shared by
@@ -447,7 +478,7 @@ struct Streamer {
   __device__ __forceinline__ void finish_tiles(float neg_lse) {
     const bool writer = col < p.G * p.N && (col & (p.G - 1)) == 0;
     // LDS address of this lane's first key of tile 0 in its query's row of smax
-    const uint32_t dst0 = lds_addr_of(smax + (col >> LG) * p.KPW + kbg * TPW * 32 + half * 4);
+    const uint32_t dst0 = lds_addr_of(smax + (col >> LG) * (p.KPW + kSmaxPad) + kbg * TPW * 32 + half);
 #pragma unroll
     for (int kb = 0; kb < TPW; ++kb) {
       float x[16];
@@ -487,17 +518,18 @@ struct Streamer {
   }
 };
 
-template <int D, int TPW>
+template <int D, int TPW, bool MEAN>
 __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev p) {
   extern __shared__ __align__(1024) unsigned char smem[];
   using St = Streamer<D, TPW>;
   constexpr int NSETS = St::NSETS, TPS = St::TPS;
   St st(p, smem);
   const int cells = p.N * p.KPW;  // (query, key) cells of this workgroup
-  float tot[8];                   // layer-mean mode: sum over layers, cell = threadIdx + 512*j
+  auto cell_at = [&](int c) { return st.smax + c + kSmaxPad * (c >> p.lgKPW); };  // skips the row padding
+  float tot[MEAN ? 8 : 1];        // layer-mean mode: sum over layers, cell = threadIdx + 512*j
 #pragma unroll
-  for (int j = 0; j < 8; ++j) tot[j] = 0.f;
-  for (int i = threadIdx.x; i < cells; i += kThreads) st.smax[i] = -INFINITY;
+  for (int j = 0; j < (MEAN ? 8 : 1); ++j) tot[j] = 0.f;
+  for (int i = threadIdx.x; i < cells; i += kThreads) *cell_at(i) = -INFINITY;
   if (threadIdx.x < 16) *reinterpret_cast<uint32_t*>(smem + kWaves * 2 * St::TILE_B + NSETS * kDepSlotBytes + threadIdx.x * 4) = 0;
   __syncthreads();
 
@@ -505,15 +537,15 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
   // than the last), fold the layer's maxima into the running sums.  Needs every wave's
   // contribution, hence the workgroup barriers; the condition is the same in every wave.
   auto close_layer = [&](int done) {
-    if (p.layer_reduce == SP_LAYER_MEAN && (done + 1) % p.slabs_per_layer == 0 && done + 1 < p.n_slabs) {
+    if (MEAN && (done + 1) % p.slabs_per_layer == 0 && done + 1 < p.n_slabs) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
       __syncthreads();
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
+      for (int j = 0; j < (MEAN ? 8 : 1); ++j) {
         const int cell = threadIdx.x + kThreads * j;
         if (cell < cells) {
-          tot[j] += fast_exp2(__uint_as_float(lds_peek(St::lds_addr_of(st.smax + cell))));
-          st.smax[cell] = -INFINITY;
+          tot[j] += fast_exp2(__uint_as_float(lds_peek(St::lds_addr_of(cell_at(cell)))));
+          *cell_at(cell) = -INFINITY;
         }
       }
       __syncthreads();
@@ -557,7 +589,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
       if (kb == St::RED_KB && slab >= St::RED_LAG) st.reduce_rows(slab - St::RED_LAG);
       st.template stats_tile<SET>(kb);
     }
-    st.deposit(slab);
+    st.template deposit<SET>();
   };
 
   for (int s0 = 0; s0 < p.n_slabs; s0 += NSETS) {
@@ -598,21 +630,21 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
 
   int nv = p.n_valid ? p.n_valid[0] : p.N;
   nv = max(1, min(nv, p.N));
-  if (p.layer_reduce == SP_LAYER_MEAN) {
+  if (MEAN) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < (MEAN ? 8 : 1); ++j) {
       const int cell = threadIdx.x + kThreads * j;
-      if (cell < cells) st.smax[cell] = tot[j] + fast_exp2(st.smax[cell]);  // + the last layer
+      if (cell < cells) *cell_at(cell) = tot[j] + fast_exp2(*cell_at(cell));  // + the last layer
     }
     __syncthreads();
   }
   for (int key = threadIdx.x; key < st.keys_wg; key += kThreads) {
     float sum = 0.f;
     for (int n = 0; n < nv; ++n) {
-      const float v = st.smax[n * p.KPW + key];
-      sum += (p.layer_reduce == SP_LAYER_MEAN) ? v : fast_exp2(v);
+      const float v = st.smax[n * (p.KPW + kSmaxPad) + smax_cell(key)];
+      sum += MEAN ? v : fast_exp2(v);
     }
-    const float denom = (p.layer_reduce == SP_LAYER_MEAN) ? (float)nv * (float)p.L : (float)nv;
+    const float denom = MEAN ? (float)nv * (float)p.L : (float)nv;
     p.scores[(int64_t)blockIdx.x * p.KPW + key] = sum / denom;
   }
   if (st.budget <= 0 && st.lane == 0) atomicOr(p.status, 1u);
@@ -656,10 +688,10 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   int kb2 = 1;
   while (kb2 < kb) kb2 <<= 1;
   if (kb2 > 16) return pl;  // beyond 16 key blocks per workgroup the slabs no longer fit
-  // S * kb2 = 8 * TPW with S in {1,2,4,8} and TPW in {1,2,4}: start from the preferred TPW and
+  // S * kb2 = 8 * TPW with S in {1,2,4,8} and TPW in {1,2}: start from the preferred TPW and
   // move it into range
   int tpw = SP_STREAM_TPW_PREF;
-  while (tpw < 4 && 8 * tpw < kb2) tpw <<= 1;
+  while (tpw < 2 && 8 * tpw < kb2) tpw <<= 1;
   while (tpw > 1 && 8 * tpw / kb2 > 8) tpw >>= 1;
   const int S = 8 * tpw / kb2;
   if (S < 1 || S > 8 || S * kb2 != 8 * tpw) return pl;
@@ -674,7 +706,7 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   pl.partial_bytes = align_up(pl.rows * nwg * sizeof(uint64_t), 256);
   pl.lse_bytes = align_up(pl.rows * sizeof(uint32_t), 256);
   pl.smem_bytes = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)(8 / tpw) * kDepSlotBytes + 64 + kWaves * 512 +
-                  (size_t)a->N * pl.KPW * sizeof(float);
+                  (size_t)a->N * (pl.KPW + kSmaxPad) * sizeof(float);
   if (pl.smem_bytes > 160 * 1024) return pl;
   if ((size_t)a->N * pl.KPW > 8 * kThreads) return pl;
   pl.ok = true;
@@ -695,9 +727,9 @@ size_t stream_status_offset(const sp_score_args* a) {
   return pl.ok ? pl.partial_bytes + pl.lse_bytes : 0;
 }
 
-template <int D, int TPW>
+template <int D, int TPW, bool MEAN>
 static sp_status launch_stream(const StreamDev& dev, const StreamPlan& pl, hipStream_t stream) {
-  auto kernel = stream_score_kernel<D, TPW>;
+  auto kernel = stream_score_kernel<D, TPW, MEAN>;
   // once per kernel: allow the large dynamic LDS size and make sure one workgroup fits on a CU
   static int prepared_for = -1;
   if (prepared_for < (int)pl.smem_bytes) {
@@ -721,6 +753,8 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   dev.M = (int)a->T; dev.L = a->L; dev.N = a->N; dev.H = a->H; dev.G = a->H / a->H_kv; dev.S = pl.S;
   dev.lgG = dev.G == 1 ? 0 : dev.G == 2 ? 1 : dev.G == 4 ? 2 : 3;
   dev.slabs_per_layer = pl.slabs_per_layer; dev.n_slabs = pl.n_slabs; dev.KPW = pl.KPW; dev.nwg = pl.nwg;
+  dev.lgKPW = 0;
+  while ((1 << dev.lgKPW) < pl.KPW) ++dev.lgKPW;
   dev.wpr = pl.wpr; dev.layer_reduce = a->layer_reduce;
   dev.c = a->scale * 1.4426950408889634f;
   dev.ts = a->k_token_stride; dev.hs = a->k_head_stride;
@@ -739,18 +773,13 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   hipLaunchKernelGGL(fill_empty_kernel, dim3(fill_blocks), dim3(256), 0, stream, reinterpret_cast<uint4*>(ws),
                      n_vec, dev.status);
   if (hipGetLastError() != hipSuccess) return SP_ELAUNCH;
+  const bool mean = a->layer_reduce == SP_LAYER_MEAN;
   if (a->d == 128) {
-    switch (pl.TPW) {
-      case 1: return launch_stream<128, 1>(dev, pl, stream);
-      case 2: return launch_stream<128, 2>(dev, pl, stream);
-      default: return launch_stream<128, 4>(dev, pl, stream);
-    }
+    if (pl.TPW == 1) return mean ? launch_stream<128, 1, true>(dev, pl, stream) : launch_stream<128, 1, false>(dev, pl, stream);
+    return mean ? launch_stream<128, 2, true>(dev, pl, stream) : launch_stream<128, 2, false>(dev, pl, stream);
   }
-  switch (pl.TPW) {
-    case 1: return launch_stream<64, 1>(dev, pl, stream);
-    case 2: return launch_stream<64, 2>(dev, pl, stream);
-    default: return launch_stream<64, 4>(dev, pl, stream);
-  }
+  if (pl.TPW == 1) return mean ? launch_stream<64, 1, true>(dev, pl, stream) : launch_stream<64, 1, false>(dev, pl, stream);
+  return mean ? launch_stream<64, 2, true>(dev, pl, stream) : launch_stream<64, 2, false>(dev, pl, stream);
 }
 
 }  // namespace sp
