@@ -18,6 +18,9 @@ HIPCC_FLAGS = [
     "-fno-honor-nans",
     # packed fp32 VALU forms are kept off on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the kernel-argument struct is read through a by-value copy; without this the copy stays in
+    # scratch memory once a kernel has more than 300 reads of it
+    "-mllvm", "-instcombine-max-copied-from-constant-users=1000000",
     "-Wall", "-Wno-unused-function",
 ]
 

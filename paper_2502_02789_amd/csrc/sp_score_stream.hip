@@ -22,12 +22,17 @@
 //     is what lets a constant "s_waitcnt vmcnt(LOADS)" stand for "everything older than the
 //     youngest tile has landed" (plain loads and stores would force full drains);
 //   * exchange, hop 1: per slab every wave deposits, for each of its rows, (max, sum 2^(x-max))
-//     over its keys in LDS; one wave (rotating) merges the workgroup's rows once all eight
-//     deposits are in and publishes them (64-byte chunks of 8 rows).  A designated workgroup per
-//     group of 8 rows reads all workgroups' chunks, folds them into the rows' log-sum-exp and
-//     publishes that;
+//     over its keys in LDS; the wave that deposits last merges the workgroup's rows into one
+//     log-sum-exp per row and publishes them, 16 bytes per four rows (every coherent access
+//     costs the chip's memory pipeline a little, so a publication is as small as it can be).  For every four rows one wave of one workgroup (both rotating) is the
+//     reducer: it samples all workgroups' values with four direct-to-LDS gathers, and once none
+//     of them is empty folds them into the four rows' log-sum-exps and publishes those;
 //   * exchange, hop 2: each wave fetches the 32 log-sum-exps of its rows with one more
-//     direct-to-LDS load, issued one tile ahead so that the ordinary tile wait covers it;
+//     direct-to-LDS load, issued one tile before they are needed;
+//   * nothing of this is ever waited for through vmcnt: a sample's LDS landing zone is filled
+//     with a "pending" pattern before the load is issued and simply looked at later, so the
+//     stream of key tiles is never drained for the exchange.  vmcnt waits are for key/query
+//     tiles only and count exactly the instructions issued after the tile waited for;
 //   * with the log-sum-exp known a slab's logits become log2-probabilities; the max over the
 //     heads of a KV group is a quad DPP max, the max over KV heads / layers an LDS float
 //     atomic max per (query, key); the layer mean (if asked) and the query mean are taken at
@@ -35,7 +40,8 @@
 //
 // Cross-workgroup words are "empty" (all ones) until written, and are written and read with
 // agent-scope coherence; a small kernel refills the workspace with the empty pattern at the
-// start of each call.  Every wait is bounded (a status word records an expired wait).  The grid
+// start of each call.  Every wait is bounded (a status word records an expired wait), and a
+// wave that waits keeps serving its own reducer duty, so waiting waves cannot starve each other.  The grid
 // is one workgroup per CU, each needing more than half of a CU's LDS, so all of them are
 // resident together on an otherwise idle device; that residency is what every wait relies on.
 #include "sp_score_internal.h"
@@ -48,18 +54,19 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * kWave;
 constexpr int kMaxWG = 256;
-constexpr uint64_t kEmpty64 = ~0ull;
 constexpr uint32_t kEmpty32 = ~0u;
+constexpr uint32_t kPending32 = ~0u - 1;  // in an LDS landing zone: the sample has not arrived yet
+constexpr int kStageBytes = kMaxWG * 16;  // landing zone of a reducer's sample: 4 rows x 4 bytes per workgroup
 constexpr int kSpinBudget = 1 << 16;  // polls per wave over the whole call before giving up (~0.1 s)
 constexpr int kDepSlotBytes = 8 * 32 * 8;  // one slab's deposits: 8 waves x 32 rows x (max, sum)
 
 struct StreamDev {
-  int M, L, N, H, G, lgG, S, slabs_per_layer, n_slabs, KPW, lgKPW, nwg, wpr, layer_reduce;
+  int M, L, N, H, G, lgG, S, lgS, slabs_per_layer, lgSPL, n_slabs, KPW, lgKPW, nwg, wpr, layer_reduce;  // S, slabs_per_layer: powers of two
   float c;  // scale * log2(e): logits are handled in the base-2 domain
   int64_t ts, hs;
   const uint16_t* q;
   const int32_t* n_valid;
-  uint64_t* partial;  // [row / 8][nwg][row % 8]
+  uint32_t* partial;  // [quad of rows][nwg][4]: each workgroup's log-sum-exp (base 2) of the quad's rows
   uint32_t* lse2;     // [rows]
   uint32_t* status;   // [0] != 0: a bounded wait ran out (results invalid)
   float* scores;
@@ -81,23 +88,21 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-__device__ __forceinline__ uint64_t poll64(const uint64_t* p, int& budget) {
-  uint64_t v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  while (v == kEmpty64 && budget > 0) {
-    __builtin_amdgcn_s_sleep(2);
-    --budget;
-    v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// "at most n vector-memory instructions of this wave still in flight", n known only at run time.
+// Rounded down to a value there is an instruction for (stricter than asked is always correct).
+__device__ __forceinline__ void wait_vmcnt_upto(int n) {
+  if (n >= 12) {
+    if (n >= 16) wait_vmcnt<16>();
+    else if (n >= 14) { if (n >= 15) wait_vmcnt<15>(); else wait_vmcnt<14>(); }
+    else { if (n >= 13) wait_vmcnt<13>(); else wait_vmcnt<12>(); }
+  } else if (n >= 8) {
+    if (n >= 10) { if (n >= 11) wait_vmcnt<11>(); else wait_vmcnt<10>(); }
+    else { if (n >= 9) wait_vmcnt<9>(); else wait_vmcnt<8>(); }
+  } else if (n >= 4) {
+    wait_vmcnt<4>();
+  } else {
+    wait_vmcnt<0>();
   }
-  return v;
-}
-__device__ __forceinline__ uint32_t poll32(const uint32_t* p, int& budget) {
-  uint32_t v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  while (v == kEmpty32 && budget > 0) {
-    __builtin_amdgcn_s_sleep(2);
-    --budget;
-    v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  return v;
 }
 
 // LDS accesses the compiler does not see as such.  The words touched this way (deposits, counters,
@@ -109,17 +114,32 @@ __device__ __forceinline__ uint32_t lds_peek(uint32_t lds_addr) {
   asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
   return v;
 }
-__device__ __forceinline__ uint64_t lds_peek64(uint32_t lds_addr) {
-  uint64_t v;
-  asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
+__device__ __forceinline__ u32x4 lds_peek128(uint32_t lds_addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
   return v;
+}
+__device__ __forceinline__ void lds_poke32(uint32_t lds_addr, uint32_t v) {
+  asm volatile("ds_write_b32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_poke128(uint32_t lds_addr, u32x4 v) {
+  asm volatile("ds_write_b128 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_add(uint32_t lds_addr, uint32_t v) {
+  asm volatile("ds_add_u32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_add_rtn(uint32_t lds_addr, uint32_t v) {
+  uint32_t old;
+  asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(old) : "v"(lds_addr), "v"(v) : "memory");
+  return old;
+}
+// 16-byte store with agent-scope coherence (written through to where every XCD can see it)
+__device__ __forceinline__ void store128_agent(void* dst, u32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(v) : "memory");
 }
 template <int OFF>
 __device__ __forceinline__ void lds_poke64(uint32_t lds_addr, uint64_t v) {
   asm volatile("ds_write_b64 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
-}
-__device__ __forceinline__ void lds_add(uint32_t lds_addr, uint32_t v) {
-  asm volatile("ds_add_u32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
 }
 template <int OFF>
 __device__ __forceinline__ void lds_fmax(uint32_t lds_addr, float v) {
@@ -160,11 +180,9 @@ struct Streamer {
   static constexpr int UNITS = ROW_B / 16;     // 16-byte units per row
   static constexpr int LOADS = TILE_B / 1024;  // wave-wide 16-byte loads per tile
   static constexpr int RPI = 64 / UNITS;       // rows covered by one such load
-  // slab s: published at the end of its own streaming, reduced while slab s + RED_LAG streams,
-  // its log-sum-exps requested at the end of slab s + NSETS - 1, finished at the start of
-  // slab s + NSETS (just before its register set is reused)
-  static constexpr int RED_LAG = NSETS >= 4 ? NSETS / 2 : 1;
-  static constexpr int RED_KB = NSETS >= 4 ? 0 : (TPW >= 2 ? TPW / 2 - 1 : 0);
+  // slab s: published by the last wave to finish it, reduced by its reducers as soon as every
+  // workgroup's words are seen, its log-sum-exps requested at the end of slab s + NSETS - 1 and
+  // used at the start of slab s + NSETS (just before its register set is reused)
 
   const StreamDev& p;
   float* smax;           // [N][KPW + kSmaxPad] running max of log2-probabilities (cells: smax_cell)
@@ -172,11 +190,16 @@ struct Streamer {
   int kvh_local, kbg;
   int keys_wg;           // valid keys owned by this workgroup
   int budget;
-  int pub_next;          // next slab this wave has to publish (slab % 8 == wave)
+  int issued;            // vector-memory instructions issued so far by this wave (never over-counted)
+  int seq0, seq1;        // value of `issued` right after the loads of the tile in ring slot 0 / 1
+  int duty_k, duty_q;    // reducer rotation: this workgroup reduces quad duty_k of the slab if duty_k < quads
+  int red_quad;          // quad of rows (counted over the whole call) this wave still has to reduce, or -1
+  int red_turn;          // its number among this workgroup's duties (they share one landing zone, in turn)
   uint32_t ring_lds;     // LDS byte address of this wave's two-slot ring
   uint32_t dep_lds;      // LDS: [NSETS][8 waves][32 rows] (max, sum) deposits
-  uint32_t cnt_lds;      // LDS: [NSETS] arrival counters
-  uint32_t lse_lds;      // LDS: this wave's [2][64] fetched log-sum-exps
+  uint32_t cnt_lds;      // LDS: [NSETS] arrival counters; word 15: number of finished reducer duties
+  uint32_t lse_lds;      // LDS: this wave's [2][32] fetched log-sum-exps
+  uint32_t stage_lds;    // LDS: landing zone of a reducer sample (one per workgroup)
   uint32_t rd0;          // LDS byte address of this lane's operand unit for k-step 0 in slot 0
   uint32_t ld_off[4];    // per-lane global byte offset of key load j (depends on j & 3 only)
   bf16x8 qf[KS];
@@ -193,17 +216,23 @@ struct Streamer {
     half = lane >> 5;
     col = lane & 31;
     wg = blockIdx.x;
-    kvh_local = wave % p.S;
-    kbg = wave / p.S;
+    kvh_local = wave & (p.S - 1);
+    kbg = wave >> p.lgS;
     const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem);
     ring_lds = smem_lds + wave * 2 * TILE_B;
     dep_lds = smem_lds + kWaves * 2 * TILE_B;
     cnt_lds = dep_lds + NSETS * kDepSlotBytes;
-    lse_lds = cnt_lds + 64 + wave * 512;
-    smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 512);
+    lse_lds = cnt_lds + 64 + wave * 256;
+    stage_lds = cnt_lds + 64 + kWaves * 256;
+    smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 256 + kStageBytes);
     keys_wg = max(0, min(p.KPW, p.M - wg * p.KPW));
     budget = kSpinBudget;
-    pub_next = wave;
+    issued = 0;
+    seq0 = seq1 = 0;
+    duty_k = wg;
+    duty_q = 0;
+    red_quad = -1;
+    red_turn = 0;
     // operand read: unit (2t + half) of row col lives at position (2t + half) ^ key(col)
     //             = 2 * (t ^ (key >> 1)) + (half ^ (key & 1)), so the address is rd0 ^ (t << 5)
     const int key = (D == 128) ? (col & 15) : ((col >> 1) & 7);
@@ -219,7 +248,7 @@ struct Streamer {
   }
 
   static size_t smem_bytes(int n_queries, int kpw) {
-    return (size_t)kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 512 +
+    return (size_t)kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 256 + kStageBytes +
            (size_t)n_queries * (kpw + kSmaxPad) * sizeof(float);
   }
 
@@ -230,9 +259,9 @@ struct Streamer {
     return (uint32_t)reinterpret_cast<uintptr_t>(generic);
   }
 
-  __device__ __forceinline__ int layer_of(int slab) const { return slab / p.slabs_per_layer; }
-  __device__ __forceinline__ int kvh_of(int slab) const { return (slab % p.slabs_per_layer) * p.S + kvh_local; }
-  __device__ __forceinline__ int row_base(int slab) const { return (slab * p.S + kvh_local) * 32; }
+  __device__ __forceinline__ int layer_of(int slab) const { return slab >> p.lgSPL; }
+  __device__ __forceinline__ int kvh_of(int slab) const { return ((slab & (p.slabs_per_layer - 1)) << p.lgS) + kvh_local; }
+  __device__ __forceinline__ int row_base(int slab) const { return ((slab << p.lgS) + kvh_local) * 32; }
 
   // Direct global->LDS load of one key tile into ring slot `slot`.  Always exactly LOADS
   // wave-wide loads (the vmcnt bookkeeping counts on it): rows beyond the prompt re-read row 0
@@ -249,12 +278,16 @@ struct Streamer {
     if (start_eff + 32 <= p.M) {  // whole tile inside the prompt
 #pragma unroll
       for (int j = 0; j < LOADS; ++j) {
-        const unsigned char* src = base + (int64_t)(j * RPI) * p.ts * 2 + (size_t)ld_off[j & 3];
+        uint32_t lane_off = ld_off[j & 3];
+        asm volatile("" : "+v"(lane_off));  // scalar row base + 32-bit lane offset; nothing 64-bit per lane to keep around
+        const unsigned char* src = base + (int64_t)(j * RPI) * p.ts * 2 + (size_t)lane_off;
         __builtin_amdgcn_global_load_lds(src, lds_ptr(dst + j * 1024), 16, 0, 0);
       }
     } else {
       const int rows_in = p.M - start_eff;  // 1..31
-      const int i = lane / UNITS;
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int i = ln / UNITS;
 #pragma unroll
       for (int j = 0; j < LOADS; ++j) {
         const bool in = j * RPI + i < rows_in;
@@ -273,12 +306,14 @@ struct Streamer {
     const uint32_t dst = ring_lds + slot * TILE_B;
     const unsigned char* base = reinterpret_cast<const unsigned char*>(p.q) +
                                 2 * (((int64_t)layer_of(slab) * p.N * p.H + kvh_of(slab) * p.G) * D);
-    const int i = lane / UNITS;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));  // per-load offsets are cheap to recompute and expensive to keep
+    const int i = ln / UNITS;
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
       const int r = j * RPI + i;
       const int key = (D == 128) ? (r & 15) : ((r >> 1) & 7);
-      const int unit = (lane % UNITS) ^ key;
+      const int unit = (ln % UNITS) ^ key;
       const int rr = r < rows ? r : 0;
       const uint32_t off = (uint32_t)((rr >> p.lgG) * p.H * ROW_B + (rr & (p.G - 1)) * ROW_B + unit * 16);
       __builtin_amdgcn_global_load_lds(base + off, lds_ptr(dst + j * 1024), 16, 0, 0);
@@ -296,7 +331,16 @@ struct Streamer {
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     const int s = min(slab + ADV, p.n_slabs - 1);
     if (I == 0) issue_queries(s, slot); else issue_keys(s, I - 1, slot);
+    note_issued(LOADS);
+    if (slot & 1) seq1 = issued; else seq0 = issued;
   }
+  // the tile in ring slot `slot` has landed once at most the instructions issued after its
+  // loads are still in flight (vector-memory instructions of a wave complete in order)
+  __device__ __forceinline__ void wait_tile(int slot) {
+    wait_vmcnt_upto(__builtin_amdgcn_readfirstlane(issued - ((slot & 1) ? seq1 : seq0)));
+  }
+  // the bookkeeping is wave-uniform; saying so keeps it in scalar registers
+  __device__ __forceinline__ void note_issued(int k) { issued = __builtin_amdgcn_readfirstlane(issued + k); }
 
   __device__ __forceinline__ bf16x8 read_unit(int t, int slot) const {
     uint32_t base = rd0;
@@ -340,9 +384,11 @@ struct Streamer {
     f32x16& a = acc[SET][kb];
     const int first = (kbg * TPW + kb) * 32;
     if (first + 32 > keys_wg) {  // ragged tail: keys beyond the prompt do not count
+      int left = keys_wg - first - half * 4;  // keys of this half-wave's first register still inside
+      asm volatile("" : "+v"(left));           // compare here, when needed: 16 hoisted lane masks would cost 32 SGPRs
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        if (key_of(kb, i) >= keys_wg) a[i] = -INFINITY;
+        if ((i >> 2) * 8 + (i & 3) >= left) a[i] = -INFINITY;
     }
     float tm = a[0];
 #pragma unroll
@@ -373,112 +419,191 @@ struct Streamer {
   }
 
   // Hop 1, sending side.  Deposit this wave's (max, sum) of each of its 32 rows in LDS and count
-  // the arrival.
+  // the arrival; the wave that arrives last publishes the slab (LDS operations of a wave are
+  // performed in order, so whoever sees the count complete also sees every deposit).
   template <int SET>
-  __device__ __forceinline__ void deposit() {
+  __device__ __forceinline__ void deposit(int slab) {
     float m = run_m, s = run_s;
     fold(m, s, __shfl_xor(run_m, 32, kWave), __shfl_xor(run_s, 32, kWave));
     uint32_t dst = dep_lds + (wave * 32 + col) * 8;
     asm volatile("" : "+v"(dst));  // one address plus an immediate per set, not NSETS addresses kept alive
     if (half == 0) lds_poke64<SET * kDepSlotBytes>(dst, pack_stat(m, s));
-    if (lane == 0) lds_add(cnt_lds + SET * 4, 1);
+    uint32_t old = 0;
+    if (lane == 0) old = lds_add_rtn(cnt_lds + SET * 4, 1);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if ((old & 7) == 7) publish(slab, dep_lds + SET * kDepSlotBytes);
   }
 
-  // Slab t is published by wave t % 8 once all 8 waves have deposited it: the rows shared by
-  // several waves are merged and the workgroup's S*32 rows go out as 64-byte chunks.  A fixed
-  // rotation (rather than "whoever deposits last") keeps the job off the wave that is already
-  // behind, and seven of eight waves issue no global store, which would linger in their vmcnt.
-  // Called at tile boundaries with `upto` = newest slab this wave has deposited; slabs up to
-  // `must` are waited for: this wave is about to block on something (a log-sum-exp, other
-  // workgroups' statistics) that cannot arrive before its own workgroup has published them.
-  __device__ __forceinline__ void service_publish(int upto, int must) {
-    while (pub_next <= upto) {
-      const int set = pub_next % NSETS;
-      const uint32_t need = 8u * (uint32_t)(pub_next / NSETS + 1);
-      uint32_t cnt = __builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + set * 4));
-      while (pub_next <= must && cnt < need && budget > 0) {
-        __builtin_amdgcn_s_sleep(1);
+  // Merge the deposits of the waves that share rows into one base-2 log-sum-exp per row and
+  // send the workgroup's S*32 rows out, four rows (16 bytes) per lane.  The words of one quad
+  // from all workgroups are neighbours in memory: the reducer's sample is one dense 4 KiB read
+  // (what is scattered is these writes, once; reads may have to be repeated).  Deposits are
+  // indexed [kbg * S + kvh_local][query row].
+  __device__ __forceinline__ void publish(int slab, uint32_t dep) {
+    const int quads = p.S * 8;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));  // address arithmetic of this rare path stays here instead of being hoisted
+    if (ln < quads) {
+      float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, z[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+      for (int g = 0; g < p.wpr; ++g) {
+        const uint32_t a = dep + ((g * p.S + (ln >> 3)) * 32 + (ln & 7) * 4) * 8;
+        const u32x4 w0 = lds_peek128(a), w1 = lds_peek128(a + 16);
+        fold(m[0], z[0], __uint_as_float(w0.x), __uint_as_float(w0.y));
+        fold(m[1], z[1], __uint_as_float(w0.z), __uint_as_float(w0.w));
+        fold(m[2], z[2], __uint_as_float(w1.x), __uint_as_float(w1.y));
+        fold(m[3], z[3], __uint_as_float(w1.z), __uint_as_float(w1.w));
+      }
+      // (-inf, 0) -- no key of the prompt in this workgroup -- gives -inf, which is a value, not "empty"
+      u32x4 out;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) out[r] = __float_as_uint(fmaf(m[r], p.c, __builtin_amdgcn_logf(z[r])));  // v_log_f32 is log2
+      store128_agent(p.partial + (((int64_t)slab * quads + ln) * p.nwg + wg) * 4, out);
+    }
+    note_issued(1);
+  }
+
+  // Reducer rotation.  Quad number x (four rows; counted over the whole call) is reduced by
+  // workgroup x % nwg, wave (x / nwg) % 8.  Called once per slab, in slab order, right after this wave
+  // has deposited the slab.
+  __device__ __forceinline__ void take_duty(int slab) {
+    const int quads = p.S * 8;
+    if (duty_k < quads && (duty_q & 7) == wave) {
+      while (red_quad >= 0 && budget > 0) {  // cannot happen unless the exchange is badly late
+        service_reduce();
+        __builtin_amdgcn_s_sleep(4);
         --budget;
-        cnt = __builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + set * 4));
       }
-      if (cnt < need) return;
-      const uint32_t dep = dep_lds + set * kDepSlotBytes;
-      const int rows = p.S * 32;
-      for (int r = lane; r < rows; r += kWave) {  // deposits are indexed [kbg * S + kvh_local][qrow]
-        float mm = -INFINITY, ss = 0.f;
-        for (int g = 0; g < p.wpr; ++g) {
-          const uint64_t w = lds_peek64(dep + ((g * p.S + (r >> 5)) * 32 + (r & 31)) * 8);
-          fold(mm, ss, __uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32)));
-        }
-        const int row = pub_next * rows + r;
-        uint64_t* dst = p.partial + ((int64_t)(row >> 3) * p.nwg + wg) * 8 + (row & 7);
-        __hip_atomic_store(dst, pack_stat(mm, ss), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      red_quad = slab * quads + duty_k;
+      red_turn = duty_q;
       }
-      pub_next += kWaves;
+    duty_k -= quads;
+    if (duty_k < 0) {
+      duty_k += p.nwg;
+      ++duty_q;
     }
   }
 
-  // Hop 1, receiving side.  If this workgroup is responsible for a group of 8 rows of the slab,
-  // fold all workgroups' (max, sum) of those rows (one row per wave) into the rows' log-sum-exp
-  // and publish them.
-  __device__ __forceinline__ void reduce_rows(int slab) {
-    const int groups = p.S * 4;  // row groups per slab
-    const int base = slab * groups;
-    const int rg = base + ((wg - base) % p.nwg + p.nwg) % p.nwg;
-    if (rg >= base + groups) return;
-    const int row = rg * 8 + wave;
-    const uint64_t* src = p.partial + (int64_t)rg * p.nwg * 8 + wave;
-    float m = -INFINITY, s = 0.f;
-    uint64_t w[kMaxWG / kWave];
+  // Hop 1, receiving side: one attempt.  Send a sample of the quad's nwg x 4 values on its way
+  // into the landing zone (marked "pending" first), watch the zone until every word has arrived
+  // -- LDS reads only, the key tiles in flight are not waited for -- and if no value is empty
+  // fold them into the four rows' log-sum-exps and publish those.  Otherwise try again a slab later.
+  __device__ __forceinline__ void service_reduce() {
+    if (red_quad < 0) return;
+    // the landing zone is the workgroup's only one: duties use it in turn
+    if ((int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 60)) != red_turn) return;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));  // address arithmetic of this rare path stays here instead of being hoisted
+    const int slab = red_quad >> (p.lgS + 3);
+    const int q4 = (red_quad - (slab << (p.lgS + 3))) * 4;  // first of the four rows, within the slab
+    const uint32_t* src = p.partial + (int64_t)red_quad * p.nwg * 4;
+    const u32x4 fill = {kPending32, kPending32, kPending32, kPending32};
+    const int groups = (p.nwg + kWave - 1) / kWave;
+#pragma unroll 1  // rare path: keep its register appetite small
+    for (int i = 0; i < groups; ++i) lds_poke128(stage_lds + (ln + i * kWave) * 16, fill);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the pattern is in place before any answer can land
 #pragma unroll
-    for (int j = 0; j < kMaxWG / kWave; ++j) {  // all of a lane's loads go out before any is looked at
-      const int e = lane + j * kWave;
-      w[j] = e < p.nwg ? __hip_atomic_load(src + (int64_t)e * 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                       : pack_stat(-INFINITY, 0.f);
-    }
-#pragma unroll
-    for (int j = 0; j < kMaxWG / kWave; ++j) {
-      if (w[j] == kEmpty64) w[j] = poll64(src + (int64_t)(lane + j * kWave) * 8, budget);
-      fold(m, s, __uint_as_float((uint32_t)w[j]), __uint_as_float((uint32_t)(w[j] >> 32)));
-    }
-    const float mw = wave_max(m);  // finite: the prompt is not empty
-    const float zw = wave_sum(s * fast_exp2((m - mw) * p.c));
-    if (lane == 0) {
-      const float lse2 = fmaf(mw, p.c, __builtin_amdgcn_logf(zw));  // v_log_f32 is log2
-      __hip_atomic_store(p.lse2 + row, __float_as_uint(lse2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (p.lse_out) {
-        const int in_slab = row - slab * p.S * 32;
-        const int qrow = in_slab & 31;
-        if (qrow < p.G * p.N) {
-          const int kvh = (slab % p.slabs_per_layer) * p.S + (in_slab >> 5);
-          p.lse_out[((int64_t)layer_of(slab) * p.N + (qrow >> p.lgG)) * p.H + kvh * p.G + (qrow & (p.G - 1))] =
-              lse2 * 0.6931471805599453f;
-        }
+    for (int i = 0; i < kMaxWG / kWave; ++i) {
+      if (i < groups) {
+        const int e = min(ln + i * kWave, p.nwg - 1);  // lanes past the end repeat the last workgroup
+        __builtin_amdgcn_global_load_lds(src + (int64_t)e * 4, lds_ptr(stage_lds + i * 1024), 16, 0, /*sc1*/ 16);
       }
     }
+    note_issued(groups);
+    bool pending, empty;
+    u32x4 w[kMaxWG / kWave];
+    do {
+      __builtin_amdgcn_s_sleep(8);
+      --budget;
+      pending = false, empty = false;
+#pragma unroll
+      for (int i = 0; i < kMaxWG / kWave; ++i) {
+        if (i < groups) {
+          w[i] = lds_peek128(stage_lds + (ln + i * kWave) * 16);
+          pending |= w[i].x == kPending32 || w[i].y == kPending32 || w[i].z == kPending32 || w[i].w == kPending32;
+          empty |= w[i].x == kEmpty32 || w[i].y == kEmpty32 || w[i].z == kEmpty32 || w[i].w == kEmpty32;
+        } else {
+          w[i] = u32x4{0xff800000u, 0xff800000u, 0xff800000u, 0xff800000u};  // -inf: contributes nothing
+        }
+      }
+    } while (__any(pending) && budget > 0);
+    if (__any(empty || pending)) return;
+    float lse4[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float v[kMaxWG / kWave];
+#pragma unroll
+      for (int i = 0; i < kMaxWG / kWave; ++i)  // lanes past the last workgroup hold a repeat: count it as nothing
+        v[i] = ln + i * kWave < p.nwg ? __uint_as_float(w[i][r]) : -INFINITY;
+      float m = v[0];
+#pragma unroll
+      for (int i = 1; i < kMaxWG / kWave; ++i) m = fmaxf(m, v[i]);
+      m = wave_max(m);  // finite: the prompt is not empty
+      float z = 0.f;
+#pragma unroll
+      for (int i = 0; i < kMaxWG / kWave; ++i) z += fast_exp2(v[i] - m);
+      lse4[r] = m + __builtin_amdgcn_logf(wave_sum(z));
+    }
+    if (ln == 0) {
+      const u32x4 out = {__float_as_uint(lse4[0]), __float_as_uint(lse4[1]), __float_as_uint(lse4[2]), __float_as_uint(lse4[3])};
+      store128_agent(p.lse2 + (int64_t)red_quad * 4, out);
+      if (p.lse_out) {
+        const int kvh = ((slab & (p.slabs_per_layer - 1)) << p.lgS) + (q4 >> 5);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int qrow = (q4 & 31) + r;
+          if (qrow < p.G * p.N)
+            p.lse_out[((int64_t)layer_of(slab) * p.N + (qrow >> p.lgG)) * p.H + kvh * p.G + (qrow & (p.G - 1))] =
+                lse4[r] * 0.6931471805599453f;
+        }
+      }
+      lds_add(cnt_lds + 60, 1);  // the landing zone is free for the workgroup's next duty
+    }
+    note_issued(1);  // (the optional log-sum-exp output is not counted: counting less only waits more)
+    red_quad = -1;
   }
 
   // Hop 2.  Request the log-sum-exps of this wave's 32 rows of the slab with one direct-to-LDS
-  // load (agent-coherent); it is older than the tile loads issued after it, so the next tile
-  // wait covers it.
+  // load (agent-coherent) into a landing zone marked "pending".  One request per slab: every
+  // coherent access costs the whole chip a little, repeats did not pay.
   __device__ __forceinline__ void request_lse(int slab) {
-    const uint32_t* src = p.lse2 + row_base(slab) + col;
-    __builtin_amdgcn_global_load_lds(src, lds_ptr(lse_lds + (slab & 1) * 256), 4, 0, /*sc1*/ 16);
+    int c = col;
+    asm volatile("" : "+v"(c));
+    if (half == 0) {
+      lds_poke32(lse_lds + (slab & 1) * 128 + c * 4, kPending32);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_global_load_lds(p.lse2 + row_base(slab) + c, lds_ptr(lse_lds + (slab & 1) * 128), 4, 0, /*sc1*/ 16);
+    }
+    note_issued(1);
   }
-  // The requested words have landed: take this lane's; if the exchange is late, poll for it.
+  // Take this lane's log-sum-exp.  Normally it is there; if the exchange is late, ask again
+  // whenever an answer came back empty, and keep this wave's own reducer duty going meanwhile
+  // (another wave may be waiting for exactly that).
   __device__ __forceinline__ float take_lse(int slab) {
-    uint32_t bits = lds_peek(lse_lds + (slab & 1) * 256 + lane * 4);
-    if (__builtin_expect(__any(bits == kEmpty32), 0)) bits = poll32(p.lse2 + row_base(slab) + col, budget);
+    int c = col;
+    asm volatile("" : "+v"(c));
+    const uint32_t addr = lse_lds + (slab & 1) * 128 + c * 4;
+    uint32_t bits = lds_peek(addr);
+    while (__any(bits == kPending32 || bits == kEmpty32) && budget > 0) {
+      if (!__any(bits == kPending32)) request_lse(slab);
+      service_reduce();
+      __builtin_amdgcn_s_sleep(4);
+      --budget;
+      bits = lds_peek(addr);
+    }
     return __uint_as_float(bits);
   }
 
   // Turn the stored logits of set SET into log2-probabilities and max them into smax: over the
   // heads of the KV group across lanes, over KV heads / layers in LDS.  LG = log2(group size).
-  template <int SET, int LG>
-  __device__ __forceinline__ void finish_tiles(float neg_lse) {
-    const bool writer = col < p.G * p.N && (col & (p.G - 1)) == 0;
+  template <int SET>
+  __device__ __forceinline__ void finish_set(float lse) {
+    const float neg_lse = -lse;
+    int c = col, h = half;
+    asm volatile("" : "+v"(c), "+v"(h));  // recompute the few lane-dependent values here rather than keep them all along
+    const bool writer = c < p.G * p.N && (c & (p.G - 1)) == 0;
     // LDS address of this lane's first key of tile 0 in its query's row of smax
-    const uint32_t dst0 = lds_addr_of(smax + (col >> LG) * (p.KPW + kSmaxPad) + kbg * TPW * 32 + half);
+    const uint32_t dst0 = lds_addr_of(smax + (c >> p.lgG) * (p.KPW + kSmaxPad) + kbg * TPW * 32 + h);
 #pragma unroll
     for (int kb = 0; kb < TPW; ++kb) {
       float x[16];
@@ -486,34 +611,26 @@ struct Streamer {
       // register would cost wait states
 #pragma unroll
       for (int i = 0; i < 16; ++i) x[i] = fmaf(acc[SET][kb][i], p.c, neg_lse);
-      if (LG >= 1) {
+      if (p.lgG >= 1) {  // group size is uniform: these are scalar branches around one copy of the code
 #pragma unroll
         for (int i = 0; i < 16; ++i) x[i] = max_quad_xor1(x[i]);
       }
-      if (LG >= 2) {
+      if (p.lgG >= 2) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) x[i] = max_quad_xor2(x[i]);
       }
-      if (LG >= 3) {
+      if (p.lgG >= 3) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) x[i] = fmaxf(x[i], __shfl_xor(x[i], 4, kWave));
       }
       const int first = (kbg * TPW + kb) * 32;
       if (first + 32 > keys_wg) {  // ragged tail: keys beyond the prompt never beat the -inf start value
+        const int left = keys_wg - first - h * 4;
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-          if (key_of(kb, i) >= keys_wg) x[i] = -INFINITY;
+          if ((i >> 2) * 8 + (i & 3) >= left) x[i] = -INFINITY;
       }
       if (writer) lds_fmax_tile(dst0 + kb * 128, x, std::make_integer_sequence<int, 16>{});
-    }
-  }
-  template <int SET>
-  __device__ __forceinline__ void finish_set(float lse) {
-    switch (p.lgG) {
-      case 0: finish_tiles<SET, 0>(-lse); break;
-      case 1: finish_tiles<SET, 1>(-lse); break;
-      case 2: finish_tiles<SET, 2>(-lse); break;
-      default: finish_tiles<SET, 3>(-lse); break;
     }
   }
 };
@@ -525,7 +642,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
   constexpr int NSETS = St::NSETS, TPS = St::TPS;
   St st(p, smem);
   const int cells = p.N * p.KPW;  // (query, key) cells of this workgroup
-  auto cell_at = [&](int c) { return st.smax + c + kSmaxPad * (c >> p.lgKPW); };  // skips the row padding
+  auto cell_at = [&](int c) __attribute__((always_inline)) { return st.smax + c + kSmaxPad * (c >> p.lgKPW); };  // skips the row padding
   float tot[MEAN ? 8 : 1];        // layer-mean mode: sum over layers, cell = threadIdx + 512*j
 #pragma unroll
   for (int j = 0; j < (MEAN ? 8 : 1); ++j) tot[j] = 0.f;
@@ -536,8 +653,15 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
   // layer-mean mode: slab `done` was just finished by this wave; if it closes a layer (other
   // than the last), fold the layer's maxima into the running sums.  Needs every wave's
   // contribution, hence the workgroup barriers; the condition is the same in every wave.
-  auto close_layer = [&](int done) {
-    if (MEAN && (done + 1) % p.slabs_per_layer == 0 && done + 1 < p.n_slabs) {
+  auto close_layer = [&](int done) __attribute__((always_inline)) {
+    if (MEAN && ((done + 1) & (p.slabs_per_layer - 1)) == 0 && done + 1 < p.n_slabs) {
+      // a wave parked at a barrier serves nobody: finish the reducer duty first (it only needs
+      // publications of slabs every wave of the grid has already left behind)
+      while (st.red_quad >= 0 && st.budget > 0) {
+        st.service_reduce();
+        __builtin_amdgcn_s_sleep(4);
+        --st.budget;
+      }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
       __syncthreads();
 #pragma unroll
@@ -556,27 +680,27 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
   st.template issue_stream<1>(0, 1);
 
   // One slab.  Stream tile x of the slab sits in ring slot (SET*TPS + x) & 1 (NSETS is even, so
-  // the slab's parity is SET's).  Before every use of a stream tile, "vmcnt <= LOADS" means: the
-  // LOADS loads of the one younger tile are the only ones that may still be in flight.
-  auto body = [&](auto set_tag, int slab) {
+  // the slab's parity is SET's).
+  auto body = [&](auto set_tag, int slab) __attribute__((always_inline)) {
     constexpr int SET = decltype(set_tag)::value;
     constexpr int SLOT0 = (SET * TPS) & 1;
-    wait_vmcnt<St::LOADS>();
-    // everything this wave may block on below (log-sum-exps of slab - NSETS, statistics of slab -
-    // RED_LAG) needs this workgroup's publications up to slab - RED_LAG
-    st.service_publish(slab - 1, slab - St::RED_LAG);
+    // The two waves that share a SIMD take turns at being the one the instruction arbiter
+    // prefers; left alone it favours the older wave throughout, and the slab is only published
+    // when the slowest wave is done with it.
+    if ((slab ^ (st.wave >> 2)) & 1) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(0);
+    st.wait_tile(SLOT0);
+    st.read_queries(SLOT0);
+    st.template issue_stream<2>(slab, SLOT0);
     if (slab >= NSETS) {  // set SET still holds slab - NSETS, whose log-sum-exps were requested a tile ago
       st.template finish_set<SET>(st.take_lse(slab - NSETS));
       close_layer(slab - NSETS);
     }
-    st.read_queries(SLOT0);
-    st.template issue_stream<2>(slab, SLOT0);
     st.run_m = -INFINITY;
     st.run_s = 0.f;
 #pragma unroll
     for (int kb = 0; kb < TPW; ++kb) {
       const int slot = (SLOT0 + 1 + kb) & 1;
-      wait_vmcnt<St::LOADS>();
+      st.wait_tile(slot);
       st.template mfma_tile<SET>(kb, slot);
       if (kb == TPW - 1 && slab + 1 >= NSETS) st.request_lse(slab + 1 - NSETS);
       switch (kb) {  // a compile-time constant after unrolling
@@ -585,11 +709,12 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
         case 2: st.template issue_stream<5>(slab, slot); break;
         default: st.template issue_stream<6>(slab, slot); break;
       }
-      if (kb == 0 && TPW > 1) st.service_publish(slab - 1, -1);
-      if (kb == St::RED_KB && slab >= St::RED_LAG) st.reduce_rows(slab - St::RED_LAG);
       st.template stats_tile<SET>(kb);
     }
-    st.template deposit<SET>();
+    st.template deposit<SET>(slab);
+    // reducer duty, once per slab and here, where the fewest registers are live
+    st.take_duty(slab);
+    st.service_reduce();
   };
 
   for (int s0 = 0; s0 < p.n_slabs; s0 += NSETS) {
@@ -609,10 +734,9 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
 
   // drain: the exchange of the last slabs cannot hide behind further streaming
   wait_vmcnt<0>();
-  st.service_publish(p.n_slabs - 1, p.n_slabs - 1);
-  for (int s = max(0, p.n_slabs - St::RED_LAG); s < p.n_slabs; ++s) st.reduce_rows(s);
   for (int s = max(0, p.n_slabs - NSETS); s < p.n_slabs; ++s) {
-    const float lse = __uint_as_float(poll32(p.lse2 + st.row_base(s) + st.col, st.budget));
+    st.request_lse(s);
+    const float lse = st.take_lse(s);
     switch (s % NSETS) {
       case 0: st.template finish_set<0>(lse); break;
       case 1: st.template finish_set<1 % NSETS>(lse); break;
@@ -624,6 +748,11 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
       default: st.template finish_set<7 % NSETS>(lse); break;
     }
     close_layer(s);
+  }
+  while (st.red_quad >= 0 && st.budget > 0) {  // nobody gets its log-sum-exps before this duty is done
+    st.service_reduce();
+    __builtin_amdgcn_s_sleep(4);
+    --st.budget;
   }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
   __syncthreads();
@@ -703,10 +832,11 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   pl.slabs_per_layer = a->H_kv / pl.S;
   pl.n_slabs = a->L * pl.slabs_per_layer;
   pl.rows = (size_t)a->L * a->H_kv * 32;
-  pl.partial_bytes = align_up(pl.rows * nwg * sizeof(uint64_t), 256);
+  if (pl.S * 8 > nwg) return pl;  // reducer rotation: at most one quad of rows per workgroup and slab
+  pl.partial_bytes = align_up(pl.rows * nwg * sizeof(uint32_t), 256);
   pl.lse_bytes = align_up(pl.rows * sizeof(uint32_t), 256);
-  pl.smem_bytes = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)(8 / tpw) * kDepSlotBytes + 64 + kWaves * 512 +
-                  (size_t)a->N * (pl.KPW + kSmaxPad) * sizeof(float);
+  pl.smem_bytes = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)(8 / tpw) * kDepSlotBytes + 64 + kWaves * 256 +
+                  kStageBytes + (size_t)a->N * (pl.KPW + kSmaxPad) * sizeof(float);
   if (pl.smem_bytes > 160 * 1024) return pl;
   if ((size_t)a->N * pl.KPW > 8 * kThreads) return pl;
   pl.ok = true;
@@ -752,6 +882,8 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   StreamDev dev;
   dev.M = (int)a->T; dev.L = a->L; dev.N = a->N; dev.H = a->H; dev.G = a->H / a->H_kv; dev.S = pl.S;
   dev.lgG = dev.G == 1 ? 0 : dev.G == 2 ? 1 : dev.G == 4 ? 2 : 3;
+  dev.lgS = pl.S == 1 ? 0 : pl.S == 2 ? 1 : pl.S == 4 ? 2 : 3;
+  dev.lgSPL = pl.slabs_per_layer == 1 ? 0 : pl.slabs_per_layer == 2 ? 1 : pl.slabs_per_layer == 4 ? 2 : 3;
   dev.slabs_per_layer = pl.slabs_per_layer; dev.n_slabs = pl.n_slabs; dev.KPW = pl.KPW; dev.nwg = pl.nwg;
   dev.lgKPW = 0;
   while ((1 << dev.lgKPW) < pl.KPW) ++dev.lgKPW;
@@ -761,7 +893,7 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   dev.q = static_cast<const uint16_t*>(a->d_q);
   dev.n_valid = a->d_n_valid;
   char* ws = static_cast<char*>(a->d_workspace);
-  dev.partial = reinterpret_cast<uint64_t*>(ws);
+  dev.partial = reinterpret_cast<uint32_t*>(ws);
   dev.lse2 = reinterpret_cast<uint32_t*>(ws + pl.partial_bytes);
   dev.status = reinterpret_cast<uint32_t*>(ws + pl.partial_bytes + pl.lse_bytes);
   dev.scores = a->d_scores; dev.lse_out = a->d_lse;
