@@ -44,9 +44,10 @@ __device__ __forceinline__ double shfl_f64(double v, int src) {
 
 // One wave serves a group of 64/chunk consecutive chunks (one chunk when chunk >= 64).
 // Lanes pool one token each; every lane then adds its chunk's pooled values in token order.
+template <bool SINGLE>  // SINGLE: one sequence of T tokens, no chunk table
 __global__ __launch_bounds__(256) void pool_chunk_kernel(const SelDev p) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int n_chunks = p.cu_chunks[p.B];
+  const int n_chunks = SINGLE ? (p.T + p.chunk - 1) / p.chunk : p.cu_chunks[p.B];
   const bool wide = p.chunk >= kWave;
   const int cpw = wide ? 1 : kWave / p.chunk;          // chunks per wave
   const int seg_len = wide ? kWave : p.chunk;          // tokens of a chunk handled per step
@@ -59,10 +60,15 @@ __global__ __launch_bounds__(256) void pool_chunk_kernel(const SelDev p) {
     const bool live = (q < cpw) && (j < n_chunks);
     int lo = 0, hi = 0, s0 = 0, s1 = 0;
     if (live) {
-      const int b = upper_segment(p.cu_chunks, p.B, j);
-      lo = p.cu[b];
-      hi = p.cu[b + 1];
-      s0 = lo + (j - p.cu_chunks[b]) * p.chunk;
+      if (SINGLE) {
+        hi = p.T;
+        s0 = j * p.chunk;
+      } else {
+        const int b = upper_segment(p.cu_chunks, p.B, j);
+        lo = p.cu[b];
+        hi = p.cu[b + 1];
+        s0 = lo + (j - p.cu_chunks[b]) * p.chunk;
+      }
       s1 = min(s0 + p.chunk, hi);
     }
     double tot = 0.0;
@@ -186,6 +192,86 @@ __global__ __launch_bounds__(1024) void select_kernel(const SelDev p) {
   if (t == 0) p.seq_keep[b] = total_tokens;
 }
 
+// Single sequence with at most kSingleMaxChunks chunks: top-k, compaction and the kept-index
+// list in one workgroup.  The chunks are sorted by (score descending, index ascending) with a
+// bitonic network in LDS, one compare-exchange per thread and stage; the k-th entry of the sorted
+// list is the threshold every chunk is then compared with.
+constexpr int kSingleMaxChunks = 2048;
+__global__ __launch_bounds__(1024) void select_emit_single_kernel(const SelDev p) {
+  __shared__ uint64_t keys[kSingleMaxChunks];
+  __shared__ uint16_t ids[kSingleMaxChunks];
+  __shared__ int sh[1024];
+  const int t = threadIdx.x;
+  const int M = p.T;
+  const int n = (M + p.chunk - 1) / p.chunk;
+  if (t == 0) p.cu_keep[0] = 0;
+  if (n == 0) {
+    if (t == 0) p.cu_keep[1] = 0;
+    return;
+  }
+  const double scaled = p.keep_rate * (double)n;
+  const double kd = ceil(scaled - 1e-9);
+  const int k = (int)fmin((double)n, fmax(1.0, kd));
+  int N = 2;
+  while (N < n) N <<= 1;
+  uint64_t mine[kSingleMaxChunks / 1024];
+#pragma unroll
+  for (int r = 0; r < kSingleMaxChunks / 1024; ++r) {
+    const int j = t + r * 1024;
+    mine[r] = j < n ? order_key(p.cs[j]) : 0;  // padding sorts last: key 0 is below every real key, index above
+    if (j < N) {
+      keys[j] = mine[r];
+      ids[j] = (uint16_t)j;
+    }
+  }
+  __syncthreads();
+  // "a goes before b"
+  auto before = [](uint64_t ka, int ia, uint64_t kb, int ib) { return ka > kb || (ka == kb && ia < ib); };
+  for (int size = 2; size <= N; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int e = t; e < N / 2; e += 1024) {
+        const int i = 2 * e - (e & (stride - 1));  // lower partner: bit `stride` clear
+        const int j = i + stride;
+        const bool ascending_block = (i & size) != 0;  // alternate blocks are sorted the other way round
+        const uint64_t ki = keys[i], kj = keys[j];
+        const int ii = ids[i], ij = ids[j];
+        const bool in_order = before(ki, ii, kj, ij);
+        if (in_order == ascending_block) {
+          keys[i] = kj; keys[j] = ki;
+          ids[i] = (uint16_t)ij; ids[j] = (uint16_t)ii;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  const uint64_t thr_key = keys[k - 1];
+  const int thr_id = ids[k - 1];
+  __syncthreads();
+  // keep flags by chunk index (reuse ids[] as the flag array)
+#pragma unroll
+  for (int r = 0; r < kSingleMaxChunks / 1024; ++r) {
+    const int j = t + r * 1024;
+    if (j < n) ids[j] = (mine[r] > thr_key || (mine[r] == thr_key && j <= thr_id)) ? 1 : 0;
+  }
+  __syncthreads();
+  // ordered pass: thread t owns chunks [j0, j1) in index order
+  const int per = (n + 1023) / 1024;
+  const int j0 = min(n, t * per), j1 = min(n, j0 + per);
+  int tokens = 0;
+  for (int j = j0; j < j1; ++j)
+    if (ids[j]) tokens += min(p.chunk, M - j * p.chunk);
+  int total_tokens;
+  int off = block_exclusive_scan_1024(tokens, sh, &total_tokens);
+  for (int j = j0; j < j1; ++j) {
+    if (!ids[j]) continue;
+    const int len = min(p.chunk, M - j * p.chunk);
+    for (int r = 0; r < len; ++r)
+      if ((int64_t)off + r < p.capacity) p.kept_idx[off + r] = j * p.chunk + r;
+    off += len;
+  }
+  if (t == 0) p.cu_keep[1] = total_tokens;
+}
+
 __global__ __launch_bounds__(1024) void cu_keep_kernel(const SelDev p) {
   block_prefix_table(p.B, [&](int b) { return p.seq_keep[b]; }, p.cu_keep);
 }
@@ -258,11 +344,17 @@ extern "C" sp_status sp_pool_select(const sp_pool_select_args* a, void* hip_stre
   p.cs = reinterpret_cast<double*>(ws);         ws += align_up(8 * mc, 256);
   p.chunk_off = reinterpret_cast<int32_t*>(ws);
 
-  hipLaunchKernelGGL(chunk_table_kernel, dim3(1), dim3(1024), 0, stream, p);
   const int cpw = a->chunk >= kWave ? 1 : kWave / a->chunk;
   const size_t groups = (mc + cpw - 1) / cpw;
   const int pool_blocks = (int)std::min<size_t>((groups + 3) / 4, 65535);
-  hipLaunchKernelGGL(pool_chunk_kernel, dim3(std::max(pool_blocks, 1)), dim3(256), 0, stream, p);
+  if (a->B == 1 && (a->T + a->chunk - 1) / a->chunk <= kSingleMaxChunks) {
+    // one sequence (its length is T, known here): no chunk table, no cross-sequence scan
+    hipLaunchKernelGGL(pool_chunk_kernel<true>, dim3(std::max(pool_blocks, 1)), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(select_emit_single_kernel, dim3(1), dim3(1024), 0, stream, p);
+    return launch_status();
+  }
+  hipLaunchKernelGGL(chunk_table_kernel, dim3(1), dim3(1024), 0, stream, p);
+  hipLaunchKernelGGL(pool_chunk_kernel<false>, dim3(std::max(pool_blocks, 1)), dim3(256), 0, stream, p);
   hipLaunchKernelGGL(select_kernel, dim3(a->B), dim3(1024), 0, stream, p);
   hipLaunchKernelGGL(cu_keep_kernel, dim3(1), dim3(1024), 0, stream, p);
   if (a->T > 0)
