@@ -241,8 +241,12 @@ __global__ __launch_bounds__(1024) void select_emit_single_kernel(const SelDev p
           ids[i] = (uint16_t)ij; ids[j] = (uint16_t)ii;
         }
       }
-      __syncthreads();
+      // pairs up to 64 apart stay inside the 128 elements one wave works on, and a wave's LDS
+      // accesses are performed in order: only wider strides (and the step down from them) need
+      // the whole workgroup to meet
+      if (stride > 64) __syncthreads(); else __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     }
+    __syncthreads();
   }
   const uint64_t thr_key = keys[k - 1];
   const int thr_id = ids[k - 1];
