@@ -128,6 +128,11 @@ __device__ __forceinline__ void lds_poke128(uint32_t lds_addr, u32x4 v) {
 __device__ __forceinline__ void lds_add(uint32_t lds_addr, uint32_t v) {
   asm volatile("ds_add_u32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
 }
+__device__ __forceinline__ uint32_t lds_or_rtn(uint32_t lds_addr, uint32_t v) {
+  uint32_t old;
+  asm volatile("ds_or_rtn_b32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(old) : "v"(lds_addr), "v"(v) : "memory");
+  return old;
+}
 __device__ __forceinline__ uint32_t lds_add_rtn(uint32_t lds_addr, uint32_t v) {
   uint32_t old;
   asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(old) : "v"(lds_addr), "v"(v) : "memory");
@@ -192,12 +197,10 @@ struct Streamer {
   int budget;
   int issued;            // vector-memory instructions issued so far by this wave (never over-counted)
   int seq0, seq1;        // value of `issued` right after the loads of the tile in ring slot 0 / 1
-  int duty_k, duty_q;    // reducer rotation: this workgroup reduces quad duty_k of the slab if duty_k < quads
-  int red_quad;          // quad of rows (counted over the whole call) this wave still has to reduce, or -1
-  int red_turn;          // its number among this workgroup's duties (they share one landing zone, in turn)
+  int duty_k;            // reducer rotation: this workgroup reduces quad duty_k of the slab if duty_k < quads
   uint32_t ring_lds;     // LDS byte address of this wave's two-slot ring
   uint32_t dep_lds;      // LDS: [NSETS][8 waves][32 rows] (max, sum) deposits
-  uint32_t cnt_lds;      // LDS: [NSETS] arrival counters; word 15: number of finished reducer duties
+  uint32_t cnt_lds;      // LDS: [NSETS] arrival counters; words 8..10: the workgroup's reducer duty (quad or -1, lock, sampled)
   uint32_t lse_lds;      // LDS: this wave's [2][32] fetched log-sum-exps
   uint32_t stage_lds;    // LDS: landing zone of a reducer sample (one per workgroup)
   uint32_t rd0;          // LDS byte address of this lane's operand unit for k-step 0 in slot 0
@@ -230,9 +233,6 @@ struct Streamer {
     issued = 0;
     seq0 = seq1 = 0;
     duty_k = wg;
-    duty_q = 0;
-    red_quad = -1;
-    red_turn = 0;
     // operand read: unit (2t + half) of row col lives at position (2t + half) ^ key(col)
     //             = 2 * (t ^ (key >> 1)) + (half ^ (key & 1)), so the address is rd0 ^ (t << 5)
     const int key = (D == 128) ? (col & 15) : ((col >> 1) & 7);
@@ -431,7 +431,9 @@ struct Streamer {
     uint32_t old = 0;
     if (lane == 0) old = lds_add_rtn(cnt_lds + SET * 4, 1);
     old = __builtin_amdgcn_readfirstlane(old);
-    if ((old & 7) == 7) publish(slab, dep_lds + SET * kDepSlotBytes);
+    const bool last = (old & 7) == 7;
+    if (last) publish(slab, dep_lds + SET * kDepSlotBytes);
+    advance_duty(slab, last);
   }
 
   // Merge the deposits of the waves that share rows into one base-2 log-sum-exp per row and
@@ -464,58 +466,56 @@ struct Streamer {
   }
 
   // Reducer rotation.  Quad number x (four rows; counted over the whole call) is reduced by
-  // workgroup x % nwg, wave (x / nwg) % 8.  Called once per slab, in slab order, right after this wave
-  // has deposited the slab.
-  __device__ __forceinline__ void take_duty(int slab) {
+  // workgroup x % nwg.  Every wave keeps the rotation in step (called once per slab, in slab
+  // order); the wave that has just published the slab posts the workgroup's duty for it, if it
+  // has one, in LDS, where any wave of the workgroup can pick it up.
+  __device__ __forceinline__ void advance_duty(int slab, bool post) {
     const int quads = p.S * 8;
-    if (duty_k < quads && (duty_q & 7) == wave) {
-      while (red_quad >= 0 && budget > 0) {  // cannot happen unless the exchange is badly late
-        service_reduce();
+    if (post && duty_k < quads) {
+      while ((int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 32)) >= 0 && budget > 0) {
+        service_reduce();  // the previous duty is still open: cannot happen unless the exchange is badly late
         __builtin_amdgcn_s_sleep(4);
         --budget;
       }
-      red_quad = slab * quads + duty_k;
-      red_turn = duty_q;
+      if (lane == 0) {
+        lds_poke32(cnt_lds + 40, 0);                               // nothing sampled yet
+        lds_poke32(cnt_lds + 32, (uint32_t)(slab * quads + duty_k));  // (LDS writes of a wave are performed in order)
       }
-    duty_k -= quads;
-    if (duty_k < 0) {
-      duty_k += p.nwg;
-      ++duty_q;
     }
+    duty_k -= quads;
+    if (duty_k < 0) duty_k += p.nwg;
   }
+  __device__ __forceinline__ bool duty_open() { return (int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 32)) >= 0; }
 
-  // Hop 1, receiving side: one attempt.  Send a sample of the quad's nwg x 4 values on its way
-  // into the landing zone (marked "pending" first), watch the zone until every word has arrived
-  // -- LDS reads only, the key tiles in flight are not waited for -- and if no value is empty
-  // fold them into the four rows' log-sum-exps and publish those.  Otherwise try again a slab later.
+  // Hop 1, receiving side: one step of the workgroup's reducer duty, by whichever wave comes
+  // by -- at the end of every slab, and all the time while it waits for a log-sum-exp, so the
+  // waves that are ahead of the others do this work.  Never waits.  No sample out yet: send one
+  // of the quad's nwg x 4 values on its way into the landing zone (marked "pending" first).
+  // Sample out: look at the zone (LDS reads only); words still pending -> later; a value still
+  // empty -> sample again; all there -> fold them into the four rows' log-sum-exps and publish.
   __device__ __forceinline__ void service_reduce() {
-    if (red_quad < 0) return;
-    // the landing zone is the workgroup's only one: duties use it in turn
-    if ((int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 60)) != red_turn) return;
+    const int quad = (int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 32));
+    if (quad < 0) return;
+    // the duty is one wave's at a time: test-and-set (an add that is taken back when it finds the
+    // lock held would make the lock look held to everybody else in the meantime, and with eight
+    // waves asking in a tight loop nobody would ever get it)
+    uint32_t held = 1;
+    if (lane == 0) held = lds_or_rtn(cnt_lds + 36, 1);
+    if (__builtin_amdgcn_readfirstlane(held) != 0) return;
+    // (the duty may have been finished between the two looks above)
+    const int quad2 = (int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 32));
+    if (quad2 == quad) reduce_step(quad);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (lane == 0) lds_poke32(cnt_lds + 36, 0);
+  }
+  __device__ __forceinline__ void reduce_step(int quad) {
     int ln = lane;
     asm volatile("" : "+v"(ln));  // address arithmetic of this rare path stays here instead of being hoisted
-    const int slab = red_quad >> (p.lgS + 3);
-    const int q4 = (red_quad - (slab << (p.lgS + 3))) * 4;  // first of the four rows, within the slab
-    const uint32_t* src = p.partial + (int64_t)red_quad * p.nwg * 4;
-    const u32x4 fill = {kPending32, kPending32, kPending32, kPending32};
+    const bool sampled = __builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 40)) != 0;
     const int groups = (p.nwg + kWave - 1) / kWave;
-#pragma unroll 1  // rare path: keep its register appetite small
-    for (int i = 0; i < groups; ++i) lds_poke128(stage_lds + (ln + i * kWave) * 16, fill);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the pattern is in place before any answer can land
-#pragma unroll
-    for (int i = 0; i < kMaxWG / kWave; ++i) {
-      if (i < groups) {
-        const int e = min(ln + i * kWave, p.nwg - 1);  // lanes past the end repeat the last workgroup
-        __builtin_amdgcn_global_load_lds(src + (int64_t)e * 4, lds_ptr(stage_lds + i * 1024), 16, 0, /*sc1*/ 16);
-      }
-    }
-    note_issued(groups);
-    bool pending, empty;
+    bool pending = false, empty = false;
     u32x4 w[kMaxWG / kWave];
-    do {
-      __builtin_amdgcn_s_sleep(8);
-      --budget;
-      pending = false, empty = false;
+    if (sampled) {
 #pragma unroll
       for (int i = 0; i < kMaxWG / kWave; ++i) {
         if (i < groups) {
@@ -526,8 +526,27 @@ struct Streamer {
           w[i] = u32x4{0xff800000u, 0xff800000u, 0xff800000u, 0xff800000u};  // -inf: contributes nothing
         }
       }
-    } while (__any(pending) && budget > 0);
-    if (__any(empty || pending)) return;
+      if (__any(pending)) return;
+    }
+    if (!sampled || __any(empty)) {
+      const uint32_t* src = p.partial + (int64_t)quad * p.nwg * 4;
+      const u32x4 fill = {kPending32, kPending32, kPending32, kPending32};
+#pragma unroll 1  // rare path: keep its register appetite small
+      for (int i = 0; i < groups; ++i) lds_poke128(stage_lds + (ln + i * kWave) * 16, fill);
+      if (ln == 0) lds_poke32(cnt_lds + 40, 1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the pattern is in place before any answer can land
+#pragma unroll
+      for (int i = 0; i < kMaxWG / kWave; ++i) {
+        if (i < groups) {
+          const int e = min(ln + i * kWave, p.nwg - 1);  // lanes past the end repeat the last workgroup
+          __builtin_amdgcn_global_load_lds(src + (int64_t)e * 4, lds_ptr(stage_lds + i * 1024), 16, 0, /*sc1*/ 16);
+        }
+      }
+      note_issued(groups);
+      return;
+    }
+    const int slab = quad >> (p.lgS + 3);
+    const int q4 = (quad - (slab << (p.lgS + 3))) * 4;  // first of the four rows, within the slab
     float lse4[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -546,7 +565,7 @@ struct Streamer {
     }
     if (ln == 0) {
       const u32x4 out = {__float_as_uint(lse4[0]), __float_as_uint(lse4[1]), __float_as_uint(lse4[2]), __float_as_uint(lse4[3])};
-      store128_agent(p.lse2 + (int64_t)red_quad * 4, out);
+      store128_agent(p.lse2 + (int64_t)quad * 4, out);
       if (p.lse_out) {
         const int kvh = ((slab & (p.slabs_per_layer - 1)) << p.lgS) + (q4 >> 5);
 #pragma unroll
@@ -557,10 +576,9 @@ struct Streamer {
                 lse4[r] * 0.6931471805599453f;
         }
       }
-      lds_add(cnt_lds + 60, 1);  // the landing zone is free for the workgroup's next duty
+      lds_poke32(cnt_lds + 32, ~0u);  // duty done
     }
     note_issued(1);  // (the optional log-sum-exp output is not counted: counting less only waits more)
-    red_quad = -1;
   }
 
   // Hop 2.  Request the log-sum-exps of this wave's 32 rows of the slab with one direct-to-LDS
@@ -647,7 +665,8 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
 #pragma unroll
   for (int j = 0; j < (MEAN ? 8 : 1); ++j) tot[j] = 0.f;
   for (int i = threadIdx.x; i < cells; i += kThreads) *cell_at(i) = -INFINITY;
-  if (threadIdx.x < 16) *reinterpret_cast<uint32_t*>(smem + kWaves * 2 * St::TILE_B + NSETS * kDepSlotBytes + threadIdx.x * 4) = 0;
+  if (threadIdx.x < 16)  // arrival counters, duty lock and flag: 0; the duty itself: none
+    *reinterpret_cast<uint32_t*>(smem + kWaves * 2 * St::TILE_B + NSETS * kDepSlotBytes + threadIdx.x * 4) = threadIdx.x == 8 ? ~0u : 0u;
   __syncthreads();
 
   // layer-mean mode: slab `done` was just finished by this wave; if it closes a layer (other
@@ -657,7 +676,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
     if (MEAN && ((done + 1) & (p.slabs_per_layer - 1)) == 0 && done + 1 < p.n_slabs) {
       // a wave parked at a barrier serves nobody: finish the reducer duty first (it only needs
       // publications of slabs every wave of the grid has already left behind)
-      while (st.red_quad >= 0 && st.budget > 0) {
+      while (st.duty_open() && st.budget > 0) {
         st.service_reduce();
         __builtin_amdgcn_s_sleep(4);
         --st.budget;
@@ -712,8 +731,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
       st.template stats_tile<SET>(kb);
     }
     st.template deposit<SET>(slab);
-    // reducer duty, once per slab and here, where the fewest registers are live
-    st.take_duty(slab);
+    // a step of the workgroup's reducer duty, here, where the fewest registers are live
     st.service_reduce();
   };
 
@@ -749,7 +767,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
     }
     close_layer(s);
   }
-  while (st.red_quad >= 0 && st.budget > 0) {  // nobody gets its log-sum-exps before this duty is done
+  while (st.duty_open() && st.budget > 0) {  // nobody gets its log-sum-exps before this duty is done
     st.service_reduce();
     __builtin_amdgcn_s_sleep(4);
     --st.budget;
