@@ -56,6 +56,7 @@ constexpr int kThreads = kWaves * kWave;
 constexpr int kMaxWG = 256;
 constexpr uint32_t kEmpty32 = ~0u;
 constexpr uint32_t kPending32 = ~0u - 1;  // in an LDS landing zone: the sample has not arrived yet
+constexpr int kCtlBytes = 128;         // arrival counters and the workgroup's duty words
 constexpr int kStageBytes = kMaxWG * 16;  // landing zone of a reducer's sample: 4 rows x 4 bytes per workgroup
 constexpr int kSpinBudget = 1 << 16;  // polls per wave over the whole call before giving up (~0.1 s)
 constexpr int kDepSlotBytes = 8 * 32 * 8;  // one slab's deposits: 8 waves x 32 rows x (max, sum)
@@ -127,6 +128,17 @@ __device__ __forceinline__ void lds_poke128(uint32_t lds_addr, u32x4 v) {
 }
 __device__ __forceinline__ void lds_add(uint32_t lds_addr, uint32_t v) {
   asm volatile("ds_add_u32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_or(uint32_t lds_addr, uint32_t v) {
+  asm volatile("ds_or_b32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_and(uint32_t lds_addr, uint32_t v) {
+  asm volatile("ds_and_b32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ uint64_t lds_peek64(uint32_t lds_addr) {
+  uint64_t v;
+  asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
+  return v;
 }
 __device__ __forceinline__ uint32_t lds_or_rtn(uint32_t lds_addr, uint32_t v) {
   uint32_t old;
@@ -200,7 +212,9 @@ struct Streamer {
   int duty_k;            // reducer rotation: this workgroup reduces quad duty_k of the slab if duty_k < quads
   uint32_t ring_lds;     // LDS byte address of this wave's two-slot ring
   uint32_t dep_lds;      // LDS: [NSETS][8 waves][32 rows] (max, sum) deposits
-  uint32_t cnt_lds;      // LDS: [NSETS] arrival counters; words 8..10: the workgroup's reducer duty (quad or -1, lock, sampled)
+  uint32_t cnt_lds;      // LDS control block: words 0..7 arrival counters per set; 8 reducer duty (quad or -1);
+                         // 9 mask of sets waiting to be published; 10, 11 the two duties' locks; 12 reducer
+                         // sample flag; 16..23 slab number of the set waiting to be published
   uint32_t lse_lds;      // LDS: this wave's [2][32] fetched log-sum-exps
   uint32_t stage_lds;    // LDS: landing zone of a reducer sample (one per workgroup)
   uint32_t rd0;          // LDS byte address of this lane's operand unit for k-step 0 in slot 0
@@ -225,9 +239,9 @@ struct Streamer {
     ring_lds = smem_lds + wave * 2 * TILE_B;
     dep_lds = smem_lds + kWaves * 2 * TILE_B;
     cnt_lds = dep_lds + NSETS * kDepSlotBytes;
-    lse_lds = cnt_lds + 64 + wave * 256;
-    stage_lds = cnt_lds + 64 + kWaves * 256;
-    smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 256 + kStageBytes);
+    lse_lds = cnt_lds + kCtlBytes + wave * 256;
+    stage_lds = cnt_lds + kCtlBytes + kWaves * 256;
+    smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + kCtlBytes + kWaves * 256 + kStageBytes);
     keys_wg = max(0, min(p.KPW, p.M - wg * p.KPW));
     budget = kSpinBudget;
     issued = 0;
@@ -248,7 +262,7 @@ struct Streamer {
   }
 
   static size_t smem_bytes(int n_queries, int kpw) {
-    return (size_t)kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + 64 + kWaves * 256 + kStageBytes +
+    return (size_t)kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + kCtlBytes + kWaves * 256 + kStageBytes +
            (size_t)n_queries * (kpw + kSmaxPad) * sizeof(float);
   }
 
@@ -432,7 +446,12 @@ struct Streamer {
     if (lane == 0) old = lds_add_rtn(cnt_lds + SET * 4, 1);
     old = __builtin_amdgcn_readfirstlane(old);
     const bool last = (old & 7) == 7;
-    if (last) publish(slab, dep_lds + SET * kDepSlotBytes);
+    // the slab is complete: leave its publication to whoever has time (this wave is the one that
+    // has none: it is the workgroup's last)
+    if (last && lane == 0) {
+      lds_poke32(cnt_lds + 64 + SET * 4, (uint32_t)slab);
+      lds_or(cnt_lds + 36, 1u << SET);
+    }
     advance_duty(slab, last);
   }
 
@@ -478,14 +497,37 @@ struct Streamer {
         --budget;
       }
       if (lane == 0) {
-        lds_poke32(cnt_lds + 40, 0);                               // nothing sampled yet
+        lds_poke32(cnt_lds + 48, 0);                               // nothing sampled yet
         lds_poke32(cnt_lds + 32, (uint32_t)(slab * quads + duty_k));  // (LDS writes of a wave are performed in order)
       }
     }
     duty_k -= quads;
     if (duty_k < 0) duty_k += p.nwg;
   }
-  __device__ __forceinline__ bool duty_open() { return (int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 32)) >= 0; }
+  // anything left that only this workgroup can do for the others?
+  __device__ __forceinline__ bool duty_open() {
+    const uint64_t v = lds_peek64(cnt_lds + 32);
+    return (int)__builtin_amdgcn_readfirstlane((uint32_t)v) >= 0 || __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32)) != 0;
+  }
+  // Publish one complete slab, if one is waiting and nobody else is at it.  `not_set`: the set this
+  // wave has just completed itself (it leaves that one to a wave with time on its hands), or -1.
+  __device__ __forceinline__ void service_publish(uint32_t mask, int not_set) {
+    if (not_set >= 0) mask &= ~(1u << not_set);
+    if (mask == 0) return;
+    uint32_t held = 1;
+    if (lane == 0) held = lds_or_rtn(cnt_lds + 44, 1);
+    if (__builtin_amdgcn_readfirstlane(held) != 0) return;
+    uint32_t now = __builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 36));
+    if (not_set >= 0) now &= ~(1u << not_set);
+    if (now != 0) {
+      const int set = __builtin_ctz(now);
+      const int slab = (int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 64 + set * 4));
+      publish(slab, dep_lds + set * kDepSlotBytes);
+      if (lane == 0) lds_and(cnt_lds + 36, ~(1u << set));
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (lane == 0) lds_poke32(cnt_lds + 44, 0);
+  }
 
   // Hop 1, receiving side: one step of the workgroup's reducer duty, by whichever wave comes
   // by -- at the end of every slab, and all the time while it waits for a log-sum-exp, so the
@@ -493,25 +535,28 @@ struct Streamer {
   // of the quad's nwg x 4 values on its way into the landing zone (marked "pending" first).
   // Sample out: look at the zone (LDS reads only); words still pending -> later; a value still
   // empty -> sample again; all there -> fold them into the four rows' log-sum-exps and publish.
-  __device__ __forceinline__ void service_reduce() {
-    const int quad = (int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 32));
+  __device__ __forceinline__ void service_reduce(int not_set = -1) {
+    const uint64_t duties = lds_peek64(cnt_lds + 32);
+    const int quad = (int)__builtin_amdgcn_readfirstlane((uint32_t)duties);
+    const uint32_t mask = __builtin_amdgcn_readfirstlane((uint32_t)(duties >> 32));
+    if (mask != 0) service_publish(mask, not_set);
     if (quad < 0) return;
     // the duty is one wave's at a time: test-and-set (an add that is taken back when it finds the
     // lock held would make the lock look held to everybody else in the meantime, and with eight
     // waves asking in a tight loop nobody would ever get it)
     uint32_t held = 1;
-    if (lane == 0) held = lds_or_rtn(cnt_lds + 36, 1);
+    if (lane == 0) held = lds_or_rtn(cnt_lds + 40, 1);
     if (__builtin_amdgcn_readfirstlane(held) != 0) return;
     // (the duty may have been finished between the two looks above)
     const int quad2 = (int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 32));
     if (quad2 == quad) reduce_step(quad);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (lane == 0) lds_poke32(cnt_lds + 36, 0);
+    if (lane == 0) lds_poke32(cnt_lds + 40, 0);
   }
   __device__ __forceinline__ void reduce_step(int quad) {
     int ln = lane;
     asm volatile("" : "+v"(ln));  // address arithmetic of this rare path stays here instead of being hoisted
-    const bool sampled = __builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 40)) != 0;
+    const bool sampled = __builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 48)) != 0;
     const int groups = (p.nwg + kWave - 1) / kWave;
     bool pending = false, empty = false;
     u32x4 w[kMaxWG / kWave];
@@ -533,7 +578,7 @@ struct Streamer {
       const u32x4 fill = {kPending32, kPending32, kPending32, kPending32};
 #pragma unroll 1  // rare path: keep its register appetite small
       for (int i = 0; i < groups; ++i) lds_poke128(stage_lds + (ln + i * kWave) * 16, fill);
-      if (ln == 0) lds_poke32(cnt_lds + 40, 1);
+      if (ln == 0) lds_poke32(cnt_lds + 48, 1);
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the pattern is in place before any answer can land
 #pragma unroll
       for (int i = 0; i < kMaxWG / kWave; ++i) {
@@ -731,8 +776,8 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
       st.template stats_tile<SET>(kb);
     }
     st.template deposit<SET>(slab);
-    // a step of the workgroup's reducer duty, here, where the fewest registers are live
-    st.service_reduce();
+    // a step of the workgroup's duties, here, where the fewest registers are live
+    st.service_reduce(SET);
   };
 
   for (int s0 = 0; s0 < p.n_slabs; s0 += NSETS) {
@@ -853,7 +898,7 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   if (pl.S * 8 > nwg) return pl;  // reducer rotation: at most one quad of rows per workgroup and slab
   pl.partial_bytes = align_up(pl.rows * nwg * sizeof(uint32_t), 256);
   pl.lse_bytes = align_up(pl.rows * sizeof(uint32_t), 256);
-  pl.smem_bytes = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)(8 / tpw) * kDepSlotBytes + 64 + kWaves * 256 +
+  pl.smem_bytes = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)(8 / tpw) * kDepSlotBytes + kCtlBytes + kWaves * 256 +
                   kStageBytes + (size_t)a->N * (pl.KPW + kSmaxPad) * sizeof(float);
   if (pl.smem_bytes > 160 * 1024) return pl;
   if ((size_t)a->N * pl.KPW > 8 * kThreads) return pl;
