@@ -17,22 +17,25 @@
 //     with direct global->LDS loads: per slab one tile of query rows (its KV head's 32
 //     (query, head-in-group) rows) followed by TPW tiles of keys.  Tiles are stored with an
 //     XOR swizzle that makes the MFMA operand reads bank-conflict free; the MFMA is
-//     v_mfma_f32_32x32x16_bf16 with keys as matrix rows and query rows as columns.  All vector
-//     memory traffic of a wave's steady state is direct-to-LDS loads in fixed-size groups, which
-//     is what lets a constant "s_waitcnt vmcnt(LOADS)" stand for "everything older than the
-//     youngest tile has landed" (plain loads and stores would force full drains);
-//   * exchange, hop 1: per slab every wave deposits, for each of its rows, (max, sum 2^(x-max))
-//     over its keys in LDS; the wave that deposits last merges the workgroup's rows into one
-//     log-sum-exp per row and publishes them, 16 bytes per four rows (every coherent access
-//     costs the chip's memory pipeline a little, so a publication is as small as it can be).  For every four rows one wave of one workgroup (both rotating) is the
-//     reducer: it samples all workgroups' values with four direct-to-LDS gathers, and once none
-//     of them is empty folds them into the four rows' log-sum-exps and publishes those;
-//   * exchange, hop 2: each wave fetches the 32 log-sum-exps of its rows with one more
+//     v_mfma_f32_32x32x16_bf16 with keys as matrix rows and query rows as columns;
+//   * exchange, publication: per slab every wave deposits, for each of its rows, (max, sum
+//     2^(x-max)) over its keys in LDS.  The wave that deposits last only flags the slab; a wave
+//     of the workgroup that has time (typically one waiting for a log-sum-exp) merges the
+//     deposits into one base-2 log-sum-exp per row and stores them, 16 bytes per four rows
+//     (every coherent access costs the chip's memory pipeline time in proportion to its size,
+//     so a publication is as small as it can be);
+//   * exchange, reduction: for every four rows one workgroup (round-robin) owns the reduction
+//     as a duty kept in LDS.  A step of it -- sample all workgroups' words with four
+//     direct-to-LDS loads, or look at the landed sample and, once no word is empty, fold it into
+//     the four rows' log-sum-exps and store those -- is done by whichever wave comes by, at the
+//     end of every slab and all the time while it waits for a log-sum-exp of its own;
+//   * exchange, consumption: each wave fetches the 32 log-sum-exps of its rows with one more
 //     direct-to-LDS load, issued one tile before they are needed;
 //   * nothing of this is ever waited for through vmcnt: a sample's LDS landing zone is filled
 //     with a "pending" pattern before the load is issued and simply looked at later, so the
-//     stream of key tiles is never drained for the exchange.  vmcnt waits are for key/query
-//     tiles only and count exactly the instructions issued after the tile waited for;
+//     stream of key tiles is never drained for the exchange (a drained wave publishes late, and
+//     everybody waits for the last publication).  vmcnt waits are for key/query tiles only and
+//     count exactly the instructions issued after the tile waited for;
 //   * with the log-sum-exp known a slab's logits become log2-probabilities; the max over the
 //     heads of a KV group is a quad DPP max, the max over KV heads / layers an LDS float
 //     atomic max per (query, key); the layer mean (if asked) and the query mean are taken at
@@ -41,9 +44,10 @@
 // Cross-workgroup words are "empty" (all ones) until written, and are written and read with
 // agent-scope coherence; a small kernel refills the workspace with the empty pattern at the
 // start of each call.  Every wait is bounded (a status word records an expired wait), and a
-// wave that waits keeps serving its own reducer duty, so waiting waves cannot starve each other.  The grid
-// is one workgroup per CU, each needing more than half of a CU's LDS, so all of them are
-// resident together on an otherwise idle device; that residency is what every wait relies on.
+// wave that waits, or is about to park at a barrier or to exit, keeps serving its workgroup's
+// duties, so waiting waves cannot starve each other.  The grid is one workgroup per CU, each
+// needing more than half of a CU's LDS, so all of them are resident together on an otherwise
+// idle device; that residency is what every wait relies on.
 #include "sp_score_internal.h"
 
 namespace sp {

@@ -128,3 +128,29 @@ def test_argument_errors_launch_nothing():
     assert status() == sp.SP_OK
     torch.cuda.synchronize()
     assert (s.scores > 0).all()
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_deep_prompt_three_calls_on_one_workspace(mode):
+    """Many slabs (the register sets wrap several times, every workgroup takes reducer duties) and
+    the same workspace used by consecutive calls: each call must refill what the previous one left."""
+    import torch
+    from paper_2502_02789_amd import binding as sp_binding, device as dev
+    w = synth.scaled(synth.workload(3), seqlens=(8192 + 17,), L=12)
+    inp = synth.make_qk(w)
+    scale = 1.0 / math.sqrt(w.d)
+    want, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, mode)
+    q = dev.bf16_from_bits(inp["q"])
+    ks = [dev.bf16_from_bits(k) for k in inp["k"]]
+    cu = torch.from_numpy(inp["cu_seqlens"]).cuda()
+    s = dev.Scorer(q, ks, cu, H_kv=w.H_kv, scale=scale, layer_reduce=mode)
+    first = None
+    for _ in range(3):
+        s.scores.fill_(float("nan"))
+        s.run()
+        sp_binding.sp_score_check(s.args)
+        got = s.scores.cpu().numpy()
+        hp.assert_scores_close(got, want, f"{w.name} mode={mode}")
+        if first is None:
+            first = got
+        assert (got.view(np.uint32) == first.view(np.uint32)).all()

@@ -139,3 +139,17 @@ def test_select_and_gather_argument_errors():
     assert lib.sp_gather(C.byref(ga), None) == sp.SP_EINVAL
     assert lib.sp_gather(None, None) == sp.SP_ENULL
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("T,chunk,rate,ties", [(32768, 32, 0.1, False), (65536, 32, 0.37, True), (1000, 7, 0.5, True)])
+def test_single_sequence_fast_path_equals_general_path(T, chunk, rate, ties):
+    """One sequence takes the two-launch path; the same tokens followed by an empty sequence take the
+    general one.  Both must keep exactly the same tokens."""
+    x = synth.random_scores(99 + T, T, ties=ties)
+    a = hp.gpu_pool_select(x, _cu([T]), chunk, 13, rate)
+    b = hp.gpu_pool_select(x, _cu([T, 0]), chunk, 13, rate)
+    na, nb = int(a.cu_keep.cpu()[1]), int(b.cu_keep.cpu()[1])
+    assert na == nb == int(b.cu_keep.cpu()[2])
+    assert (a.kept_idx.cpu().numpy()[:na] == b.kept_idx.cpu().numpy()[:nb]).all()
+    np.testing.assert_array_equal(a.chunk_scores.cpu().numpy()[: (T + chunk - 1) // chunk],
+                                  b.chunk_scores.cpu().numpy()[: (T + chunk - 1) // chunk])
