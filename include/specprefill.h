@@ -63,7 +63,8 @@ typedef enum { SP_LAYER_MAX = 0, SP_LAYER_MEAN = 1 } sp_layer_reduce;
  *     SP_LAYER_MAX : score[i] = mean_{n < n_valid[b]} max_{l,h} a               (Sec. 3.2.2)
  *     SP_LAYER_MEAN: score[i] = mean_{n < n_valid[b]} mean_l max_h a
  * The softmax runs over the prompt keys of the token's own sequence only.
- * Q and K are taken as stored by the draft model (already position-encoded).
+ * Q and K are taken as stored by the draft model (already position-encoded) unless
+ * rope_theta > 0 asks for the rotary encoding to be applied here.
  * --------------------------------------------------------------------------- */
 typedef struct {
   int32_t B;                 /* sequences, >= 1                                           */
@@ -84,8 +85,15 @@ typedef struct {
                                 first n_valid[b] query rows count (EOS validity, Sec. 3.3)  */
   float scale;               /* logit scale; the model's own attention uses 1/sqrt(d)     */
   int32_t layer_reduce;      /* sp_layer_reduce                                           */
-  float rope_theta;          /* must be 0: Q and K are already rotated                    */
-  const int32_t* d_q_pos;    /* reserved for in-kernel rotation; must be NULL             */
+  float rope_theta;          /* 0: Q and K are stored already position-encoded (what a serving
+                                cache holds; the fast path).  > 0: Q and K are stored
+                                un-rotated and are rotated here, rotate-half pairing
+                                (t, t + d/2), angle pos * theta^(-2t/d): key i of a sequence
+                                at position i, query row n of sequence b at d_q_pos[b*N+n];
+                                cosine/sine in fp32, rotated values rounded to bf16, then
+                                everything as for rope_theta = 0.  Runs the general kernels
+                                and needs the larger workspace the size query reports.     */
+  const int32_t* d_q_pos;    /* int32 [B, N] query positions if rope_theta > 0, else NULL  */
   float* d_scores;           /* out fp32 [T]                                              */
   float* d_lse;              /* out fp32 [L, B, N, H] row log-sum-exp, or NULL            */
   void* d_workspace;         /* device scratch, 256-byte aligned                          */
@@ -97,7 +105,7 @@ typedef struct {
 SP_API size_t sp_score_workspace_bytes(const sp_score_args* args);
 
 /* Enqueue the scoring on hip_stream.  Errors: SP_ENULL, SP_EINVAL (shape limits above),
- * SP_EALIGN, SP_EWORKSPACE, SP_EUNSUPPORTED (rope_theta != 0), SP_ELAUNCH. */
+ * SP_EALIGN, SP_EWORKSPACE, SP_ELAUNCH. */
 SP_API sp_status sp_score(const sp_score_args* args, void* hip_stream);
 
 /* Same contract and results as sp_score, but always runs the general two-pass kernels

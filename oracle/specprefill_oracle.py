@@ -20,6 +20,9 @@ Steps and where the paper defines them
   select_chunks        Sec. 3.2.3  Top-K chunks
   pool_select          Algorithm 1, chunk_select_from_smoothed_attention
   gather               Sec. 3.2.4  position-id restoration (+ token ids, embedding rows)
+  rope_rotate_bits     not in the paper: the rotary position encoding a Llama-family draft
+                       applies to Q and K before they are cached (needed only when the
+                       library is handed an un-rotated cache)
 
 Readings where the paper is silent (each listed in the design doc): softmax over the M
 prompt keys only; scale is an argument; pooling window clipped at sequence edges with
@@ -51,6 +54,32 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
 # ----------------------------------------------------------------------------
 # a1 + a2: logits and row softmax for one sequence in one layer
 # ----------------------------------------------------------------------------
+def rope_rotate_bits(x_bits: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
+    """Rotary position encoding of un-rotated bf16 vectors, result rounded back to bf16.
+
+    x_bits: uint16 bf16 patterns [P, heads, d]; pos: [P] integer positions.  Pair (t, t + d/2)
+    is rotated by the angle pos * theta^(-2t/d) (the Llama "rotate-half" convention).  The
+    angle is formed in fp64, its cosine and sine are rounded to fp32, the rotation itself is
+    done in fp32 and the result is rounded to bf16, nearest-even: this is what a draft model
+    running in bf16 with fp32 rotary tables stores in its cache.  Returns uint16 patterns.
+    """
+    x = (np.asarray(x_bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    d = x.shape[-1]
+    half = d // 2
+    t = np.arange(half, dtype=np.float64)
+    inv_freq = np.power(float(theta), -2.0 * t / d)
+    ang = np.asarray(pos, dtype=np.float64)[:, None] * inv_freq[None, :]
+    c = np.cos(ang).astype(np.float32)[:, None, :]
+    s = np.sin(ang).astype(np.float32)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    out = np.empty_like(x)
+    out[..., :half] = lo * c - hi * s
+    out[..., half:] = hi * c + lo * s
+    u = out.view(np.uint32)
+    rounded = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
 def layer_attention(q: np.ndarray, k: np.ndarray, scale: float) -> Tuple[np.ndarray, np.ndarray]:
     """q fp64 [N, H, d]; k fp64 [M, H_kv, d] -> (a [N, M, H], lse [N, H]).
 

@@ -125,7 +125,7 @@ def _check(fn: str, status: int) -> None:
 def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, scale: float,
                     layer_reduce: int = SP_LAYER_MAX, n_valid=None, lse=None, workspace=None,
                     k_token_stride: Optional[int] = None, k_head_stride: Optional[int] = None,
-                    T: Optional[int] = None) -> ScoreArgs:
+                    T: Optional[int] = None, rope_theta: float = 0.0, q_pos=None) -> ScoreArgs:
     """q: bf16 [L,B,N,H,d]; k_layers: L bf16 tensors [T,H_kv,d] (any token/head strides)."""
     L, B, N, H, d = q.shape
     a = ScoreArgs()
@@ -141,8 +141,8 @@ def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, sca
     a.d_n_valid = _ptr(n_valid)
     a.scale = float(scale)
     a.layer_reduce = int(layer_reduce)
-    a.rope_theta = 0.0
-    a.d_q_pos = None
+    a.rope_theta = float(rope_theta)
+    a.d_q_pos = _ptr(q_pos)
     a.d_scores = _ptr(scores)
     a.d_lse = _ptr(lse)
     a.d_workspace = _ptr(workspace)

@@ -22,6 +22,62 @@ __global__ __launch_bounds__(1024) void tile_table_kernel(int B, const int32_t* 
   block_prefix_table(B, [&](int b) { return (cu[b + 1] - cu[b] + kTileKeys - 1) / kTileKeys; }, tile_cu);
 }
 
+// fp32 -> bf16 (round to nearest even) -> fp32: what storing a rotated value in a bf16 cache does
+__device__ __forceinline__ float round_to_bf16(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return __uint_as_float((u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u);
+}
+__device__ __forceinline__ uint16_t bf16_bits(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+// Rotary encoding of one un-rotated row held in registers: pair (t, t + D/2) turns by the
+// angle whose (cos, sin) is rope_row[t]; results are rounded as a bf16 cache would hold them.
+template <int D>
+__device__ __forceinline__ void rope_row_inplace(float (&kf)[D], const float2* __restrict__ rope_row) {
+#pragma unroll
+  for (int t = 0; t < D / 2; ++t) {
+    const float2 cs = rope_row[t];
+    const float lo = kf[t], hi = kf[t + D / 2];
+    kf[t] = round_to_bf16(lo * cs.x - hi * cs.y);
+    kf[t + D / 2] = round_to_bf16(hi * cs.x + lo * cs.y);
+  }
+}
+
+// (cos, sin) of pos * theta^(-2t/d) for every position and pair; the angle is formed in fp64
+__global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ table, int64_t n, int half,
+                                                          double log2_theta) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const int t = (int)(i % half);
+  const double pos = (double)(i / half);
+  const double inv_freq = exp2(-((double)t / (double)half) * log2_theta);
+  double sn, cs;
+  sincos(pos * inv_freq, &sn, &cs);
+  table[i] = make_float2((float)cs, (float)sn);
+}
+
+// rotated copy of the un-rotated queries [L, B, N, H, d]; one thread per (row, pair)
+__global__ __launch_bounds__(256) void rope_q_kernel(const uint16_t* __restrict__ q_raw, uint16_t* __restrict__ q_rot,
+                                                      const int32_t* __restrict__ q_pos, int B, int N, int H, int half,
+                                                      int64_t n, double log2_theta) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const int t = (int)(i % half);
+  const int64_t row = i / half;               // ((l * B + b) * N + nq) * H + h
+  const int nq = (int)((row / H) % N);
+  const int b = (int)((row / ((int64_t)H * N)) % B);
+  const double inv_freq = exp2(-((double)t / (double)half) * log2_theta);
+  double sn, cs;
+  sincos((double)q_pos[b * N + nq] * inv_freq, &sn, &cs);
+  const float c = (float)cs, s = (float)sn;
+  const uint16_t* src = q_raw + row * 2 * half;
+  const float lo = __uint_as_float((uint32_t)src[t] << 16), hi = __uint_as_float((uint32_t)src[t + half] << 16);
+  q_rot[row * 2 * half + t] = bf16_bits(lo * c - hi * s);
+  q_rot[row * 2 * half + t + half] = bf16_bits(hi * c + lo * s);
+}
+
 template <int D>
 __device__ __forceinline__ void load_k_row(const uint16_t* __restrict__ kp, bool valid, float (&kf)[D]) {
   const uint4* p4 = reinterpret_cast<const uint4*>(kp);
@@ -70,6 +126,7 @@ __global__ __launch_bounds__(64) void lse_partial_kernel(const ScoreDev p) {
   float kf[D];
   load_k_row<D>(p.k[l] + (int64_t)(seq0 + (valid ? key : 0)) * p.k_token_stride + (int64_t)g * p.k_head_stride,
                 valid, kf);
+  if (p.rope) rope_row_inplace<D>(kf, p.rope + (int64_t)(valid ? key : 0) * (D / 2));
   for (int n = 0; n < p.N; ++n) {
     for (int j = 0; j < p.G; ++j) {
       const int h = g * p.G + j;
@@ -141,6 +198,7 @@ __global__ __launch_bounds__(256) void score_accum_kernel(const ScoreDev p) {
     for (int g = wave; g < p.H_kv; g += 4) {
       float kf[D];
       load_k_row<D>(p.k[l] + tok * p.k_token_stride + (int64_t)g * p.k_head_stride, valid, kf);
+      if (p.rope) rope_row_inplace<D>(kf, p.rope + (int64_t)(valid ? key : 0) * (D / 2));
 #pragma unroll
       for (int n = 0; n < SP_MAX_QUERIES; ++n) {
         if (n < p.N) {
@@ -203,6 +261,10 @@ size_t general_workspace_bytes(const sp_score_args* a) {
   size_t bytes = align_up(sizeof(int32_t) * ((size_t)a->B + 1), 256);
   bytes += align_up(sizeof(float) * (size_t)a->L * a->B * a->N * a->H, 256);
   bytes += align_up(sizeof(float2) * (size_t)a->L * a->N * a->H * general_max_tiles(a), 256);
+  if (a->rope_theta > 0.f) {  // (cos, sin) table for positions 0..T-1 and a rotated copy of the queries
+    bytes += align_up(sizeof(float2) * (size_t)a->T * (a->d / 2), 256);
+    bytes += align_up(sizeof(uint16_t) * (size_t)a->L * a->B * a->N * a->H * a->d, 256);
+  }
   return bytes;
 }
 
@@ -216,6 +278,23 @@ sp_status general_score(const sp_score_args* a, hipStream_t stream) {
   p.ws_lse = reinterpret_cast<float*>(ws);
   ws += align_up(sizeof(float) * (size_t)a->L * a->B * a->N * a->H, 256);
   p.part = reinterpret_cast<float2*>(ws);
+  ws += align_up(sizeof(float2) * (size_t)a->L * a->N * a->H * general_max_tiles(a), 256);
+  if (a->rope_theta > 0.f) {
+    float2* table = reinterpret_cast<float2*>(ws);
+    ws += align_up(sizeof(float2) * (size_t)a->T * (a->d / 2), 256);
+    uint16_t* q_rot = reinterpret_cast<uint16_t*>(ws);
+    const double log2_theta = std::log2((double)a->rope_theta);
+    const int half = a->d / 2;
+    const int64_t n_tab = a->T * half;
+    if (n_tab > 0)
+      hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n_tab + 255) / 256)), dim3(256), 0, stream, table, n_tab,
+                         half, log2_theta);
+    const int64_t n_q = (int64_t)a->L * a->B * a->N * a->H * half;
+    hipLaunchKernelGGL(rope_q_kernel, dim3((unsigned)((n_q + 255) / 256)), dim3(256), 0, stream, p.q, q_rot, a->d_q_pos,
+                       a->B, a->N, a->H, half, n_q, log2_theta);
+    p.rope = table;
+    p.q = q_rot;
+  }
 
   hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(1024), 0, stream, p.B, p.cu, p.tile_cu);
   const dim3 grid1(p.max_tiles, p.H_kv, p.L);
@@ -251,6 +330,7 @@ void fill_score_dev(const sp_score_args* a, ScoreDev* p) {
   p->tile_cu = nullptr; p->ws_lse = nullptr; p->part = nullptr;
   p->scores = a->d_scores;
   p->lse_out = a->d_lse;
+  p->rope = nullptr;
   for (int l = 0; l < SP_MAX_LAYERS; ++l)
     p->k[l] = l < a->L ? static_cast<const uint16_t*>(a->k_layers[l]) : nullptr;
 }
@@ -270,7 +350,9 @@ static sp_status check_score_args(const sp_score_args* a) {
   if (!a->d_q || !a->k_layers || !a->d_cu_seqlens || !a->d_scores) return SP_ENULL;
   for (int l = 0; l < a->L; ++l)
     if (!a->k_layers[l]) return SP_ENULL;
-  if (a->rope_theta != 0.f || a->d_q_pos != nullptr) return SP_EUNSUPPORTED;
+  if (!(a->rope_theta >= 0.f)) return SP_EINVAL;
+  if (a->rope_theta == 0.f && a->d_q_pos != nullptr) return SP_EINVAL;
+  if (a->rope_theta > 0.f && a->d_q_pos == nullptr) return SP_ENULL;
   if (!(a->scale == a->scale) || a->scale <= 0.f) return SP_EINVAL;
   if (a->k_token_stride < 0 || a->k_head_stride < 0) return SP_EINVAL;
   if ((a->k_token_stride & 7) || (a->k_head_stride & 7) || !sp::aligned16(a->d_q)) return SP_EALIGN;

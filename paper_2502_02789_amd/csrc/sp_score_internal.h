@@ -21,6 +21,7 @@ struct ScoreDev {
   float2* part;
   float* scores;
   float* lse_out;
+  const float2* rope;  // [position][d/2] (cos, sin) if keys are stored un-rotated, else null
   const uint16_t* k[SP_MAX_LAYERS];
 };
 

@@ -12,7 +12,7 @@ TIE_RTOL = 1e-6            # stage-isolated selection: chunks this close to the 
 
 
 def gpu_score(q_bits, k_bits_layers, cu, H_kv, scale, mode, n_valid=None, general=False, want_lse=True,
-              head_major=False):
+              head_major=False, rope_theta=0.0, q_pos=None):
     import torch
     from paper_2502_02789_amd import binding as sp_binding, device as dev
     q = dev.bf16_from_bits(q_bits)
@@ -22,7 +22,9 @@ def gpu_score(q_bits, k_bits_layers, cu, H_kv, scale, mode, n_valid=None, genera
         ks = [dev.bf16_from_bits(k) for k in k_bits_layers]
     cu_d = torch.from_numpy(np.asarray(cu, dtype=np.int32)).cuda()
     nv_d = None if n_valid is None else torch.from_numpy(np.asarray(n_valid, dtype=np.int32)).cuda()
-    s = dev.Scorer(q, ks, cu_d, H_kv=H_kv, scale=scale, layer_reduce=mode, n_valid=nv_d, want_lse=want_lse)
+    qp_d = None if q_pos is None else torch.from_numpy(np.ascontiguousarray(q_pos, dtype=np.int32)).cuda()
+    s = dev.Scorer(q, ks, cu_d, H_kv=H_kv, scale=scale, layer_reduce=mode, n_valid=nv_d, want_lse=want_lse,
+                   rope_theta=rope_theta, q_pos=qp_d)
     s.scores.fill_(float("nan"))
     s.run(general=general)
     sp_binding.sp_score_check(s.args)          # synchronises; raises if a device-side wait expired

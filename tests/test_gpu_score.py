@@ -122,7 +122,9 @@ def test_argument_errors_launch_nothing():
     assert status(d_q=q.data_ptr() + 2) == sp.SP_EALIGN
     assert status(workspace_bytes=16) == sp.SP_EWORKSPACE
     assert status(d_workspace=None) == sp.SP_EWORKSPACE
-    assert status(rope_theta=5e5) == sp.SP_EUNSUPPORTED
+    assert status(rope_theta=5e5) == sp.SP_ENULL                  # un-rotated cache without query positions
+    assert status(rope_theta=-1.0) == sp.SP_EINVAL
+    assert status(d_q_pos=cu.data_ptr()) == sp.SP_EINVAL          # positions given but nothing to rotate
     torch.cuda.synchronize()
     assert (s.scores == -7.0).all()
     assert status() == sp.SP_OK
@@ -154,3 +156,47 @@ def test_deep_prompt_three_calls_on_one_workspace(mode):
         if first is None:
             first = got
         assert (got.view(np.uint32) == first.view(np.uint32)).all()
+
+
+def _raw_inputs(seed, seqlens, L, H, H_kv, d, N):
+    """Un-rotated bf16 Q [L,B,N,H,d] and per-layer K [T,H_kv,d], plus query positions [B,N]."""
+    rng = np.random.default_rng(seed)
+    B, T = len(seqlens), int(sum(seqlens))
+    q = synth.f32_to_bf16_bits(rng.standard_normal((L, B, N, H, d)).astype(np.float32))
+    k = [synth.f32_to_bf16_bits(rng.standard_normal((T, H_kv, d)).astype(np.float32)) for _ in range(L)]
+    cu = np.zeros(B + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(seqlens)
+    q_pos = np.array([[m + n for n in range(N)] for m in seqlens], dtype=np.int32)
+    return q, k, cu, q_pos
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("shape", [((700, 33, 0, 1290), 2, 8, 2, 64, 3), ((2100,), 2, 32, 8, 128, 8)])
+def test_unrotated_cache_is_rotated_by_the_library(shape, mode):
+    """rope_theta > 0: raw Q and K in, same scores as the oracle gets after rotating them itself."""
+    seqlens, L, H, H_kv, d, N = shape
+    theta = 5e5
+    q, k, cu, q_pos = _raw_inputs(11, seqlens, L, H, H_kv, d, N)
+    q_rot = np.stack([np.stack([orc.rope_rotate_bits(q[l, b], q_pos[b], theta) for b in range(len(seqlens))])
+                      for l in range(L)])
+    k_rot = []
+    for l in range(L):
+        kr = np.empty_like(k[l])
+        for b in range(len(seqlens)):
+            lo, hi = int(cu[b]), int(cu[b + 1])
+            kr[lo:hi] = orc.rope_rotate_bits(k[l][lo:hi], np.arange(hi - lo), theta)
+        k_rot.append(kr)
+    scale = 1.0 / math.sqrt(d)
+    want, want_lse = orc.token_importance(q_rot, k_rot, cu, scale, mode)
+    got, lse = hp.gpu_score(q, k, cu, H_kv, scale, mode, rope_theta=theta, q_pos=q_pos)
+    hp.assert_scores_close(got, want, f"raw cache {shape} mode={mode}")
+    np.testing.assert_allclose(lse, want_lse, rtol=0, atol=2e-3)
+
+
+def test_rotation_by_position_zero_changes_nothing():
+    """All positions zero is the identity rotation: bit-identical to the already-rotated path."""
+    q, k, cu, _ = _raw_inputs(12, (1,), 2, 8, 2, 64, 1)      # one key at position 0, one query at position 0
+    zero_pos = np.zeros((1, 1), dtype=np.int32)
+    a, la = hp.gpu_score(q, k, cu, 2, 0.125, orc.LAYER_MAX, general=True)
+    b, lb = hp.gpu_score(q, k, cu, 2, 0.125, orc.LAYER_MAX, rope_theta=1e4, q_pos=zero_pos)
+    assert (a.view(np.uint32) == b.view(np.uint32)).all() and (la.view(np.uint32) == lb.view(np.uint32)).all()

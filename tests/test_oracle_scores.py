@@ -231,3 +231,60 @@ def test_planted_salient_tokens_score_high_on_the_tiny_workload():
     assert sal.sum() == 20
     top = np.argsort(-s)[: int(sal.sum())]
     assert len(set(top.tolist()) & set(np.flatnonzero(sal).tolist())) >= 18
+
+
+# ---------------------------------------------------------------------------------------
+# rotary encoding used when the library is handed an un-rotated cache
+# ---------------------------------------------------------------------------------------
+def _bits(x):
+    from paper_2502_02789_amd import synth
+    return synth.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def _vals(b):
+    return orc.bf16_bits_to_f64(b)
+
+
+def test_rope_position_zero_is_identity_and_pairs_keep_their_norm():
+    rng = np.random.default_rng(5)
+    x = _bits(rng.standard_normal((7, 3, 64)))
+    same = orc.rope_rotate_bits(x, np.zeros(7, dtype=np.int64), 5e5)
+    assert (same == x).all()
+    pos = np.array([1, 2, 3, 500, 4096, 70000, 131071])
+    y = _vals(orc.rope_rotate_bits(x, pos, 5e5))
+    xv = _vals(x)
+    n_in = xv[..., :32] ** 2 + xv[..., 32:] ** 2
+    n_out = y[..., :32] ** 2 + y[..., 32:] ** 2
+    np.testing.assert_allclose(n_out, n_in, rtol=2e-2, atol=1e-4)      # a rotation, up to bf16 rounding
+
+
+def test_rope_equals_complex_multiplication():
+    """Independent formula: (lo + i hi) * exp(i * pos * theta^(-2t/d)), in complex128."""
+    rng = np.random.default_rng(6)
+    x = _bits(rng.standard_normal((5, 2, 128)))
+    pos = np.array([0, 1, 17, 9999, 100000])
+    theta = 5e5
+    xv = _vals(x)
+    z = xv[..., :64] + 1j * xv[..., 64:]
+    ang = pos[:, None].astype(np.float64) * theta ** (-2.0 * np.arange(64) / 128)
+    w = z * np.exp(1j * ang)[:, None, :]
+    want = np.concatenate([w.real, w.imag], axis=-1)
+    got = _vals(orc.rope_rotate_bits(x, pos, theta))
+    np.testing.assert_allclose(got, want, rtol=0, atol=2.0 ** -7 * np.abs(want).max())   # bf16 output + fp32 tables
+
+
+def test_rope_makes_logits_depend_on_relative_position_only():
+    """<R(p) q, R(p') k> depends on p - p' only: shifting every position by a constant leaves the
+    token scores unchanged (up to the bf16 rounding of the rotated vectors)."""
+    rng = np.random.default_rng(7)
+    M, N, H, d = 96, 2, 2, 64
+    q_raw = _bits(rng.standard_normal((N, H, d)))
+    k_raw = _bits(rng.standard_normal((M, 1, d)))
+    cu = np.array([0, M], dtype=np.int32)
+    out = []
+    for shift in (0, 1000):
+        q = orc.rope_rotate_bits(q_raw, np.arange(M, M + N) + shift, 1e4)[None, None]      # [L=1,B=1,N,H,d]
+        k = orc.rope_rotate_bits(k_raw, np.arange(M) + shift, 1e4)
+        s, _ = orc.token_importance(q, [k], cu, 0.125, orc.LAYER_MAX)
+        out.append(s)
+    np.testing.assert_allclose(out[0], out[1], rtol=0.1, atol=1e-4)
