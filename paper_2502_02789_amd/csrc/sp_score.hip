@@ -6,7 +6,8 @@
 // every shape the header allows (ragged batches, any G = H/H_kv <= 8, N <= 16, d in {64,128}).
 // They read the K cache twice (once for the row statistics, once for the probabilities) and
 // use plain fp32 FMAs.  The single-pass MFMA kernel for one long prompt lives in
-// sp_score_stream.hip and is chosen by the dispatcher when the shape fits it.
+// sp_score_stream.hip, the two-pass MFMA kernels for ragged batches in sp_score_tiled.hip; the
+// dispatcher takes the first of the three that fits the shape.
 #include "sp_common.h"
 #include "sp_score_internal.h"
 
@@ -265,10 +266,23 @@ size_t general_workspace_bytes(const sp_score_args* a) {
     bytes += align_up(sizeof(float2) * (size_t)a->T * (a->d / 2), 256);
     bytes += align_up(sizeof(uint16_t) * (size_t)a->L * a->B * a->N * a->H * a->d, 256);
   }
+  bytes += tiled_extra_workspace_bytes(a);
   return bytes;
 }
 
-sp_status general_score(const sp_score_args* a, hipStream_t stream) {
+void launch_lse_combine(const ScoreDev& p, hipStream_t stream) {
+  hipLaunchKernelGGL(lse_combine_kernel, dim3(p.L * p.B * p.N * p.H), dim3(64), 0, stream, p);
+}
+
+// these paths have no bounded waits: leave "no wait expired" where sp_score_check looks
+static void clear_stream_status(const sp_score_args* a, hipStream_t stream) {
+  const size_t status_off = stream_supported(a) ? stream_status_offset(a) : 0;
+  if (status_off)
+    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, stream,
+                       reinterpret_cast<uint32_t*>(static_cast<char*>(a->d_workspace) + status_off));
+}
+
+sp_status general_score(const sp_score_args* a, hipStream_t stream, bool allow_mfma) {
   ScoreDev p;
   fill_score_dev(a, &p);
   p.max_tiles = general_max_tiles(a);
@@ -297,6 +311,11 @@ sp_status general_score(const sp_score_args* a, hipStream_t stream) {
   }
 
   hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(1024), 0, stream, p.B, p.cu, p.tile_cu);
+  if (allow_mfma && tiled_supported(a)) {  // (never with an un-rotated cache: ws is this path's own part)
+    const sp_status st = tiled_score(a, p, ws, stream);
+    clear_stream_status(a, stream);
+    return st != SP_OK ? st : launch_status();
+  }
   const dim3 grid1(p.max_tiles, p.H_kv, p.L);
   const int rows = p.L * p.B * p.N * p.H;
   if (p.d == 64) {
@@ -308,11 +327,7 @@ sp_status general_score(const sp_score_args* a, hipStream_t stream) {
     hipLaunchKernelGGL(lse_combine_kernel, dim3(rows), dim3(64), 0, stream, p);
     hipLaunchKernelGGL(score_accum_kernel<128>, dim3(p.max_tiles), dim3(256), 0, stream, p);
   }
-  // these kernels have no bounded waits: leave "no wait expired" where sp_score_check looks
-  const size_t status_off = stream_supported(a) ? stream_status_offset(a) : 0;
-  if (status_off)
-    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, stream,
-                       reinterpret_cast<uint32_t*>(static_cast<char*>(a->d_workspace) + status_off));
+  clear_stream_status(a, stream);
   return launch_status();
 }
 
@@ -368,7 +383,7 @@ extern "C" sp_status sp_score(const sp_score_args* a, void* hip_stream) {
   if (st != SP_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (sp::stream_supported(a)) return sp::stream_score(a, stream);
-  return sp::general_score(a, stream);
+  return sp::general_score(a, stream, /*allow_mfma=*/true);
 }
 
 extern "C" sp_status sp_score_check(const sp_score_args* a, void* hip_stream) {
@@ -388,5 +403,5 @@ extern "C" sp_status sp_score_check(const sp_score_args* a, void* hip_stream) {
 extern "C" sp_status sp_score_general(const sp_score_args* a, void* hip_stream) {
   const sp_status st = check_score_args(a);
   if (st != SP_OK) return st;
-  return sp::general_score(a, static_cast<hipStream_t>(hip_stream));
+  return sp::general_score(a, static_cast<hipStream_t>(hip_stream), /*allow_mfma=*/false);
 }

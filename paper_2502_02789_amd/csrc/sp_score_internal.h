@@ -29,7 +29,15 @@ void fill_score_dev(const sp_score_args* a, ScoreDev* p);
 
 // general two-pass kernels (sp_score.hip)
 size_t general_workspace_bytes(const sp_score_args* a);
-sp_status general_score(const sp_score_args* a, hipStream_t stream);
+// allow_mfma: hand the two passes to the tiled MFMA kernels when the shape fits them
+sp_status general_score(const sp_score_args* a, hipStream_t stream, bool allow_mfma);
+void launch_lse_combine(const ScoreDev& p, hipStream_t stream);
+
+// two-pass MFMA kernels for ragged batches (sp_score_tiled.hip); they share the general kernels'
+// tile table, partials and log-sum-exps (`gen`), `extra` is their own workspace part
+bool tiled_supported(const sp_score_args* a);
+size_t tiled_extra_workspace_bytes(const sp_score_args* a);
+sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, hipStream_t stream);
 
 // single-pass streaming kernel (sp_score_stream.hip)
 bool stream_supported(const sp_score_args* a);

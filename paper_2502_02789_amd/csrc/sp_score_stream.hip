@@ -49,11 +49,10 @@
 // needing more than half of a CU's LDS, so all of them are resident together on an otherwise
 // idle device; that residency is what every wait relies on.
 #include "sp_score_internal.h"
+#include "sp_lds.h"
 
 namespace sp {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * kWave;
@@ -86,86 +85,6 @@ __global__ __launch_bounds__(256) void fill_empty_kernel(uint4* __restrict__ dst
   if (blockIdx.x == 0 && threadIdx.x == 0) status[0] = 0;
 }
 
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-
-// "at most n vector-memory instructions of this wave still in flight", n known only at run time.
-// Rounded down to a value there is an instruction for (stricter than asked is always correct).
-__device__ __forceinline__ void wait_vmcnt_upto(int n) {
-  if (n >= 12) {
-    if (n >= 16) wait_vmcnt<16>();
-    else if (n >= 14) { if (n >= 15) wait_vmcnt<15>(); else wait_vmcnt<14>(); }
-    else { if (n >= 13) wait_vmcnt<13>(); else wait_vmcnt<12>(); }
-  } else if (n >= 8) {
-    if (n >= 10) { if (n >= 11) wait_vmcnt<11>(); else wait_vmcnt<10>(); }
-    else { if (n >= 9) wait_vmcnt<9>(); else wait_vmcnt<8>(); }
-  } else if (n >= 4) {
-    wait_vmcnt<4>();
-  } else {
-    wait_vmcnt<0>();
-  }
-}
-
-// LDS accesses the compiler does not see as such.  The words touched this way (deposits, counters,
-// fetched log-sum-exps, the running maxima) are never the target of a direct-to-LDS TILE load, so
-// there is no reason to wait for the tile loads in flight before touching them -- which an
-// ordinary LDS access would be made to do.  LDS operations of one wave are performed in order.
-__device__ __forceinline__ uint32_t lds_peek(uint32_t lds_addr) {
-  uint32_t v;
-  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
-  return v;
-}
-__device__ __forceinline__ u32x4 lds_peek128(uint32_t lds_addr) {
-  u32x4 v;
-  asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
-  return v;
-}
-__device__ __forceinline__ void lds_poke32(uint32_t lds_addr, uint32_t v) {
-  asm volatile("ds_write_b32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
-}
-__device__ __forceinline__ void lds_poke128(uint32_t lds_addr, u32x4 v) {
-  asm volatile("ds_write_b128 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
-}
-__device__ __forceinline__ void lds_add(uint32_t lds_addr, uint32_t v) {
-  asm volatile("ds_add_u32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
-}
-__device__ __forceinline__ void lds_or(uint32_t lds_addr, uint32_t v) {
-  asm volatile("ds_or_b32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
-}
-__device__ __forceinline__ void lds_and(uint32_t lds_addr, uint32_t v) {
-  asm volatile("ds_and_b32 %0, %1" : : "v"(lds_addr), "v"(v) : "memory");
-}
-__device__ __forceinline__ uint64_t lds_peek64(uint32_t lds_addr) {
-  uint64_t v;
-  asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr) : "memory");
-  return v;
-}
-__device__ __forceinline__ uint32_t lds_or_rtn(uint32_t lds_addr, uint32_t v) {
-  uint32_t old;
-  asm volatile("ds_or_rtn_b32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(old) : "v"(lds_addr), "v"(v) : "memory");
-  return old;
-}
-__device__ __forceinline__ uint32_t lds_add_rtn(uint32_t lds_addr, uint32_t v) {
-  uint32_t old;
-  asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(old) : "v"(lds_addr), "v"(v) : "memory");
-  return old;
-}
-// 16-byte store with agent-scope coherence (written through to where every XCD can see it)
-__device__ __forceinline__ void store128_agent(void* dst, u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(v) : "memory");
-}
-template <int OFF>
-__device__ __forceinline__ void lds_poke64(uint32_t lds_addr, uint64_t v) {
-  asm volatile("ds_write_b64 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
-}
-template <int OFF>
-__device__ __forceinline__ void lds_fmax(uint32_t lds_addr, float v) {
-  asm volatile("ds_max_f32 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
-}
 // Register i of a 32x32 accumulator tile holds key (i / 4) * 8 + (i % 4) (+ 4 for the upper
 // half-wave).  In the running-max array that key sits at cell (i / 4) * 8 + (i % 4) * 2 (+ 1 for
 // the upper half-wave) of its tile, and query rows are kSmaxPad cells apart modulo 32: the 16
@@ -177,14 +96,6 @@ __device__ __forceinline__ int smax_cell(int key) {  // key within the workgroup
 template <int... I>
 __device__ __forceinline__ void lds_fmax_tile(uint32_t lds_addr, const float (&x)[16], std::integer_sequence<int, I...>) {
   (lds_fmax<((I >> 2) * 8 + (I & 3) * 2) * 4>(lds_addr, x[I]), ...);
-}
-
-// max with the value of lane ^ 1 / lane ^ 2 (inside the quad); folds into v_max_f32_dpp
-__device__ __forceinline__ float max_quad_xor1(float v) {
-  return fmaxf(v, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true)));
-}
-__device__ __forceinline__ float max_quad_xor2(float v) {
-  return fmaxf(v, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x4E, 0xF, 0xF, true)));
 }
 
 __device__ __forceinline__ uint64_t pack_stat(float m, float s) {

@@ -1,0 +1,462 @@
+// Two-pass MFMA scorer for ragged batches (and every other shape the single-pass kernel does
+// not take, as long as the query rows of one KV head fit a 32-column MFMA tile).
+//
+// Same quantity as the other scoring kernels: row softmax of the stored queries against the
+// prompt keys (Sec. 3.2 equation of arXiv 2502.02789), max over heads, max/mean over layers,
+// mean over queries (Sec. 3.2.2).  The K cache is read twice, as by the plain-FMA general
+// kernels, whose workspace layout (64-key tiles numbered over the whole batch, per-tile
+// (max, sum) partials, per-row log-sum-exps) is reused together with their tile-table and
+// combine kernels:
+//
+//   pass 0  every wave owns one 64-key tile of one sequence and walks over (layer, KV head)
+//           "slabs"; per slab it streams the KV head's 32 query rows and its two 32-key tiles
+//           through a private two-slot LDS ring with direct global->LDS loads (XOR-swizzled so
+//           that MFMA operand reads are conflict free), forms the 64 x 32 logits with
+//           v_mfma_f32_32x32x16_bf16 and writes each row's (max, sum exp) over its keys;
+//   combine the general kernels' combine step turns the partials into log-sum-exps;
+//   pass 1  the same walk; the row's log-sum-exp arrives with the query tile, logits become
+//           log2-probabilities, the max over the heads of a KV group is a quad DPP max, the
+//           max over KV heads and layers (or the sum over layers of the per-layer max) stays
+//           in registers: a wave owns its keys for all heads and layers of its layer group;
+//   finish  the layer groups' results (the grid is cut along the layers too, to give the chip
+//           several workgroups per CU to balance) are merged and averaged over the queries.
+//
+// No wave waits for another one: there is no cross-workgroup exchange in this path.
+#include "sp_score_internal.h"
+#include "sp_lds.h"
+
+namespace sp {
+
+constexpr int kTiledWaves = 8;
+constexpr int kTiledThreads = kTiledWaves * kWave;
+constexpr int kWaveKeys = 64;        // keys per wave = the general kernels' tile size (shared tile table)
+constexpr int kTiledTargetWGs = 2048;  // cut the layers into groups until the grid has about this many workgroups
+
+struct TiledDev {
+  int B, N, L, H, H_kv, G, lgG, layers_per_group, n_groups, max_tiles, layer_reduce;
+  float scale;  // logits -> natural-log domain (what the partials and log-sum-exps are kept in)
+  float c;      // scale * log2(e)
+  int64_t ts, hs, T;
+  const uint16_t* q;
+  const int32_t* cu;
+  const int32_t* n_valid;
+  const int32_t* tile_cu;
+  const float* ws_lse;   // [L][B][N][H]
+  float2* part;          // [(l*N + n)*H + h][max_tiles]
+  float* group_scores;   // [n_groups][N][T]: per layer group, log2 of the max probability (layer max) or the
+                         // sum over its layers of the per-layer max probability (layer mean)
+  float* scores;
+  const uint16_t* k[SP_MAX_LAYERS];
+};
+
+template <int D>
+struct TileWalker {
+  static constexpr int KS = D / 16;            // MFMA k-steps per tile
+  static constexpr int ROW_B = D * 2;          // bytes of one row (one key / one query row)
+  static constexpr int TILE_B = 32 * ROW_B;    // 32 rows
+  static constexpr int UNITS = ROW_B / 16;     // 16-byte units per row
+  static constexpr int LOADS = TILE_B / 1024;  // wave-wide 16-byte loads per tile
+  static constexpr int RPI = 64 / UNITS;       // rows covered by one such load
+
+  const TiledDev& p;
+  int wave, lane, half, col;
+  int b, seq0, rows_in;  // sequence, its first token, valid keys of this wave's tile (1..64)
+  int64_t tok0;          // flat token index of the tile's first key
+  int issued, seq_a, seq_b;  // vector-memory instructions issued so far; value right after the loads into slot 0 / 1
+  uint32_t ring_lds, lse_lds, rd0, u0;
+  uint32_t ld_off[4];
+  bf16x8 qf[KS];
+  f32x16 acc[2];
+  float run_m, run_s;
+
+  __device__ __forceinline__ TileWalker(const TiledDev& p_, unsigned char* smem, int tile) : p(p_) {
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    lane = threadIdx.x & 63;
+    half = lane >> 5;
+    col = lane & 31;
+    b = upper_segment(p.tile_cu, p.B, tile);
+    seq0 = p.cu[b];
+    const int key0 = (tile - p.tile_cu[b]) * kWaveKeys;
+    rows_in = min(kWaveKeys, p.cu[b + 1] - seq0 - key0);
+    tok0 = (int64_t)seq0 + key0;
+    issued = seq_a = seq_b = 0;
+    const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+    ring_lds = smem_lds + wave * 2 * TILE_B;
+    lse_lds = smem_lds + kTiledWaves * 2 * TILE_B + wave * 512;
+    // LDS layout of a tile: row r at r*ROW_B; inside a row the 16-byte unit holding head-dim
+    // elements [8u, 8u+8) sits at position u ^ key(r), key(r) = r & 15 (D=128) or (r >> 1) & 7
+    // (D=64): the 16 lanes of an operand read hit 16 distinct bank groups, and a wave-wide
+    // direct load still fills 1 KiB of consecutive LDS.
+    const int key = (D == 128) ? (col & 15) : ((col >> 1) & 7);
+    rd0 = ring_lds + col * ROW_B + ((half ^ (key & 1)) << 4) + ((key >> 1) << 5);
+    const int i = lane / UNITS;
+    const int key_i = (D == 128) ? i : (i >> 1);
+    u0 = (lane % UNITS) ^ key_i;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+      ld_off[jj] = (uint32_t)((int64_t)i * p.ts * 2) + (uint32_t)((u0 ^ ((4 * jj) & (UNITS - 1))) << 4);
+  }
+
+  static size_t smem_bytes() { return (size_t)kTiledWaves * 2 * TILE_B + kTiledWaves * 512; }
+
+  __device__ __forceinline__ static __attribute__((address_space(3))) void* lds_ptr(uint32_t addr) {
+    return reinterpret_cast<__attribute__((address_space(3))) void*>(addr);
+  }
+  __device__ __forceinline__ void note_issued(int k) { issued = __builtin_amdgcn_readfirstlane(issued + k); }
+  __device__ __forceinline__ void mark_slot(int slot) { if (slot & 1) seq_b = issued; else seq_a = issued; }
+  __device__ __forceinline__ void wait_tile(int slot) {
+    wait_vmcnt_upto(__builtin_amdgcn_readfirstlane(issued - ((slot & 1) ? seq_b : seq_a)));
+  }
+  // the slot is about to be overwritten: every LDS read of its previous tile must have been performed
+  __device__ __forceinline__ void slot_free() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+  // Key tile kb (0/1) of KV head g in layer l -> ring slot.  Always exactly LOADS wave-wide
+  // loads; rows beyond the sequence re-read the tile's (or the wave's) first row and are masked later.
+  __device__ __forceinline__ void issue_keys(int l, int g, int kb, int slot) {
+    const uint32_t dst = ring_lds + slot * TILE_B;
+    int rows = min(32, rows_in - kb * 32);
+    asm volatile("" : "+s"(rows));
+    const int64_t tok = rows > 0 ? tok0 + kb * 32 : tok0;
+    const unsigned char* base = reinterpret_cast<const unsigned char*>(p.k[l]) + 2 * ((int64_t)g * p.hs + tok * p.ts);
+    if (rows == 32) {
+#pragma unroll
+      for (int j = 0; j < LOADS; ++j) {
+        uint32_t lane_off = ld_off[j & 3];
+        asm volatile("" : "+v"(lane_off));
+        __builtin_amdgcn_global_load_lds(base + (int64_t)(j * RPI) * p.ts * 2 + (size_t)lane_off, lds_ptr(dst + j * 1024),
+                                         16, 0, 0);
+      }
+    } else {
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int i = ln / UNITS;
+#pragma unroll
+      for (int j = 0; j < LOADS; ++j) {
+        const int r = j * RPI + i;
+        const int64_t row_off = r < rows ? (int64_t)r * p.ts * 2 : 0;
+        const uint32_t unit = u0 ^ ((4 * j) & (UNITS - 1));
+        __builtin_amdgcn_global_load_lds(base + row_off + (unit << 4), lds_ptr(dst + j * 1024), 16, 0, 0);
+      }
+    }
+    note_issued(LOADS);
+    mark_slot(slot);
+  }
+
+  // Query tile of (layer l, KV head g) of this wave's sequence: row r = n*G + j holds
+  // Q[l, b, n, g*G + j, :] (rows beyond G*N repeat row 0; their columns are never used).  With
+  // WITH_LSE the rows' log-sum-exps follow into lse zone `zone` and land with the tile.
+  template <bool WITH_LSE>
+  __device__ __forceinline__ void issue_queries(int l, int g, int slot, int zone) {
+    int rows = p.G * p.N;
+    asm volatile("" : "+s"(rows));
+    const uint32_t dst = ring_lds + slot * TILE_B;
+    const int64_t row0 = (((int64_t)l * p.B + b) * p.N) * p.H + g * p.G;
+    const unsigned char* base = reinterpret_cast<const unsigned char*>(p.q) + 2 * row0 * D;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int i = ln / UNITS;
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+      const int r = j * RPI + i;
+      const int key = (D == 128) ? (r & 15) : ((r >> 1) & 7);
+      const int unit = (ln % UNITS) ^ key;
+      const int rr = r < rows ? r : 0;
+      const uint32_t off = (uint32_t)((rr >> p.lgG) * p.H * ROW_B + (rr & (p.G - 1)) * ROW_B + unit * 16);
+      __builtin_amdgcn_global_load_lds(base + off, lds_ptr(dst + j * 1024), 16, 0, 0);
+    }
+    note_issued(LOADS);
+    if (WITH_LSE) {
+      const int cc = (ln & 31) < rows ? (ln & 31) : 0;
+      const float* src = p.ws_lse + row0 + (cc >> p.lgG) * p.H + (cc & (p.G - 1));
+      __builtin_amdgcn_global_load_lds(src, lds_ptr(lse_lds + zone * 256), 4, 0, 0);
+      note_issued(1);
+    }
+    mark_slot(slot);
+  }
+
+  __device__ __forceinline__ bf16x8 read_unit(int t, int slot) const {
+    uint32_t base = rd0;
+    asm volatile("" : "+v"(base));
+    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+        lds_ptr((base ^ (uint32_t)(t << 5)) + slot * TILE_B));
+  }
+  __device__ __forceinline__ void read_queries(int slot) {
+#pragma unroll
+    for (int t = 0; t < KS; ++t) qf[t] = read_unit(t, slot);
+  }
+  __device__ __forceinline__ void mfma_tile(int kb, int slot) {
+    f32x16 a = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    bf16x8 kf[KS];
+#pragma unroll
+    for (int t = 0; t < KS; ++t) kf[t] = read_unit(t, slot);
+#pragma unroll
+    for (int t = 0; t < KS; ++t) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], a, 0, 0, 0);
+    constexpr int kAhead = KS < 4 ? KS : 4;
+    __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+    for (int t = 0; t < KS - kAhead; ++t) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
+    acc[kb] = a;
+  }
+
+  // Register i of a 32x32 accumulator tile holds key (i / 4) * 8 + (i % 4) (+ 4 for the upper
+  // half-wave) of the tile, for query column `col`.
+  __device__ __forceinline__ void stats_tile(int kb) {
+    f32x16& a = acc[kb];
+    if ((kb + 1) * 32 > rows_in) {  // ragged tail: keys beyond the sequence do not count
+      int left = rows_in - kb * 32 - half * 4;
+      asm volatile("" : "+v"(left));
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if ((i >> 2) * 8 + (i & 3) >= left) a[i] = -INFINITY;
+    }
+    float tm = a[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) tm = fmaxf(tm, a[i]);
+    const float m_new = fmaxf(run_m, tm);
+    const float ref = (m_new == -INFINITY) ? 0.f : m_new;
+    const float off = -ref * p.c;
+    float s0 = run_s * fast_exp2(fmaf(run_m, p.c, off)), s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i += 4) {
+      s0 += fast_exp2(fmaf(a[i], p.c, off));
+      s1 += fast_exp2(fmaf(a[i + 1], p.c, off));
+      s2 += fast_exp2(fmaf(a[i + 2], p.c, off));
+      s3 += fast_exp2(fmaf(a[i + 3], p.c, off));
+    }
+    run_m = m_new;
+    run_s = (s0 + s1) + (s2 + s3);
+  }
+
+  // pass 0, end of a slab: the row's (max, sum exp) over this wave's keys, in the natural-log domain
+  __device__ __forceinline__ void store_partial(int l, int g, int tile) {
+    const float pm = __shfl_xor(run_m, 32, kWave), ps = __shfl_xor(run_s, 32, kWave);
+    const float mn = fmaxf(run_m, pm);
+    const float ref = (mn == -INFINITY) ? 0.f : mn;
+    const float z = run_s * fast_exp2((run_m - ref) * p.c) + ps * fast_exp2((pm - ref) * p.c);
+    int c = col;
+    asm volatile("" : "+v"(c));
+    if (half == 0 && c < p.G * p.N) {
+      const int n = c >> p.lgG, h = g * p.G + (c & (p.G - 1));
+      p.part[((int64_t)(l * p.N + n) * p.H + h) * p.max_tiles + tile] = make_float2(mn * p.scale, z);
+    }
+    note_issued(1);
+  }
+};
+
+// One slab's step along the stream: tiles in stream order are Q(s) K0(s) K1(s) Q(s+1) ...,
+// tile number x of slab s sits in ring slot (3s + x) & 1.
+struct SlabCursor {
+  int l, g;
+  __device__ __forceinline__ void advance(int H_kv, int l_last) {
+    if (++g == H_kv) { g = 0; l = min(l + 1, l_last); }  // past the end: the last layer again (nobody consumes it)
+  }
+};
+
+template <int D, int PASS, bool MEAN>
+__global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledDev p) {
+  extern __shared__ __align__(1024) unsigned char smem[];
+  using TW = TileWalker<D>;
+  const int tile = blockIdx.x * kTiledWaves + (threadIdx.x >> 6);
+  if (tile >= p.tile_cu[p.B]) return;  // (no workgroup barrier anywhere in this kernel)
+  const int l0 = blockIdx.y * p.layers_per_group;
+  const int l1 = min(p.L, l0 + p.layers_per_group);
+  if (l0 >= l1) return;
+  TW w(p, smem, __builtin_amdgcn_readfirstlane(tile));
+  const int n_slabs = (l1 - l0) * p.H_kv;
+
+  float smax[PASS ? 32 : 1], tot[(PASS && MEAN) ? 32 : 1];
+#pragma unroll
+  for (int i = 0; i < (PASS ? 32 : 1); ++i) smax[i] = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < ((PASS && MEAN) ? 32 : 1); ++i) tot[i] = 0.f;
+
+  SlabCursor cur{l0, 0}, nxt{l0, 0};
+  w.template issue_queries<PASS == 1>(l0, 0, 0, 0);
+  w.issue_keys(l0, 0, 0, 1);
+  nxt.advance(p.H_kv, l1 - 1);
+
+  auto body = [&](auto par_tag) __attribute__((always_inline)) {
+    constexpr int PAR = decltype(par_tag)::value;  // parity of the slab = ring slot of its query tile
+    w.wait_tile(PAR);
+    w.read_queries(PAR);
+    float neg_lse2 = 0.f;
+    if (PASS) {
+      int c = w.col;
+      asm volatile("" : "+v"(c));
+      neg_lse2 = -1.4426950408889634f * __uint_as_float(lds_peek(w.lse_lds + PAR * 256 + c * 4));
+    }
+    w.slot_free();
+    w.issue_keys(cur.l, cur.g, 1, PAR);
+    w.run_m = -INFINITY;
+    w.run_s = 0.f;
+    // key tile 0
+    w.wait_tile(PAR ^ 1);
+    w.mfma_tile(0, PAR ^ 1);
+    w.slot_free();
+    w.template issue_queries<PASS == 1>(nxt.l, nxt.g, PAR ^ 1, PAR ^ 1);
+    if (!PASS) w.stats_tile(0);
+    // key tile 1
+    w.wait_tile(PAR);
+    w.mfma_tile(1, PAR);
+    w.slot_free();
+    w.issue_keys(nxt.l, nxt.g, 0, PAR);
+    if (!PASS) {
+      w.stats_tile(1);
+      w.store_partial(cur.l, cur.g, tile);
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = fmaf(w.acc[kb][i], p.c, neg_lse2);
+        if (p.lgG >= 1) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) x[i] = max_quad_xor1(x[i]);
+        }
+        if (p.lgG >= 2) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) x[i] = max_quad_xor2(x[i]);
+        }
+        if (p.lgG >= 3) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) x[i] = fmaxf(x[i], __shfl_xor(x[i], 4, kWave));
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) smax[kb * 16 + i] = fmaxf(smax[kb * 16 + i], x[i]);
+      }
+      if (MEAN && cur.g == p.H_kv - 1) {  // the layer is complete: its max probability joins the sum
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+          tot[i] += fast_exp2(smax[i]);
+          smax[i] = -INFINITY;
+        }
+      }
+    }
+    cur = nxt;
+    nxt.advance(p.H_kv, l1 - 1);
+  };
+
+  for (int s = 0; s < n_slabs; s += 2) {
+    body(std::integral_constant<int, 0>{});
+    if (s + 1 < n_slabs) body(std::integral_constant<int, 1>{});
+  }
+  wait_vmcnt<0>();  // loads issued past the end land before the wave (and its LDS) goes away
+
+  if (PASS) {
+    int c = w.col, h = w.half;
+    asm volatile("" : "+v"(c), "+v"(h));
+    if (c < p.G * p.N && (c & (p.G - 1)) == 0) {
+      float* dst = p.group_scores + ((int64_t)blockIdx.y * p.N + (c >> p.lgG)) * p.T + w.tok0;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = kb * 32 + (i >> 2) * 8 + h * 4 + (i & 3);
+          if (key < w.rows_in) dst[key] = MEAN ? tot[kb * 16 + i] : smax[kb * 16 + i];
+        }
+    }
+  }
+}
+
+// merge the layer groups and average over the valid queries; one thread per token
+__global__ __launch_bounds__(256) void tiled_finish_kernel(const TiledDev p) {
+  const int64_t tok = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (tok >= p.T) return;
+  const int b = upper_segment(p.cu, p.B, (int)tok);
+  int nv = p.n_valid ? p.n_valid[b] : p.N;
+  nv = max(1, min(nv, p.N));
+  float sum = 0.f;
+  for (int n = 0; n < nv; ++n) {
+    if (p.layer_reduce == SP_LAYER_MAX) {
+      float m = -INFINITY;
+      for (int g = 0; g < p.n_groups; ++g) m = fmaxf(m, p.group_scores[((int64_t)g * p.N + n) * p.T + tok]);
+      sum += fast_exp2(m);
+    } else {
+      for (int g = 0; g < p.n_groups; ++g) sum += p.group_scores[((int64_t)g * p.N + n) * p.T + tok];
+    }
+  }
+  const float denom = (p.layer_reduce == SP_LAYER_MAX) ? (float)nv : (float)nv * (float)p.L;
+  p.scores[tok] = sum / denom;
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+static int tiled_max_tiles(const sp_score_args* a) { return (int)(a->T / kWaveKeys) + a->B; }
+
+static void tiled_grouping(const sp_score_args* a, int* layers_per_group, int* n_groups) {
+  const int wgs = (tiled_max_tiles(a) + kTiledWaves - 1) / kTiledWaves;
+  int groups = std::min(a->L, (kTiledTargetWGs + wgs - 1) / wgs);
+  groups = std::max(groups, 1);
+  *layers_per_group = (a->L + groups - 1) / groups;
+  *n_groups = (a->L + *layers_per_group - 1) / *layers_per_group;
+}
+
+bool tiled_supported(const sp_score_args* a) {
+  const int G = a->H / a->H_kv;
+  if (a->rope_theta != 0.f) return false;  // un-rotated caches take the plain-FMA kernels
+  if (G != 1 && G != 2 && G != 4 && G != 8) return false;
+  if (G * a->N > 32) return false;
+  if (a->T < 1) return false;
+  return true;
+}
+
+size_t tiled_extra_workspace_bytes(const sp_score_args* a) {
+  if (!tiled_supported(a)) return 0;
+  int lpg, groups;
+  tiled_grouping(a, &lpg, &groups);
+  return align_up(sizeof(float) * (size_t)groups * a->N * (size_t)a->T, 256);
+}
+
+template <int D, int PASS, bool MEAN>
+static sp_status launch_tiled(const TiledDev& dev, hipStream_t stream) {
+  auto kernel = tiled_score_kernel<D, PASS, MEAN>;
+  const size_t smem = TileWalker<D>::smem_bytes();
+  static bool prepared = false;
+  if (!prepared) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)smem) != hipSuccess)
+      return SP_ELAUNCH;
+    prepared = true;
+  }
+  const dim3 grid((dev.max_tiles + kTiledWaves - 1) / kTiledWaves, dev.n_groups);
+  hipLaunchKernelGGL(kernel, grid, dim3(kTiledThreads), smem, stream, dev);
+  return launch_status();
+}
+
+template <int D>
+static sp_status tiled_passes(const TiledDev& dev, const ScoreDev& gen, hipStream_t stream) {
+  sp_status st = launch_tiled<D, 0, false>(dev, stream);
+  if (st != SP_OK) return st;
+  launch_lse_combine(gen, stream);
+  st = dev.layer_reduce == SP_LAYER_MEAN ? launch_tiled<D, 1, true>(dev, stream) : launch_tiled<D, 1, false>(dev, stream);
+  if (st != SP_OK) return st;
+  hipLaunchKernelGGL(tiled_finish_kernel, dim3((unsigned)((dev.T + 255) / 256)), dim3(256), 0, stream, dev);
+  return launch_status();
+}
+
+// `gen` carries the general kernels' workspace pointers (tile table, partials, log-sum-exps),
+// already laid out and with the tile table kernel launched; `extra` is this path's own part.
+sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, hipStream_t stream) {
+  TiledDev dev;
+  dev.B = a->B; dev.N = a->N; dev.L = a->L; dev.H = a->H; dev.H_kv = a->H_kv; dev.G = a->H / a->H_kv;
+  dev.lgG = dev.G == 1 ? 0 : dev.G == 2 ? 1 : dev.G == 4 ? 2 : 3;
+  tiled_grouping(a, &dev.layers_per_group, &dev.n_groups);
+  dev.max_tiles = gen.max_tiles;
+  dev.layer_reduce = a->layer_reduce;
+  dev.scale = a->scale;
+  dev.c = a->scale * 1.4426950408889634f;
+  dev.ts = a->k_token_stride; dev.hs = a->k_head_stride; dev.T = a->T;
+  dev.q = gen.q; dev.cu = gen.cu; dev.n_valid = gen.n_valid; dev.tile_cu = gen.tile_cu;
+  dev.ws_lse = gen.ws_lse; dev.part = gen.part;
+  dev.group_scores = static_cast<float*>(extra);
+  dev.scores = a->d_scores;
+  for (int l = 0; l < SP_MAX_LAYERS; ++l) dev.k[l] = gen.k[l];
+  return a->d == 64 ? tiled_passes<64>(dev, gen, stream) : tiled_passes<128>(dev, gen, stream);
+}
+
+}  // namespace sp

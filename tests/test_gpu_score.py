@@ -200,3 +200,33 @@ def test_rotation_by_position_zero_changes_nothing():
     a, la = hp.gpu_score(q, k, cu, 2, 0.125, orc.LAYER_MAX, general=True)
     b, lb = hp.gpu_score(q, k, cu, 2, 0.125, orc.LAYER_MAX, rope_theta=1e4, q_pos=zero_pos)
     assert (a.view(np.uint32) == b.view(np.uint32)).all() and (la.view(np.uint32) == lb.view(np.uint32)).all()
+
+
+# The ragged-batch MFMA kernels (what sp_score picks for B > 1): every tile-boundary case of
+# the 64-key wave tiles and of their two 32-key halves, several layer groups, both modes.
+@pytest.mark.parametrize("shape", [
+    dict(H=32, H_kv=8, d=128, N=1, L=5),
+    dict(H=32, H_kv=8, d=128, N=8, L=3),
+    dict(H=24, H_kv=3, d=64, N=4, L=4),
+    dict(H=5, H_kv=5, d=64, N=16, L=2),
+])
+def test_ragged_batch_tile_boundaries(shape):
+    lens = (1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 0, 700)
+    w = synth.scaled(synth.workload(4), seqlens=lens, salient_frac=0.02, salient_run=1, **shape)
+    inp = synth.make_qk(w)
+    nv = np.array([1 + (i % shape["N"]) for i in range(len(lens))], dtype=np.int32)
+    for mode in MODES:
+        _check(w, inp, mode, general=False, n_valid=nv)
+
+
+def test_ragged_batch_paths_agree_and_repeat_bitwise():
+    w = synth.scaled(synth.workload(4), seqlens=(1500, 77, 2049, 640), L=4)
+    inp = synth.make_qk(w)
+    scale = 1.0 / math.sqrt(w.d)
+    for mode in MODES:
+        a, la = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, scale, mode)
+        b, lb = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, scale, mode)
+        g, lg = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, scale, mode, general=True)
+        assert np.array_equal(a, b) and np.array_equal(la, lb)
+        np.testing.assert_allclose(a, g, rtol=2e-3, atol=1e-12)
+        np.testing.assert_allclose(la, lg, rtol=0, atol=2e-4)
