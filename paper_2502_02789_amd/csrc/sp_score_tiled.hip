@@ -30,7 +30,11 @@ namespace sp {
 constexpr int kTiledWaves = 8;
 constexpr int kTiledThreads = kTiledWaves * kWave;
 constexpr int kWaveKeys = 64;        // keys per wave = the general kernels' tile size (shared tile table)
-constexpr int kTiledTargetWGs = 2048;  // cut the layers into groups until the grid has about this many workgroups
+constexpr int kPartBufBytes = 3072;  // per wave: pass 0 collects the slabs' row statistics here before writing them out
+#ifndef SP_TILED_TARGET_WGS
+#define SP_TILED_TARGET_WGS 2048
+#endif
+constexpr int kTiledTargetWGs = SP_TILED_TARGET_WGS;  // cut the layers into groups until the grid has about this many workgroups
 
 struct TiledDev {
   int B, N, L, H, H_kv, G, lgG, layers_per_group, n_groups, max_tiles, layer_reduce;
@@ -63,7 +67,8 @@ struct TileWalker {
   int b, seq0, rows_in;  // sequence, its first token, valid keys of this wave's tile (1..64)
   int64_t tok0;          // flat token index of the tile's first key
   int issued, seq_a, seq_b;  // vector-memory instructions issued so far; value right after the loads into slot 0 / 1
-  uint32_t ring_lds, lse_lds, rd0, u0;
+  uint32_t ring_lds, lse_lds, part_lds, rd0, u0;
+  int part_n;            // slabs waiting in the statistics buffer
   uint32_t ld_off[4];
   bf16x8 qf[KS];
   f32x16 acc[2];
@@ -83,6 +88,8 @@ struct TileWalker {
     const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem);
     ring_lds = smem_lds + wave * 2 * TILE_B;
     lse_lds = smem_lds + kTiledWaves * 2 * TILE_B + wave * 512;
+    part_lds = smem_lds + kTiledWaves * (2 * TILE_B + 512) + wave * kPartBufBytes;
+    part_n = 0;
     // LDS layout of a tile: row r at r*ROW_B; inside a row the 16-byte unit holding head-dim
     // elements [8u, 8u+8) sits at position u ^ key(r), key(r) = r & 15 (D=128) or (r >> 1) & 7
     // (D=64): the 16 lanes of an operand read hit 16 distinct bank groups, and a wave-wide
@@ -97,7 +104,7 @@ struct TileWalker {
       ld_off[jj] = (uint32_t)((int64_t)i * p.ts * 2) + (uint32_t)((u0 ^ ((4 * jj) & (UNITS - 1))) << 4);
   }
 
-  static size_t smem_bytes() { return (size_t)kTiledWaves * 2 * TILE_B + kTiledWaves * 512; }
+  static size_t smem_bytes() { return (size_t)kTiledWaves * (2 * TILE_B + 512 + kPartBufBytes); }
 
   __device__ __forceinline__ static __attribute__((address_space(3))) void* lds_ptr(uint32_t addr) {
     return reinterpret_cast<__attribute__((address_space(3))) void*>(addr);
@@ -231,19 +238,43 @@ struct TileWalker {
     run_s = (s0 + s1) + (s2 + s3);
   }
 
-  // pass 0, end of a slab: the row's (max, sum exp) over this wave's keys, in the natural-log domain
-  __device__ __forceinline__ void store_partial(int l, int g, int tile) {
+  // pass 0, end of a slab: the row's (max, sum exp) over this wave's keys, in the natural-log
+  // domain, goes into the wave's LDS buffer.  (Vector-memory instructions of a wave complete in
+  // order: a store per slab makes the next tile's wait sit out the store's round trip.)
+  __device__ __forceinline__ void keep_partial() {
     const float pm = __shfl_xor(run_m, 32, kWave), ps = __shfl_xor(run_s, 32, kWave);
     const float mn = fmaxf(run_m, pm);
     const float ref = (mn == -INFINITY) ? 0.f : mn;
     const float z = run_s * fast_exp2((run_m - ref) * p.c) + ps * fast_exp2((pm - ref) * p.c);
     int c = col;
     asm volatile("" : "+v"(c));
-    if (half == 0 && c < p.G * p.N) {
-      const int n = c >> p.lgG, h = g * p.G + (c & (p.G - 1));
-      p.part[((int64_t)(l * p.N + n) * p.H + h) * p.max_tiles + tile] = make_float2(mn * p.scale, z);
+    const int rows = p.G * p.N;
+    if (half == 0 && c < rows)
+      lds_poke64<0>(part_lds + (part_n * rows + c) * 8, ((uint64_t)__float_as_uint(z) << 32) | __float_as_uint(mn * p.scale));
+    part_n = __builtin_amdgcn_readfirstlane(part_n + 1);
+  }
+  __device__ __forceinline__ bool partials_full() const { return (part_n + 1) * p.G * p.N * 8 > kPartBufBytes; }
+  // write the buffered statistics of slabs [first, first + part_n) of the layer group starting
+  // at layer l0 out, 64 (slab, row) pairs per store instruction
+  __device__ __forceinline__ void flush_partials(int first, int l0, int tile) {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int rows = p.G * p.N, total = part_n * rows;
+#pragma unroll 1
+    for (int base = 0; base < total; base += kWave) {
+      const int idx = base + ln;
+      if (idx < total) {  // (never empty: lane 0 is always inside)
+        const uint64_t v = lds_peek64(part_lds + idx * 8);
+        const int j = idx / rows, c = idx - j * rows;
+        const int s = first + j;
+        const int l = l0 + s / p.H_kv, g = s % p.H_kv;
+        const int n = c >> p.lgG, h = g * p.G + (c & (p.G - 1));
+        p.part[((int64_t)(l * p.N + n) * p.H + h) * p.max_tiles + tile] =
+            make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
+      }
+      note_issued(1);
     }
-    note_issued(1);
+    part_n = 0;
   }
 };
 
@@ -275,6 +306,7 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
   for (int i = 0; i < ((PASS && MEAN) ? 32 : 1); ++i) tot[i] = 0.f;
 
   SlabCursor cur{l0, 0}, nxt{l0, 0};
+  int done = 0;  // pass 0: slabs whose statistics have been written out
   w.template issue_queries<PASS == 1>(l0, 0, 0, 0);
   w.issue_keys(l0, 0, 0, 1);
   nxt.advance(p.H_kv, l1 - 1);
@@ -306,7 +338,11 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
     w.issue_keys(nxt.l, nxt.g, 0, PAR);
     if (!PASS) {
       w.stats_tile(1);
-      w.store_partial(cur.l, cur.g, tile);
+      w.keep_partial();
+      if (w.partials_full()) {
+        done += w.part_n;
+        w.flush_partials(done - w.part_n, l0, tile);
+      }
     } else {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
@@ -344,6 +380,7 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
     body(std::integral_constant<int, 0>{});
     if (s + 1 < n_slabs) body(std::integral_constant<int, 1>{});
   }
+  if (!PASS && w.part_n > 0) w.flush_partials(done, l0, tile);
   wait_vmcnt<0>();  // loads issued past the end land before the wave (and its LDS) goes away
 
   if (PASS) {

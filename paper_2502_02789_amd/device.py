@@ -20,6 +20,17 @@ def bits_from_bf16(t: torch.Tensor) -> np.ndarray:
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+# The three configurations the paper compares (Sec. 4, list of evaluated variants), as settings
+# of the same three calls: the plain variant scores with the last prompt token only and keeps
+# single tokens by their un-smoothed scores; "full" adds pooling and chunk selection; "full_lah"
+# adds the look-ahead queries.  (Window and chunk size are the synthetic workloads' choices.)
+VARIANTS = {
+    "raw": dict(n_queries=1, chunk=1, pool_window=1),
+    "full": dict(n_queries=1, chunk=32, pool_window=13),
+    "full_lah": dict(n_queries=8, chunk=32, pool_window=13),
+}
+
+
 class Scorer:
     """Holds the argument struct, outputs and workspace of one sp_score problem."""
 

@@ -90,3 +90,12 @@ def test_workload_4_ragged_batch_full_tokens():
 
 def test_workload_5_full_tokens_and_full_embedding_table():
     _run_whole_path(synth.scaled(synth.workload(5), L=4), orc.LAYER_MAX, with_table=True)
+
+
+@pytest.mark.parametrize("variant", ["raw", "full", "full_lah"])
+def test_paper_variants_as_presets(variant):
+    from paper_2502_02789_amd import device as dev
+    v = dev.VARIANTS[variant]
+    w = synth.scaled(synth.workload(3), seqlens=(3000, 1111), L=3, N=v["n_queries"], chunk=v["chunk"],
+                     pool_window=v["pool_window"], keep_rate=0.2, salient_frac=0.02, salient_run=1)
+    _run_whole_path(w, orc.LAYER_MAX)
