@@ -150,14 +150,30 @@ __global__ __launch_bounds__(1024) void select_kernel(const SelDev p) {
       if ((key & himask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255u)], 1);
     }
     __syncthreads();
-    if (t == 0) {
-      int above = 0, bucket = 255;
-      for (; bucket > 0; --bucket) {
-        if (above + hist[bucket] >= need) break;
-        above += hist[bucket];
+    // the bucket holding the need-th largest remaining key: the highest bucket whose count, added to
+    // the counts above it, reaches `need`.  One wave, four buckets per lane, suffix sums by shuffles.
+    if (t < kWave) {
+      int h[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) h[u] = hist[4 * t + u];
+      const int own = h[0] + h[1] + h[2] + h[3];
+      int suffix = own;  // counts of this lane's buckets and of all higher lanes'
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const int v = __shfl_down(suffix, off, kWave);
+        if (t + off < kWave) suffix += v;
       }
-      s_bucket = bucket;
-      s_need = need - above;
+      int above = suffix - own;
+      if (above < need && need <= suffix) {  // exactly one lane: the keys still in play number at least `need`
+        int bucket = 4 * t;
+#pragma unroll
+        for (int u = 3; u >= 0; --u) {
+          if (above + h[u] >= need) { bucket = 4 * t + u; break; }
+          above += h[u];
+        }
+        s_bucket = bucket;
+        s_need = need - above;
+      }
     }
     __syncthreads();
     prefix |= (uint64_t)s_bucket << shift;
