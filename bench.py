@@ -34,8 +34,10 @@ def measured_traffic(workload, general):
 
 
 def cpu_baseline(w, inp, layer_reduce, sample_layers):
-    """Times the fp64 oracle, unchanged, on a layer subset of the same inputs (full prompt,
-    all heads and queries) plus selection and gather on its scores; cost is linear in layers."""
+    """Times the fp64 oracle, unchanged, on the same inputs (full prompt, all heads and queries)
+    plus selection and gather on its scores.  sample_layers = 0: a two-layer pilot decides how
+    many layers fit about 15 s (cost is linear in layers); when the whole depth fits, whole
+    passes are repeated until about 10 s have been spent and their mean is reported."""
     import numpy as np
     from oracle import specprefill_oracle as orc
     try:
@@ -43,20 +45,41 @@ def cpu_baseline(w, inp, layer_reduce, sample_layers):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    sub_q = inp["q"][:sample_layers]
-    sub_k = inp["k"][:sample_layers]
-    t0 = time.perf_counter()
-    scores, _ = orc.token_importance(sub_q, sub_k, inp["cu_seqlens"], 1.0 / math.sqrt(w.d), layer_reduce)
+    scale = 1.0 / math.sqrt(w.d)
+
+    def score_pass(n_layers):
+        t0 = time.perf_counter()
+        scores, _ = orc.token_importance(inp["q"][:n_layers], inp["k"][:n_layers], inp["cu_seqlens"], scale,
+                                         layer_reduce)
+        return scores, time.perf_counter() - t0
+
+    note = ""
+    if sample_layers <= 0:
+        pilot = min(2, w.L)
+        _, t_pilot = score_pass(pilot)
+        sample_layers = max(pilot, min(w.L, int(15.0 / max(t_pilot / pilot, 1e-6))))
+        note = f" (after a {pilot}-layer pilot of {t_pilot:.2f} s)"
+    sample_layers = min(sample_layers, w.L)
+    passes, spent = 0, 0.0
+    while True:
+        scores, dt = score_pass(sample_layers)
+        passes += 1
+        spent += dt
+        if sample_layers < w.L or spent >= 10.0 or passes >= 20:
+            break
+    t_score = spent / passes
     t1 = time.perf_counter()
     kept, cu_keep, _, _ = orc.pool_select(scores.astype(np.float32), inp["cu_seqlens"], w.chunk, w.pool_window,
                                           w.keep_rate)
     orc.gather(kept, cu_keep, inp["cu_seqlens"], inp["token_ids"])
-    t2 = time.perf_counter()
-    est_full = (t1 - t0) * (w.L / sample_layers) + (t2 - t1)
+    t_sel = time.perf_counter() - t1
+    est_full = t_score * (w.L / sample_layers) + t_sel
+    what = (f"all {w.L} layers, mean of {passes} whole passes of {t_score:.2f} s" if sample_layers == w.L else
+            f"{sample_layers} of {w.L} layers in {t_score:.2f} s, scaled linearly in layers")
     return {
         "value": w.T / est_full, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-        "sample": f"{sample_layers} of {w.L} layers of the same inputs (full {w.T}-token prompt, all heads and "
-                  f"queries) in {t1 - t0:.2f} s, scaled linearly in layers, plus selection+gather {t2 - t1:.3f} s",
+        "sample": f"{what}{note}; same inputs (full {w.T}-token prompt, all heads and queries); "
+                  f"plus selection+gather {t_sel:.3f} s",
     }
 
 
@@ -68,7 +91,8 @@ def main():
     ap.add_argument("--workload", type=int, default=3, help="1..5, numbered as the benchmark configs")
     ap.add_argument("--layer-reduce", choices=["max", "mean"], default="max")
     ap.add_argument("--general", action="store_true", help="force the general two-pass scoring kernels")
-    ap.add_argument("--cpu-sample-layers", type=int, default=4)
+    ap.add_argument("--cpu-sample-layers", type=int, default=0,
+                    help="layers the oracle is timed on (0: as many as fit about 15 s, all of them if possible)")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="also launch a plain device copy of MIB MiB three times outside the timed region, so a "
@@ -171,7 +195,7 @@ def main():
     }
     if not args.skip_cpu:
         out["cpu_baseline"] = cpu_baseline(w, inp, 0 if args.layer_reduce == "max" else 1,
-                                           min(args.cpu_sample_layers, w.L))
+                                           args.cpu_sample_layers)
     print(json.dumps(out), flush=True)
 
 
