@@ -29,7 +29,8 @@ def measured_traffic(workload, general):
     if general or not os.path.exists(path):
         return None
     with open(path) as f:
-        entry = json.load(f).get(f"workload{workload}:stream_score_kernel")
+        table = json.load(f)
+    entry = table.get(f"workload{workload}:stream_score_kernel") or table.get(f"workload{workload}:sp_score")
     return None if entry is None else entry["traffic_bytes_per_launch"]
 
 
