@@ -31,6 +31,8 @@ constexpr int kTiledWaves = 8;
 constexpr int kTiledThreads = kTiledWaves * kWave;
 constexpr int kWaveKeys = 64;        // keys per wave = the general kernels' tile size (shared tile table)
 constexpr int kPartBufBytes = 3072;  // per wave: pass 0 collects the slabs' row statistics here before writing them out
+constexpr int kKeepRows = 4;         // "keep" mode: a KV head has at most this many query rows (16 bytes of logits per key)
+constexpr int kKeepStageBytes = kWaveKeys * kKeepRows * 4;  // taken from the end of the statistics buffer
 #ifndef SP_TILED_TARGET_WGS
 #define SP_TILED_TARGET_WGS 2048
 #endif
@@ -49,6 +51,7 @@ struct TiledDev {
   float2* part;          // [(l*N + n)*H + h][max_tiles]
   float* group_scores;   // [n_groups][N][T]: per layer group, log2 of the max probability (layer max) or the
                          // sum over its layers of the per-layer max probability (layer mean)
+  float* logits;         // keep mode: [L][H_kv][T][kKeepRows] base-2 logits (scale * log2(e) applied), else null
   float* scores;
   const uint16_t* k[SP_MAX_LAYERS];
 };
@@ -253,7 +256,34 @@ struct TileWalker {
       lds_poke64<0>(part_lds + (part_n * rows + c) * 8, ((uint64_t)__float_as_uint(z) << 32) | __float_as_uint(mn * p.scale));
     part_n = __builtin_amdgcn_readfirstlane(part_n + 1);
   }
-  __device__ __forceinline__ bool partials_full() const { return (part_n + 1) * p.G * p.N * 8 > kPartBufBytes; }
+  __device__ __forceinline__ bool partials_full(int buf_bytes) const { return (part_n + 1) * p.G * p.N * 8 > buf_bytes; }
+
+  // keep mode, end of a slab: the wave's 64 x (G*N <= 4) logits, scaled to base 2, as 16 bytes
+  // per key in the key's lane, after a turn through LDS (a lane holds one query row of 32 keys,
+  // the store wants one key's rows per lane).  A slab's logits are one dense 1 KiB store; the
+  // caller collects several slabs in registers and stores them together (a store per slab would
+  // make the tile waits sit out a store round trip every slab).
+  __device__ __forceinline__ u32x4 transposed_logits() {
+    const uint32_t stage = part_lds + kPartBufBytes - kKeepStageBytes;
+    int c = col, h = half, ln = lane;
+    asm volatile("" : "+v"(c), "+v"(h), "+v"(ln));
+    if (c < kKeepRows) {  // (columns beyond G*N repeat row 0: finite values nobody reads)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          lds_poke32(stage + ((kb * 32 + (i >> 2) * 8 + h * 4 + (i & 3)) * kKeepRows + c) * 4,
+                     __float_as_uint(acc[kb][i] * p.c));
+    }
+    return lds_peek128(stage + ln * 16);  // (LDS operations of a wave are performed in order)
+  }
+  __device__ __forceinline__ void store_logits(const u32x4& v, int l, int g) {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    if (ln < rows_in)  // (never empty: a tile has at least one key)
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.logits + (((int64_t)l * p.H_kv + g) * p.T + tok0 + ln) * kKeepRows));
+    note_issued(1);
+  }
   // write the buffered statistics of slabs [first, first + part_n) of the layer group starting
   // at layer l0 out, 64 (slab, row) pairs per store instruction
   __device__ __forceinline__ void flush_partials(int first, int l0, int tile) {
@@ -299,12 +329,28 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
   TW w(p, smem, __builtin_amdgcn_readfirstlane(tile));
   const int n_slabs = (l1 - l0) * p.H_kv;
 
-  float smax[PASS ? 32 : 1], tot[(PASS && MEAN) ? 32 : 1];
+  // PASS 0: row statistics; 1: probabilities; 2: row statistics, and the logits are kept for logit_score_kernel
+  float smax[PASS == 1 ? 32 : 1], tot[(PASS == 1 && MEAN) ? 32 : 1];
 #pragma unroll
-  for (int i = 0; i < (PASS ? 32 : 1); ++i) smax[i] = -INFINITY;
+  for (int i = 0; i < (PASS == 1 ? 32 : 1); ++i) smax[i] = -INFINITY;
 #pragma unroll
-  for (int i = 0; i < ((PASS && MEAN) ? 32 : 1); ++i) tot[i] = 0.f;
+  for (int i = 0; i < ((PASS == 1 && MEAN) ? 32 : 1); ++i) tot[i] = 0.f;
 
+  // keep mode: the logits of up to kKeepHeld slabs wait here, slab held_first + k in held[k]
+  constexpr int kKeepHeld = 8;
+  u32x4 held[PASS == 2 ? kKeepHeld : 1];
+  int held_n = 0, held_first = 0;
+  auto flush_held = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < (PASS == 2 ? kKeepHeld : 1); ++k) {
+      if (k < held_n) {
+        const int sl = held_first + k;
+        w.store_logits(held[k], l0 + sl / p.H_kv, sl % p.H_kv);
+      }
+    }
+    held_first += held_n;
+    held_n = 0;
+  };
   SlabCursor cur{l0, 0}, nxt{l0, 0};
   int done = 0;  // pass 0: slabs whose statistics have been written out
   w.template issue_queries<PASS == 1>(l0, 0, 0, 0);
@@ -316,7 +362,7 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
     w.wait_tile(PAR);
     w.read_queries(PAR);
     float neg_lse2 = 0.f;
-    if (PASS) {
+    if (PASS == 1) {
       int c = w.col;
       asm volatile("" : "+v"(c));
       neg_lse2 = -1.4426950408889634f * __uint_as_float(lds_peek(w.lse_lds + PAR * 256 + c * 4));
@@ -330,16 +376,31 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
     w.mfma_tile(0, PAR ^ 1);
     w.slot_free();
     w.template issue_queries<PASS == 1>(nxt.l, nxt.g, PAR ^ 1, PAR ^ 1);
-    if (!PASS) w.stats_tile(0);
+    if (PASS != 1) w.stats_tile(0);
     // key tile 1
     w.wait_tile(PAR);
     w.mfma_tile(1, PAR);
     w.slot_free();
     w.issue_keys(nxt.l, nxt.g, 0, PAR);
-    if (!PASS) {
+    if (PASS != 1) {
       w.stats_tile(1);
+      if constexpr (PASS == 2) {
+        const u32x4 v = w.transposed_logits();
+        switch (held_n) {
+          case 0: held[0] = v; break;
+          case 1: held[1] = v; break;
+          case 2: held[2] = v; break;
+          case 3: held[3] = v; break;
+          case 4: held[4] = v; break;
+          case 5: held[5] = v; break;
+          case 6: held[6] = v; break;
+          default: held[7] = v; break;
+        }
+        held_n = __builtin_amdgcn_readfirstlane(held_n + 1);
+        if (held_n == kKeepHeld) flush_held();
+      }
       w.keep_partial();
-      if (w.partials_full()) {
+      if (w.partials_full(PASS == 2 ? kPartBufBytes - kKeepStageBytes : kPartBufBytes)) {
         done += w.part_n;
         w.flush_partials(done - w.part_n, l0, tile);
       }
@@ -380,10 +441,11 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
     body(std::integral_constant<int, 0>{});
     if (s + 1 < n_slabs) body(std::integral_constant<int, 1>{});
   }
-  if (!PASS && w.part_n > 0) w.flush_partials(done, l0, tile);
+  if (PASS == 2 && held_n > 0) flush_held();
+  if (PASS != 1 && w.part_n > 0) w.flush_partials(done, l0, tile);
   wait_vmcnt<0>();  // loads issued past the end land before the wave (and its LDS) goes away
 
-  if (PASS) {
+  if (PASS == 1) {
     int c = w.col, h = w.half;
     asm volatile("" : "+v"(c), "+v"(h));
     if (c < p.G * p.N && (c & (p.G - 1)) == 0) {
@@ -397,6 +459,77 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
         }
     }
   }
+}
+
+// keep mode, second pass: one thread per token walks over the kept logits of all layers and KV
+// heads (16 bytes each, neighbouring tokens neighbouring in memory), turns them into
+// log2-probabilities with the rows' log-sum-exps and aggregates as the other kernels do.
+template <bool MEAN>
+__global__ __launch_bounds__(256) void logit_score_kernel(const TiledDev p) {
+  // four threads per token, each with every fourth layer: four times the loads in flight
+  const int64_t tok = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 2;
+  const int part = threadIdx.x & 3;
+  if (tok >= p.T) return;  // (the four threads of a token leave together)
+  const int b = upper_segment(p.cu, p.B, (int)tok);
+  const int rows = p.G * p.N;
+  float best[kKeepRows], tot[kKeepRows];  // per query (entries beyond N unused)
+#pragma unroll
+  for (int n = 0; n < kKeepRows; ++n) { best[n] = -INFINITY; tot[n] = 0.f; }
+  const float* lse_b = p.ws_lse + (int64_t)b * p.N * p.H;
+  const bool one_query_four_heads = p.N == 1 && p.G == 4;  // the common shape: a KV head's four log-sum-exps are one 16-byte load
+  for (int l = part; l < p.L; l += 4) {
+    const float* lse_l = lse_b + (int64_t)l * p.B * p.N * p.H;
+    const float* src = p.logits + ((int64_t)l * p.H_kv * p.T + tok) * kKeepRows;
+    if (one_query_four_heads) {
+      float m = best[0];
+#pragma unroll 8
+      for (int g = 0; g < p.H_kv; ++g) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (int64_t)g * p.T * kKeepRows));
+        const u32x4 e = *reinterpret_cast<const u32x4*>(lse_l + g * 4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) m = fmaxf(m, __uint_as_float(v[r]) - 1.4426950408889634f * __uint_as_float(e[r]));
+      }
+      best[0] = m;
+      if (MEAN) { tot[0] += fast_exp2(best[0]); best[0] = -INFINITY; }
+      continue;
+    }
+#pragma unroll 4
+    for (int g = 0; g < p.H_kv; ++g) {
+      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (int64_t)g * p.T * kKeepRows));
+#pragma unroll
+      for (int r = 0; r < kKeepRows; ++r) {
+        if (r < rows) {
+          const int n = r >> p.lgG, h = g * p.G + (r & (p.G - 1));
+          const float x = __uint_as_float(v[r]) - 1.4426950408889634f * lse_l[n * p.H + h];
+#pragma unroll
+          for (int q = 0; q < kKeepRows; ++q)
+            if (q == n) best[q] = fmaxf(best[q], x);
+        }
+      }
+    }
+    if (MEAN) {
+#pragma unroll
+      for (int n = 0; n < kKeepRows; ++n) { tot[n] += fast_exp2(best[n]); best[n] = -INFINITY; }
+    }
+  }
+#pragma unroll
+  for (int n = 0; n < kKeepRows; ++n) {  // fold the four threads of the token
+    if (MEAN) {
+      tot[n] += __shfl_xor(tot[n], 1, kWave);
+      tot[n] += __shfl_xor(tot[n], 2, kWave);
+    } else {
+      best[n] = fmaxf(best[n], __shfl_xor(best[n], 1, kWave));
+      best[n] = fmaxf(best[n], __shfl_xor(best[n], 2, kWave));
+    }
+  }
+  if (part != 0) return;
+  int nv = p.n_valid ? p.n_valid[b] : p.N;
+  nv = max(1, min(nv, p.N));
+  float sum = 0.f;
+#pragma unroll
+  for (int n = 0; n < kKeepRows; ++n)
+    if (n < nv) sum += MEAN ? tot[n] : fast_exp2(best[n]);
+  p.scores[tok] = sum / (MEAN ? (float)nv * (float)p.L : (float)nv);
 }
 
 // merge the layer groups and average over the valid queries; one thread per token
@@ -442,8 +575,23 @@ bool tiled_supported(const sp_score_args* a) {
   return true;
 }
 
+// Keep mode: with few query rows per KV head the logits of a key (16 bytes per layer and KV
+// head) are much smaller than the key itself (2*d bytes), so the second pass reads the logits
+// the first pass wrote instead of reading the K cache again.
+#ifndef SP_TILED_KEEP_MAX_BYTES
+#define SP_TILED_KEEP_MAX_BYTES (16ull << 30)
+#endif
+static size_t keep_bytes(const sp_score_args* a) {
+  return sizeof(float) * kKeepRows * (size_t)a->L * a->H_kv * (size_t)a->T;
+}
+static bool keep_mode(const sp_score_args* a) {
+  const int G = a->H / a->H_kv;
+  return G * a->N <= kKeepRows && keep_bytes(a) <= SP_TILED_KEEP_MAX_BYTES;
+}
+
 size_t tiled_extra_workspace_bytes(const sp_score_args* a) {
   if (!tiled_supported(a)) return 0;
+  if (keep_mode(a)) return align_up(keep_bytes(a), 256);
   int lpg, groups;
   tiled_grouping(a, &lpg, &groups);
   return align_up(sizeof(float) * (size_t)groups * a->N * (size_t)a->T, 256);
@@ -467,6 +615,15 @@ static sp_status launch_tiled(const TiledDev& dev, hipStream_t stream) {
 
 template <int D>
 static sp_status tiled_passes(const TiledDev& dev, const ScoreDev& gen, hipStream_t stream) {
+  if (dev.logits) {
+    const sp_status st = launch_tiled<D, 2, false>(dev, stream);
+    if (st != SP_OK) return st;
+    launch_lse_combine(gen, stream);
+    const dim3 grid((unsigned)((dev.T * 4 + 255) / 256));
+    if (dev.layer_reduce == SP_LAYER_MEAN) hipLaunchKernelGGL(logit_score_kernel<true>, grid, dim3(256), 0, stream, dev);
+    else hipLaunchKernelGGL(logit_score_kernel<false>, grid, dim3(256), 0, stream, dev);
+    return launch_status();
+  }
   sp_status st = launch_tiled<D, 0, false>(dev, stream);
   if (st != SP_OK) return st;
   launch_lse_combine(gen, stream);
@@ -490,7 +647,9 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
   dev.ts = a->k_token_stride; dev.hs = a->k_head_stride; dev.T = a->T;
   dev.q = gen.q; dev.cu = gen.cu; dev.n_valid = gen.n_valid; dev.tile_cu = gen.tile_cu;
   dev.ws_lse = gen.ws_lse; dev.part = gen.part;
-  dev.group_scores = static_cast<float*>(extra);
+  const bool keep = keep_mode(a);
+  dev.group_scores = keep ? nullptr : static_cast<float*>(extra);
+  dev.logits = keep ? static_cast<float*>(extra) : nullptr;
   dev.scores = a->d_scores;
   for (int l = 0; l < SP_MAX_LAYERS; ++l) dev.k[l] = gen.k[l];
   return a->d == 64 ? tiled_passes<64>(dev, gen, stream) : tiled_passes<128>(dev, gen, stream);

@@ -209,6 +209,8 @@ def test_rotation_by_position_zero_changes_nothing():
     dict(H=32, H_kv=8, d=128, N=8, L=3),
     dict(H=24, H_kv=3, d=64, N=4, L=4),
     dict(H=5, H_kv=5, d=64, N=16, L=2),
+    dict(H=3, H_kv=3, d=64, N=3, L=3),     # three query rows per KV head: logits kept between the passes
+    dict(H=4, H_kv=2, d=128, N=2, L=2),    # four rows from two queries x two heads
 ])
 def test_ragged_batch_tile_boundaries(shape):
     lens = (1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 0, 700)
