@@ -101,7 +101,10 @@ typedef struct {
 } sp_score_args;
 
 /* Bytes of workspace sp_score needs for these shapes (pointers are not read).
- * Returns 0 if the shape fields are invalid. */
+ * Returns 0 if the shape fields are invalid.  The size grows with T: per-tile row statistics
+ * (L*N*H*8 bytes per 64 tokens) always, plus, for batches whose KV heads have at most four
+ * query rows (H/H_kv * N <= 4), 16 bytes per token, layer and KV head of logits kept between
+ * the two passes (0.7 GB for 167K tokens of a 32-layer, 8-KV-head model). */
 SP_API size_t sp_score_workspace_bytes(const sp_score_args* args);
 
 /* Enqueue the scoring on hip_stream.  Errors: SP_ENULL, SP_EINVAL (shape limits above),
