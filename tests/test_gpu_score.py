@@ -232,3 +232,14 @@ def test_ragged_batch_paths_agree_and_repeat_bitwise():
         assert np.array_equal(a, b) and np.array_equal(la, lb)
         np.testing.assert_allclose(a, g, rtol=2e-3, atol=1e-12)
         np.testing.assert_allclose(la, lg, rtol=0, atol=2e-4)
+
+
+def test_maximum_depth_on_every_path():
+    """L = SP_MAX_LAYERS: one long-ish prompt (single-pass kernel), a ragged batch with look-ahead
+    queries (two MFMA passes), one without (logits kept between the passes), and the plain kernels."""
+    for lens, n in (((2000,), 8), ((700, 150, 1), 8), ((700, 150, 1), 1)):
+        w = synth.scaled(synth.workload(2), seqlens=lens, L=128, N=n, salient_frac=0.02, salient_run=1)
+        inp = synth.make_qk(w)
+        for mode in MODES:
+            _check(w, inp, mode, general=False)
+        _check(w, inp, orc.LAYER_MAX, general=True)
