@@ -243,3 +243,12 @@ def test_maximum_depth_on_every_path():
         for mode in MODES:
             _check(w, inp, mode, general=False)
         _check(w, inp, orc.LAYER_MAX, general=True)
+
+
+@pytest.mark.parametrize("n_queries", [1, 8])
+def test_head_major_k_layout_ragged_batch(n_queries):
+    """[H_kv, T, d] caches through the ragged-batch kernels (both of their second passes)."""
+    w = synth.scaled(synth.workload(3), seqlens=(333, 64, 1000), L=3, N=n_queries)
+    inp = synth.make_qk(w)
+    for mode in MODES:
+        _check(w, inp, mode, general=False, head_major=True)
