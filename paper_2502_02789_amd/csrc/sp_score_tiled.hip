@@ -39,7 +39,9 @@ constexpr int kKeepStageBytes = kWaveKeys * kKeepRows * 4;  // taken from the en
 constexpr int kTiledTargetWGs = SP_TILED_TARGET_WGS;  // cut the layers into groups until the grid has about this many workgroups
 
 struct TiledDev {
-  int B, N, L, H, H_kv, G, lgG, layers_per_group, n_groups, max_tiles, layer_reduce;
+  // G heads per KV head; their query rows are laid out with the group size padded to a power of
+  // two, Gp = 1 << lgG (columns of padding heads repeat head 0 and are masked where it matters)
+  int B, N, L, H, H_kv, G, Gp, lgG, layers_per_group, n_groups, max_tiles, layer_reduce;
   float scale;  // logits -> natural-log domain (what the partials and log-sum-exps are kept in)
   float c;      // scale * log2(e)
   int64_t ts, hs, T;
@@ -157,7 +159,7 @@ struct TileWalker {
   // WITH_LSE the rows' log-sum-exps follow into lse zone `zone` and land with the tile.
   template <bool WITH_LSE>
   __device__ __forceinline__ void issue_queries(int l, int g, int slot, int zone) {
-    int rows = p.G * p.N;
+    int rows = p.Gp * p.N;
     asm volatile("" : "+s"(rows));
     const uint32_t dst = ring_lds + slot * TILE_B;
     const int64_t row0 = (((int64_t)l * p.B + b) * p.N) * p.H + g * p.G;
@@ -171,13 +173,15 @@ struct TileWalker {
       const int key = (D == 128) ? (r & 15) : ((r >> 1) & 7);
       const int unit = (ln % UNITS) ^ key;
       const int rr = r < rows ? r : 0;
-      const uint32_t off = (uint32_t)((rr >> p.lgG) * p.H * ROW_B + (rr & (p.G - 1)) * ROW_B + unit * 16);
+      const int jj = (rr & (p.Gp - 1)) < p.G ? (rr & (p.Gp - 1)) : 0;
+      const uint32_t off = (uint32_t)((rr >> p.lgG) * p.H * ROW_B + jj * ROW_B + unit * 16);
       __builtin_amdgcn_global_load_lds(base + off, lds_ptr(dst + j * 1024), 16, 0, 0);
     }
     note_issued(LOADS);
     if (WITH_LSE) {
       const int cc = (ln & 31) < rows ? (ln & 31) : 0;
-      const float* src = p.ws_lse + row0 + (cc >> p.lgG) * p.H + (cc & (p.G - 1));
+      const int cj = (cc & (p.Gp - 1)) < p.G ? (cc & (p.Gp - 1)) : 0;
+      const float* src = p.ws_lse + row0 + (cc >> p.lgG) * p.H + cj;
       __builtin_amdgcn_global_load_lds(src, lds_ptr(lse_lds + zone * 256), 4, 0, 0);
       note_issued(1);
     }
@@ -251,12 +255,12 @@ struct TileWalker {
     const float z = run_s * fast_exp2((run_m - ref) * p.c) + ps * fast_exp2((pm - ref) * p.c);
     int c = col;
     asm volatile("" : "+v"(c));
-    const int rows = p.G * p.N;
+    const int rows = p.Gp * p.N;
     if (half == 0 && c < rows)
       lds_poke64<0>(part_lds + (part_n * rows + c) * 8, ((uint64_t)__float_as_uint(z) << 32) | __float_as_uint(mn * p.scale));
     part_n = __builtin_amdgcn_readfirstlane(part_n + 1);
   }
-  __device__ __forceinline__ bool partials_full(int buf_bytes) const { return (part_n + 1) * p.G * p.N * 8 > buf_bytes; }
+  __device__ __forceinline__ bool partials_full(int buf_bytes) const { return (part_n + 1) * p.Gp * p.N * 8 > buf_bytes; }
 
   // keep mode, end of a slab: the wave's 64 x (G*N <= 4) logits, scaled to base 2, as 16 bytes
   // per key in the key's lane, after a turn through LDS (a lane holds one query row of 32 keys,
@@ -289,7 +293,7 @@ struct TileWalker {
   __device__ __forceinline__ void flush_partials(int first, int l0, int tile) {
     int ln = lane;
     asm volatile("" : "+v"(ln));
-    const int rows = p.G * p.N, total = part_n * rows;
+    const int rows = p.Gp * p.N, total = part_n * rows;
 #pragma unroll 1
     for (int base = 0; base < total; base += kWave) {
       const int idx = base + ln;
@@ -298,7 +302,8 @@ struct TileWalker {
         const int j = idx / rows, c = idx - j * rows;
         const int s = first + j;
         const int l = l0 + s / p.H_kv, g = s % p.H_kv;
-        const int n = c >> p.lgG, h = g * p.G + (c & (p.G - 1));
+        // (a padding column repeats head 0 of its query: same statistics, written to the same place)
+        const int n = c >> p.lgG, h = g * p.G + ((c & (p.Gp - 1)) < p.G ? (c & (p.Gp - 1)) : 0);
         p.part[((int64_t)(l * p.N + n) * p.H + h) * p.max_tiles + tile] =
             make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
       }
@@ -448,7 +453,7 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
   if (PASS == 1) {
     int c = w.col, h = w.half;
     asm volatile("" : "+v"(c), "+v"(h));
-    if (c < p.G * p.N && (c & (p.G - 1)) == 0) {
+    if (c < p.Gp * p.N && (c & (p.Gp - 1)) == 0) {
       float* dst = p.group_scores + ((int64_t)blockIdx.y * p.N + (c >> p.lgG)) * p.T + w.tok0;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -471,7 +476,7 @@ __global__ __launch_bounds__(256) void logit_score_kernel(const TiledDev p) {
   const int part = threadIdx.x & 3;
   if (tok >= p.T) return;  // (the four threads of a token leave together)
   const int b = upper_segment(p.cu, p.B, (int)tok);
-  const int rows = p.G * p.N;
+  const int rows = p.Gp * p.N;
   float best[kKeepRows], tot[kKeepRows];  // per query (entries beyond N unused)
 #pragma unroll
   for (int n = 0; n < kKeepRows; ++n) { best[n] = -INFINITY; tot[n] = 0.f; }
@@ -499,7 +504,7 @@ __global__ __launch_bounds__(256) void logit_score_kernel(const TiledDev p) {
 #pragma unroll
       for (int r = 0; r < kKeepRows; ++r) {
         if (r < rows) {
-          const int n = r >> p.lgG, h = g * p.G + (r & (p.G - 1));
+          const int n = r >> p.lgG, h = g * p.G + ((r & (p.Gp - 1)) < p.G ? (r & (p.Gp - 1)) : 0);
           const float x = __uint_as_float(v[r]) - 1.4426950408889634f * lse_l[n * p.H + h];
 #pragma unroll
           for (int q = 0; q < kKeepRows; ++q)
@@ -566,11 +571,15 @@ static void tiled_grouping(const sp_score_args* a, int* layers_per_group, int* n
   *n_groups = (a->L + *layers_per_group - 1) / *layers_per_group;
 }
 
-bool tiled_supported(const sp_score_args* a) {
+static int padded_group(const sp_score_args* a) {
   const int G = a->H / a->H_kv;
+  return G <= 2 ? G : G <= 4 ? 4 : 8;
+}
+
+bool tiled_supported(const sp_score_args* a) {
   if (a->rope_theta != 0.f) return false;  // un-rotated caches take the plain-FMA kernels
-  if (G != 1 && G != 2 && G != 4 && G != 8) return false;
-  if (G * a->N > 32) return false;
+  if (a->H / a->H_kv > 8) return false;
+  if (padded_group(a) * a->N > 32) return false;
   if (a->T < 1) return false;
   return true;
 }
@@ -585,8 +594,7 @@ static size_t keep_bytes(const sp_score_args* a) {
   return sizeof(float) * kKeepRows * (size_t)a->L * a->H_kv * (size_t)a->T;
 }
 static bool keep_mode(const sp_score_args* a) {
-  const int G = a->H / a->H_kv;
-  return G * a->N <= kKeepRows && keep_bytes(a) <= SP_TILED_KEEP_MAX_BYTES;
+  return padded_group(a) * a->N <= kKeepRows && keep_bytes(a) <= SP_TILED_KEEP_MAX_BYTES;
 }
 
 size_t tiled_extra_workspace_bytes(const sp_score_args* a) {
@@ -638,7 +646,8 @@ static sp_status tiled_passes(const TiledDev& dev, const ScoreDev& gen, hipStrea
 sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, hipStream_t stream) {
   TiledDev dev;
   dev.B = a->B; dev.N = a->N; dev.L = a->L; dev.H = a->H; dev.H_kv = a->H_kv; dev.G = a->H / a->H_kv;
-  dev.lgG = dev.G == 1 ? 0 : dev.G == 2 ? 1 : dev.G == 4 ? 2 : 3;
+  dev.lgG = dev.G == 1 ? 0 : dev.G == 2 ? 1 : dev.G <= 4 ? 2 : 3;
+  dev.Gp = 1 << dev.lgG;
   tiled_grouping(a, &dev.layers_per_group, &dev.n_groups);
   dev.max_tiles = gen.max_tiles;
   dev.layer_reduce = a->layer_reduce;

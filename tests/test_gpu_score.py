@@ -252,3 +252,17 @@ def test_head_major_k_layout_ragged_batch(n_queries):
     inp = synth.make_qk(w)
     for mode in MODES:
         _check(w, inp, mode, general=False, head_major=True)
+
+
+@pytest.mark.parametrize("shape", [
+    dict(H=14, H_kv=2, d=64, N=4),    # seven heads per KV head (padded to eight columns per query)
+    dict(H=12, H_kv=2, d=128, N=1),   # six
+    dict(H=9, H_kv=3, d=64, N=1),     # three: logits kept between the passes, one padding column
+    dict(H=5, H_kv=1, d=128, N=2),    # five
+])
+def test_group_sizes_that_are_not_powers_of_two(shape):
+    w = synth.scaled(synth.workload(2), seqlens=(130, 517, 64), L=3, salient_frac=0.02, salient_run=1, **shape)
+    inp = synth.make_qk(w)
+    for mode in MODES:
+        a = _check(w, inp, mode, general=False)
+    _check(w, inp, orc.LAYER_MAX, general=True)
