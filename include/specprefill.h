@@ -98,6 +98,18 @@ typedef struct {
   float* d_lse;              /* out fp32 [L, B, N, H] row log-sum-exp, or NULL            */
   void* d_workspace;         /* device scratch, 256-byte aligned                          */
   size_t workspace_bytes;
+  /* Paged K cache (Sec. 3.3: the draft's keys are fetched through the serving engine's slot
+   * mapping).  d_block_table == NULL: token i of sequence b is row cu_seqlens[b] + i of every
+   * layer, as described at k_layers.  Otherwise every layer is a pool of pages and token i of
+   * sequence b is row (i % page_size) of page d_block_table[b*blocks_per_seq + i/page_size]:
+   * element offset page*k_page_stride + (i % page_size)*k_token_stride + g*k_head_stride + t.
+   * The table must cover every sequence and hold valid page numbers (not checked: a wrong
+   * entry reads outside the pool).  Scores are still indexed by cu_seqlens[b] + i.  Paged
+   * caches take the two-pass kernels. */
+  const int32_t* d_block_table; /* int32 [B, blocks_per_seq] page numbers, or NULL             */
+  int32_t page_size;         /* tokens per page: a power of two >= 8 (ignored if not paged)   */
+  int32_t blocks_per_seq;    /* row length of the table, >= 1                                 */
+  int64_t k_page_stride;     /* elements, multiple of 8                                       */
 } sp_score_args;
 
 /* Bytes of workspace sp_score needs for these shapes (pointers are not read).

@@ -80,6 +80,20 @@ def rope_rotate_bits(x_bits: np.ndarray, pos: np.ndarray, theta: float) -> np.nd
     return (rounded >> np.uint32(16)).astype(np.uint16)
 
 
+def keys_from_pages(pool: np.ndarray, block_table: np.ndarray, cu_seqlens: np.ndarray) -> np.ndarray:
+    """Sec. 3.3 / Algorithm 1, the step that fetches the draft's keys through the serving engine's
+    slot mapping: `pool` is one layer's page pool [pages, page_size, H_kv, d]; token i of sequence b
+    is row i % page_size of page block_table[b, i // page_size].  Returns the layer as [T, H_kv, d]
+    rows in cu_seqlens order.  One key at a time, as the definition reads."""
+    page_size = pool.shape[1]
+    T = int(cu_seqlens[-1])
+    out = np.empty((T,) + pool.shape[2:], dtype=pool.dtype)
+    for b in range(len(cu_seqlens) - 1):
+        for i in range(int(cu_seqlens[b + 1] - cu_seqlens[b])):
+            out[int(cu_seqlens[b]) + i] = pool[int(block_table[b, i // page_size]), i % page_size]
+    return out
+
+
 def layer_attention(q: np.ndarray, k: np.ndarray, scale: float) -> Tuple[np.ndarray, np.ndarray]:
     """q fp64 [N, H, d]; k fp64 [M, H_kv, d] -> (a [N, M, H], lse [N, H]).
 

@@ -39,6 +39,8 @@ class ScoreArgs(C.Structure):
         ("d_n_valid", C.c_void_p), ("scale", C.c_float), ("layer_reduce", C.c_int32),
         ("rope_theta", C.c_float), ("d_q_pos", C.c_void_p), ("d_scores", C.c_void_p), ("d_lse", C.c_void_p),
         ("d_workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+        ("d_block_table", C.c_void_p), ("page_size", C.c_int32), ("blocks_per_seq", C.c_int32),
+        ("k_page_stride", C.c_int64),
     ]
 
 
@@ -125,8 +127,10 @@ def _check(fn: str, status: int) -> None:
 def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, scale: float,
                     layer_reduce: int = SP_LAYER_MAX, n_valid=None, lse=None, workspace=None,
                     k_token_stride: Optional[int] = None, k_head_stride: Optional[int] = None,
-                    T: Optional[int] = None, rope_theta: float = 0.0, q_pos=None) -> ScoreArgs:
-    """q: bf16 [L,B,N,H,d]; k_layers: L bf16 tensors [T,H_kv,d] (any token/head strides)."""
+                    T: Optional[int] = None, rope_theta: float = 0.0, q_pos=None,
+                    block_table=None, page_size: int = 0) -> ScoreArgs:
+    """q: bf16 [L,B,N,H,d]; k_layers: L bf16 tensors [T,H_kv,d] (any token/head strides), or, with
+    block_table (int32 [B, blocks_per_seq]), L page pools [pages, page_size, H_kv, d] (then T must be given)."""
     L, B, N, H, d = q.shape
     a = ScoreArgs()
     a.B, a.N, a.L, a.H, a.H_kv, a.d = B, N, L, H, H_kv, d
@@ -135,8 +139,19 @@ def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, sca
     arr = (C.c_void_p * len(k_layers))(*[_ptr(k) for k in k_layers])
     a._keepalive = arr                    # the struct only holds a pointer to this host array
     a.k_layers = C.cast(arr, C.POINTER(C.c_void_p))
-    a.k_token_stride = int(k_layers[0].stride(0)) if k_token_stride is None else int(k_token_stride)
-    a.k_head_stride = int(k_layers[0].stride(1)) if k_head_stride is None else int(k_head_stride)
+    if block_table is not None:
+        if T is None:
+            raise ValueError("T (total tokens) must be given with a paged cache")
+        a.d_block_table = _ptr(block_table)
+        a.page_size = int(page_size)
+        a.blocks_per_seq = int(block_table.shape[1])
+        a.k_page_stride = int(k_layers[0].stride(0))
+        a._keepalive_table = block_table
+        a.k_token_stride = int(k_layers[0].stride(1)) if k_token_stride is None else int(k_token_stride)
+        a.k_head_stride = int(k_layers[0].stride(2)) if k_head_stride is None else int(k_head_stride)
+    else:
+        a.k_token_stride = int(k_layers[0].stride(0)) if k_token_stride is None else int(k_token_stride)
+        a.k_head_stride = int(k_layers[0].stride(1)) if k_head_stride is None else int(k_head_stride)
     a.d_cu_seqlens = _ptr(cu_seqlens)
     a.d_n_valid = _ptr(n_valid)
     a.scale = float(scale)

@@ -93,6 +93,13 @@ __device__ __forceinline__ void load_k_row(const uint16_t* __restrict__ kp, bool
   }
 }
 
+// element offset of key `key` of sequence b (first token seq0) inside a layer, KV head 0
+__device__ __forceinline__ int64_t key_row_offset(const ScoreDev& p, int b, int seq0, int key) {
+  if (!p.block_table) return (int64_t)(seq0 + key) * p.k_token_stride;
+  const int page = p.block_table[(int64_t)b * p.blocks_per_seq + (key >> p.lg_page)];
+  return (int64_t)page * p.k_page_stride + (int64_t)(key & ((1 << p.lg_page) - 1)) * p.k_token_stride;
+}
+
 // <q row, k row> with the q row at a wave-uniform address
 template <int D>
 __device__ __forceinline__ float dot_row(const uint16_t* __restrict__ qp, const float (&kf)[D]) {
@@ -125,8 +132,7 @@ __global__ __launch_bounds__(64) void lse_partial_kernel(const ScoreDev p) {
   const int key = (tile - p.tile_cu[b]) * kTileKeys + lane;
   const bool valid = key < M;
   float kf[D];
-  load_k_row<D>(p.k[l] + (int64_t)(seq0 + (valid ? key : 0)) * p.k_token_stride + (int64_t)g * p.k_head_stride,
-                valid, kf);
+  load_k_row<D>(p.k[l] + key_row_offset(p, b, seq0, valid ? key : 0) + (int64_t)g * p.k_head_stride, valid, kf);
   if (p.rope) rope_row_inplace<D>(kf, p.rope + (int64_t)(valid ? key : 0) * (D / 2));
   for (int n = 0; n < p.N; ++n) {
     for (int j = 0; j < p.G; ++j) {
@@ -187,6 +193,7 @@ __global__ __launch_bounds__(256) void score_accum_kernel(const ScoreDev p) {
   const int key = (tile - p.tile_cu[b]) * kTileKeys + lane;
   const bool valid = key < M;
   const int64_t tok = seq0 + (valid ? key : 0);
+  const int64_t row_off = key_row_offset(p, b, seq0, valid ? key : 0);
 
   float tot[SP_MAX_QUERIES];
 #pragma unroll
@@ -198,7 +205,7 @@ __global__ __launch_bounds__(256) void score_accum_kernel(const ScoreDev p) {
     for (int n = 0; n < SP_MAX_QUERIES; ++n) nmax[n] = -INFINITY;
     for (int g = wave; g < p.H_kv; g += 4) {
       float kf[D];
-      load_k_row<D>(p.k[l] + tok * p.k_token_stride + (int64_t)g * p.k_head_stride, valid, kf);
+      load_k_row<D>(p.k[l] + row_off + (int64_t)g * p.k_head_stride, valid, kf);
       if (p.rope) rope_row_inplace<D>(kf, p.rope + (int64_t)(valid ? key : 0) * (D / 2));
 #pragma unroll
       for (int n = 0; n < SP_MAX_QUERIES; ++n) {
@@ -346,6 +353,11 @@ void fill_score_dev(const sp_score_args* a, ScoreDev* p) {
   p->scores = a->d_scores;
   p->lse_out = a->d_lse;
   p->rope = nullptr;
+  p->block_table = a->d_block_table;
+  p->lg_page = 0;
+  while (a->d_block_table && (1 << p->lg_page) < a->page_size) ++p->lg_page;
+  p->blocks_per_seq = a->blocks_per_seq;
+  p->k_page_stride = a->k_page_stride;
   for (int l = 0; l < SP_MAX_LAYERS; ++l)
     p->k[l] = l < a->L ? static_cast<const uint16_t*>(a->k_layers[l]) : nullptr;
 }
@@ -370,6 +382,11 @@ static sp_status check_score_args(const sp_score_args* a) {
   if (a->rope_theta > 0.f && a->d_q_pos == nullptr) return SP_ENULL;
   if (!(a->scale == a->scale) || a->scale <= 0.f) return SP_EINVAL;
   if (a->k_token_stride < 0 || a->k_head_stride < 0) return SP_EINVAL;
+  if (a->d_block_table) {
+    if (a->page_size < 8 || (a->page_size & (a->page_size - 1)) != 0 || a->blocks_per_seq < 1) return SP_EINVAL;
+    if (a->k_page_stride < 0) return SP_EINVAL;
+    if (a->k_page_stride & 7) return SP_EALIGN;
+  }
   if ((a->k_token_stride & 7) || (a->k_head_stride & 7) || !sp::aligned16(a->d_q)) return SP_EALIGN;
   for (int l = 0; l < a->L; ++l)
     if (!sp::aligned16(a->k_layers[l])) return SP_EALIGN;

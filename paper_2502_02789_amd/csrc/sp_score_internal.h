@@ -22,6 +22,9 @@ struct ScoreDev {
   float* scores;
   float* lse_out;
   const float2* rope;  // [position][d/2] (cos, sin) if keys are stored un-rotated, else null
+  const int32_t* block_table;  // paged cache: [B][blocks_per_seq] page numbers, else null
+  int lg_page, blocks_per_seq;
+  int64_t k_page_stride;
   const uint16_t* k[SP_MAX_LAYERS];
 };
 

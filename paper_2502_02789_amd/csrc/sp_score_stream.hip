@@ -789,6 +789,7 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   const int G = a->H / a->H_kv;
   if (a->B != 1 || a->H_kv != 8 || a->T < 1) return pl;
   if (a->rope_theta != 0.f) return pl;  // un-rotated caches take the general kernels
+  if (a->d_block_table) return pl;      // paged caches take the two-pass kernels
   if (G != 1 && G != 2 && G != 4 && G != 8) return pl;
   if (G * a->N > 32 || a->N > 8) return pl;
   nwg = std::min(nwg, kMaxWG);

@@ -55,6 +55,9 @@ struct TiledDev {
                          // sum over its layers of the per-layer max probability (layer mean)
   float* logits;         // keep mode: [L][H_kv][T][kKeepRows] base-2 logits (scale * log2(e) applied), else null
   float* scores;
+  const int32_t* block_table;  // paged cache: [B][blocks_per_seq] page numbers, else null
+  int lg_page, blocks_per_seq;
+  int64_t page_stride;
   const uint16_t* k[SP_MAX_LAYERS];
 };
 
@@ -69,7 +72,7 @@ struct TileWalker {
 
   const TiledDev& p;
   int wave, lane, half, col;
-  int b, seq0, rows_in;  // sequence, its first token, valid keys of this wave's tile (1..64)
+  int b, seq0, key0, rows_in;  // sequence, its first token, the tile's first key within it, valid keys of the tile (1..64)
   int64_t tok0;          // flat token index of the tile's first key
   int issued, seq_a, seq_b;  // vector-memory instructions issued so far; value right after the loads into slot 0 / 1
   uint32_t ring_lds, lse_lds, part_lds, rd0, u0;
@@ -86,7 +89,7 @@ struct TileWalker {
     col = lane & 31;
     b = upper_segment(p.tile_cu, p.B, tile);
     seq0 = p.cu[b];
-    const int key0 = (tile - p.tile_cu[b]) * kWaveKeys;
+    key0 = (tile - p.tile_cu[b]) * kWaveKeys;
     rows_in = min(kWaveKeys, p.cu[b + 1] - seq0 - key0);
     tok0 = (int64_t)seq0 + key0;
     issued = seq_a = seq_b = 0;
@@ -128,6 +131,12 @@ struct TileWalker {
     const uint32_t dst = ring_lds + slot * TILE_B;
     int rows = min(32, rows_in - kb * 32);
     asm volatile("" : "+s"(rows));
+    if (p.block_table) {
+      issue_keys_paged(l, g, rows > 0 ? key0 + kb * 32 : key0, rows, dst);
+      note_issued(LOADS);
+      mark_slot(slot);
+      return;
+    }
     const int64_t tok = rows > 0 ? tok0 + kb * 32 : tok0;
     const unsigned char* base = reinterpret_cast<const unsigned char*>(p.k[l]) + 2 * ((int64_t)g * p.hs + tok * p.ts);
     if (rows == 32) {
@@ -152,6 +161,31 @@ struct TileWalker {
     }
     note_issued(LOADS);
     mark_slot(slot);
+  }
+
+  // The same from a paged cache.  key_first: in-sequence index of the tile's row 0 (a multiple of
+  // 32).  The RPI (4 or 8) rows of one load lie in one page: pages hold a power of two >= 8 keys.
+  // Loads whose rows are all beyond the sequence, and lanes beyond it, re-read a valid row.
+  __device__ __forceinline__ void issue_keys_paged(int l, int g, int key_first, int rows, uint32_t dst) {
+    const unsigned char* layer = reinterpret_cast<const unsigned char*>(p.k[l]) + 2 * (int64_t)g * p.hs;
+    const int32_t* table = p.block_table + (int64_t)b * p.blocks_per_seq;
+    const int pmask = (1 << p.lg_page) - 1;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int i = ln / UNITS;
+    const unsigned char* base = layer;
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+      const bool inside = j * RPI < rows;
+      const int kk = inside ? key_first + j * RPI : key_first;
+      if (j == 0 || !inside || ((j * RPI) & pmask) == 0)  // first load, fallback row, or a new page begins
+        base = layer + 2 * ((int64_t)table[kk >> p.lg_page] * p.page_stride + (int64_t)(kk & pmask) * p.ts);
+      else
+        base += (int64_t)RPI * p.ts * 2;
+      const int64_t row_off = (j * RPI + i < rows) ? (int64_t)i * p.ts * 2 : 0;
+      const uint32_t unit = u0 ^ ((4 * j) & (UNITS - 1));
+      __builtin_amdgcn_global_load_lds(base + row_off + (unit << 4), lds_ptr(dst + j * 1024), 16, 0, 0);
+    }
   }
 
   // Query tile of (layer l, KV head g) of this wave's sequence: row r = n*G + j holds
@@ -660,6 +694,8 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
   dev.group_scores = keep ? nullptr : static_cast<float*>(extra);
   dev.logits = keep ? static_cast<float*>(extra) : nullptr;
   dev.scores = a->d_scores;
+  dev.block_table = gen.block_table; dev.lg_page = gen.lg_page; dev.blocks_per_seq = gen.blocks_per_seq;
+  dev.page_stride = gen.k_page_stride;
   for (int l = 0; l < SP_MAX_LAYERS; ++l) dev.k[l] = gen.k[l];
   return a->d == 64 ? tiled_passes<64>(dev, gen, stream) : tiled_passes<128>(dev, gen, stream);
 }

@@ -31,6 +31,48 @@ def gpu_score(q_bits, k_bits_layers, cu, H_kv, scale, mode, n_valid=None, genera
     return s.scores.cpu().numpy(), (s.lse.cpu().numpy() if want_lse else None)
 
 
+def paged_copy(k_bits_layers, cu, page_size, seed):
+    """Scatters contiguous [T, H_kv, d] layers into shuffled page pools (with unused pages in
+    between); returns (pools, block_table).  Unused rows hold a bit pattern that decodes to a huge
+    value, so a kernel that reads a wrong row does not go unnoticed."""
+    cu = np.asarray(cu, dtype=np.int64)
+    B = len(cu) - 1
+    lens = cu[1:] - cu[:-1]
+    blocks = [int(-(-m // page_size)) for m in lens]
+    bps = max(1, max(blocks))
+    n_pages = sum(blocks) + 3
+    order = np.random.default_rng(seed).permutation(n_pages)
+    table = np.zeros((B, bps), dtype=np.int32)
+    nxt = 0
+    for b in range(B):
+        for j in range(blocks[b]):
+            table[b, j] = order[nxt]
+            nxt += 1
+    pools = []
+    for k in k_bits_layers:
+        pool = np.full((n_pages, page_size) + k.shape[1:], 0x7F00, dtype=np.uint16)   # bf16 1.7e38
+        for b in range(B):
+            for i in range(int(lens[b])):
+                pool[table[b, i // page_size], i % page_size] = k[cu[b] + i]
+        pools.append(pool)
+    return pools, table
+
+
+def gpu_score_paged(q_bits, pools, table, cu, H_kv, scale, mode, general=False):
+    import torch
+    from paper_2502_02789_amd import binding as sp_binding, device as dev
+    q = dev.bf16_from_bits(q_bits)
+    ks = [dev.bf16_from_bits(p) for p in pools]
+    cu_d = torch.from_numpy(np.asarray(cu, dtype=np.int32)).cuda()
+    tab_d = torch.from_numpy(np.ascontiguousarray(table, dtype=np.int32)).cuda()
+    s = dev.Scorer(q, ks, cu_d, H_kv=H_kv, scale=scale, layer_reduce=mode, want_lse=True, block_table=tab_d,
+                   page_size=pools[0].shape[1], total_tokens=int(cu[-1]))
+    s.scores.fill_(float("nan"))
+    s.run(general=general)
+    sp_binding.sp_score_check(s.args)
+    return s.scores.cpu().numpy(), s.lse.cpu().numpy()
+
+
 def assert_scores_close(got, want, what=""):
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)

@@ -266,3 +266,32 @@ def test_group_sizes_that_are_not_powers_of_two(shape):
     for mode in MODES:
         a = _check(w, inp, mode, general=False)
     _check(w, inp, orc.LAYER_MAX, general=True)
+
+
+@pytest.mark.parametrize("page_size", [8, 16, 64])
+@pytest.mark.parametrize("n_queries", [1, 8])
+def test_paged_cache(page_size, n_queries):
+    """Keys fetched through a block table (shuffled pages, partly filled last pages) give what the
+    same keys give when they lie in sequence order; oracle: gather the pages, then as always."""
+    w = synth.scaled(synth.workload(3), seqlens=(333, 64, 1, 0, 1000), L=3, N=n_queries, salient_frac=0.02,
+                     salient_run=1)
+    inp = synth.make_qk(w)
+    scale = 1.0 / math.sqrt(w.d)
+    pools, table = hp.paged_copy(inp["k"], inp["cu_seqlens"], page_size, seed=page_size)
+    k_back = [orc.keys_from_pages(p, table, inp["cu_seqlens"]) for p in pools]
+    for mode in MODES:
+        want, want_lse = orc.token_importance(inp["q"], k_back, inp["cu_seqlens"], scale, mode)
+        for general in (False, True):
+            got, lse = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], w.H_kv, scale, mode, general)
+            hp.assert_scores_close(got, want, f"paged {page_size} mode={mode} general={general}")
+            np.testing.assert_allclose(lse, want_lse, rtol=0, atol=2e-4)
+
+
+def test_paged_single_prompt_takes_the_two_pass_kernels():
+    w = synth.scaled(synth.workload(3), seqlens=(4100,), L=2)
+    inp = synth.make_qk(w)
+    scale = 1.0 / math.sqrt(w.d)
+    pools, table = hp.paged_copy(inp["k"], inp["cu_seqlens"], 16, seed=3)
+    want, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, orc.LAYER_MAX)
+    got, _ = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], w.H_kv, scale, orc.LAYER_MAX)
+    hp.assert_scores_close(got, want, "paged single prompt")

@@ -288,3 +288,21 @@ def test_rope_makes_logits_depend_on_relative_position_only():
         s, _ = orc.token_importance(q, [k], cu, 0.125, orc.LAYER_MAX)
         out.append(s)
     np.testing.assert_allclose(out[0], out[1], rtol=0.1, atol=1e-4)
+
+
+def test_keys_from_pages_worked_example():
+    """Two sequences of 5 and 3 keys in pages of 4: sequence 0 sits in pages 2 and 0, sequence 1 in
+    page 3; written out by hand."""
+    pool = np.arange(4 * 4 * 1 * 2, dtype=np.uint16).reshape(4, 4, 1, 2)   # element (p, r, 0, t) = 8p + 2r + t
+    table = np.array([[2, 0], [3, 1]], dtype=np.int32)                      # (the 1 is never used)
+    cu = np.array([0, 5, 8], dtype=np.int32)
+    got = orc.keys_from_pages(pool, table, cu)[:, 0, 0]
+    assert got.tolist() == [16, 18, 20, 22, 0, 24, 26, 28]
+
+
+def test_keys_from_pages_identity_table_is_a_reshape():
+    rng = np.random.default_rng(5)
+    pool = rng.integers(0, 65535, size=(6, 8, 2, 4), dtype=np.uint16)
+    cu = np.array([0, 48], dtype=np.int32)
+    table = np.arange(6, dtype=np.int32)[None, :]
+    assert np.array_equal(orc.keys_from_pages(pool, table, cu), pool.reshape(48, 2, 4))
