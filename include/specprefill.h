@@ -104,8 +104,7 @@ typedef struct {
    * sequence b is row (i % page_size) of page d_block_table[b*blocks_per_seq + i/page_size]:
    * element offset page*k_page_stride + (i % page_size)*k_token_stride + g*k_head_stride + t.
    * The table must cover every sequence and hold valid page numbers (not checked: a wrong
-   * entry reads outside the pool).  Scores are still indexed by cu_seqlens[b] + i.  Paged
-   * caches take the two-pass kernels. */
+   * entry reads outside the pool).  Scores are still indexed by cu_seqlens[b] + i. */
   const int32_t* d_block_table; /* int32 [B, blocks_per_seq] page numbers, or NULL             */
   int32_t page_size;         /* tokens per page: a power of two >= 8 (ignored if not paged)   */
   int32_t blocks_per_seq;    /* row length of the table, >= 1                                 */

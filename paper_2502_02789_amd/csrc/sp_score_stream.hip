@@ -75,6 +75,9 @@ struct StreamDev {
   uint32_t* status;   // [0] != 0: a bounded wait ran out (results invalid)
   float* scores;
   float* lse_out;
+  const int32_t* block_table;  // paged cache: page numbers of the (single) prompt, else null
+  int lg_page;
+  int64_t page_stride;
   const uint16_t* k[SP_MAX_LAYERS];
 };
 
@@ -102,7 +105,7 @@ __device__ __forceinline__ uint64_t pack_stat(float m, float s) {
   return ((uint64_t)__float_as_uint(s) << 32) | __float_as_uint(m);
 }
 
-template <int D, int TPW>
+template <int D, int TPW, bool PAGED = false>
 struct Streamer {
   static constexpr int NSETS = 8 / TPW;        // slabs of logits alive in registers
   static constexpr int TPS = TPW + 1;          // stream tiles per slab: query tile + key tiles
@@ -201,6 +204,36 @@ struct Streamer {
     // pin dozens of registers for the whole kernel
     asm volatile("" : "+s"(key_start));
     const uint32_t dst = ring_lds + slot * TILE_B;
+    if constexpr (PAGED) {
+      // Paged cache: the RPI (4 or 8) rows of one load lie in one page (pages hold a power of two
+      // >= 8 keys, tiles start at multiples of 32); a scalar table lookup where a load enters a
+      // new page.  Loads and lanes beyond the prompt re-read a valid row (masked later).
+      int rows = min(32, p.M - key_start);
+      asm volatile("" : "+s"(rows));
+      const int first = rows > 0 ? key_start : 0;
+      const unsigned char* layer = reinterpret_cast<const unsigned char*>(p.k[layer_of(slab)]) +
+                                   2 * (int64_t)kvh_of(slab) * p.hs;
+      const int pmask = (1 << p.lg_page) - 1;
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int i = ln / UNITS;
+      const uint32_t row_part = (uint32_t)((int64_t)i * p.ts * 2);
+      const unsigned char* base = layer;
+#pragma unroll
+      for (int j = 0; j < LOADS; ++j) {
+        const bool inside = j * RPI < rows;
+        const int kk = inside ? first + j * RPI : first;
+        if (j == 0 || !inside || ((j * RPI) & pmask) == 0)
+          base = layer + 2 * ((int64_t)p.block_table[kk >> p.lg_page] * p.page_stride + (int64_t)(kk & pmask) * p.ts);
+        else
+          base += (int64_t)RPI * p.ts * 2;
+        uint32_t lane_off = ld_off[j & 3];
+        asm volatile("" : "+v"(lane_off));
+        if (j * RPI + i >= rows) lane_off -= row_part;  // this lane's row is beyond the prompt: the load's first row instead
+        __builtin_amdgcn_global_load_lds(base + (size_t)lane_off, lds_ptr(dst + j * 1024), 16, 0, 0);
+      }
+      return;
+    }
     const int start_eff = min(key_start, (p.M - 1) & ~31);
     const unsigned char* base = reinterpret_cast<const unsigned char*>(p.k[layer_of(slab)]) +
                                 2 * ((int64_t)kvh_of(slab) * p.hs + (int64_t)start_eff * p.ts);
@@ -613,10 +646,10 @@ struct Streamer {
   }
 };
 
-template <int D, int TPW, bool MEAN>
+template <int D, int TPW, bool MEAN, bool PAGED>
 __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev p) {
   extern __shared__ __align__(1024) unsigned char smem[];
-  using St = Streamer<D, TPW>;
+  using St = Streamer<D, TPW, PAGED>;
   constexpr int NSETS = St::NSETS, TPS = St::TPS;
   St st(p, smem);
   const int cells = p.N * p.KPW;  // (query, key) cells of this workgroup
@@ -789,7 +822,7 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   const int G = a->H / a->H_kv;
   if (a->B != 1 || a->H_kv != 8 || a->T < 1) return pl;
   if (a->rope_theta != 0.f) return pl;  // un-rotated caches take the general kernels
-  if (a->d_block_table) return pl;      // paged caches take the two-pass kernels
+  if (a->d_block_table && a->layer_reduce == SP_LAYER_MEAN) return pl;  // (no paged form of the layer-mean kernel)
   if (G != 1 && G != 2 && G != 4 && G != 8) return pl;
   if (G * a->N > 32 || a->N > 8) return pl;
   nwg = std::min(nwg, kMaxWG);
@@ -837,9 +870,9 @@ size_t stream_status_offset(const sp_score_args* a) {
   return pl.ok ? pl.partial_bytes + pl.lse_bytes : 0;
 }
 
-template <int D, int TPW, bool MEAN>
+template <int D, int TPW, bool MEAN, bool PAGED = false>
 static sp_status launch_stream(const StreamDev& dev, const StreamPlan& pl, hipStream_t stream) {
-  auto kernel = stream_score_kernel<D, TPW, MEAN>;
+  auto kernel = stream_score_kernel<D, TPW, MEAN, PAGED>;
   // once per kernel: allow the large dynamic LDS size and make sure one workgroup fits on a CU
   static int prepared_for = -1;
   if (prepared_for < (int)pl.smem_bytes) {
@@ -877,6 +910,10 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   dev.lse2 = reinterpret_cast<uint32_t*>(ws + pl.partial_bytes);
   dev.status = reinterpret_cast<uint32_t*>(ws + pl.partial_bytes + pl.lse_bytes);
   dev.scores = a->d_scores; dev.lse_out = a->d_lse;
+  dev.block_table = a->d_block_table;
+  dev.lg_page = 0;
+  while (a->d_block_table && (1 << dev.lg_page) < a->page_size) ++dev.lg_page;
+  dev.page_stride = a->k_page_stride;
   for (int l = 0; l < SP_MAX_LAYERS; ++l)
     dev.k[l] = l < a->L ? static_cast<const uint16_t*>(a->k_layers[l]) : nullptr;
 
@@ -886,6 +923,10 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
                      n_vec, dev.status);
   if (hipGetLastError() != hipSuccess) return SP_ELAUNCH;
   const bool mean = a->layer_reduce == SP_LAYER_MEAN;
+  if (a->d_block_table) {
+    if (a->d == 128) return pl.TPW == 1 ? launch_stream<128, 1, false, true>(dev, pl, stream) : launch_stream<128, 2, false, true>(dev, pl, stream);
+    return pl.TPW == 1 ? launch_stream<64, 1, false, true>(dev, pl, stream) : launch_stream<64, 2, false, true>(dev, pl, stream);
+  }
   if (a->d == 128) {
     if (pl.TPW == 1) return mean ? launch_stream<128, 1, true>(dev, pl, stream) : launch_stream<128, 1, false>(dev, pl, stream);
     return mean ? launch_stream<128, 2, true>(dev, pl, stream) : launch_stream<128, 2, false>(dev, pl, stream);

@@ -287,11 +287,18 @@ def test_paged_cache(page_size, n_queries):
             np.testing.assert_allclose(lse, want_lse, rtol=0, atol=2e-4)
 
 
-def test_paged_single_prompt_takes_the_two_pass_kernels():
-    w = synth.scaled(synth.workload(3), seqlens=(4100,), L=2)
+@pytest.mark.parametrize("page_size", [8, 16, 128])
+def test_paged_single_prompt(page_size):
+    """One long prompt behind a block table: the single-pass kernel reads the table itself (layer
+    max); layer mean takes the two-pass kernels.  Ragged tail, several key tiles per workgroup."""
+    w = synth.scaled(synth.workload(3), seqlens=(16500,), L=3)
     inp = synth.make_qk(w)
     scale = 1.0 / math.sqrt(w.d)
-    pools, table = hp.paged_copy(inp["k"], inp["cu_seqlens"], 16, seed=3)
-    want, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, orc.LAYER_MAX)
-    got, _ = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], w.H_kv, scale, orc.LAYER_MAX)
-    hp.assert_scores_close(got, want, "paged single prompt")
+    pools, table = hp.paged_copy(inp["k"], inp["cu_seqlens"], page_size, seed=3)
+    for mode in MODES:
+        want, want_lse = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, mode)
+        got, lse = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], w.H_kv, scale, mode)
+        hp.assert_scores_close(got, want, f"paged single prompt, page {page_size}, mode {mode}")
+        np.testing.assert_allclose(lse, want_lse, rtol=0, atol=2e-4)
+        again, _ = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], w.H_kv, scale, mode)
+        assert np.array_equal(got, again)
