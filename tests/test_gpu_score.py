@@ -125,6 +125,11 @@ def test_argument_errors_launch_nothing():
     assert status(rope_theta=5e5) == sp.SP_ENULL                  # un-rotated cache without query positions
     assert status(rope_theta=-1.0) == sp.SP_EINVAL
     assert status(d_q_pos=cu.data_ptr()) == sp.SP_EINVAL          # positions given but nothing to rotate
+    table = cu.data_ptr()                                          # (never read: the checks come first)
+    assert status(d_block_table=table, page_size=12, blocks_per_seq=4) == sp.SP_EINVAL   # not a power of two
+    assert status(d_block_table=table, page_size=4, blocks_per_seq=4) == sp.SP_EINVAL    # below eight
+    assert status(d_block_table=table, page_size=16, blocks_per_seq=0) == sp.SP_EINVAL
+    assert status(d_block_table=table, page_size=16, blocks_per_seq=4, k_page_stride=12) == sp.SP_EALIGN
     torch.cuda.synchronize()
     assert (s.scores == -7.0).all()
     assert status() == sp.SP_OK
