@@ -676,14 +676,19 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
       __syncthreads();
+      int t = threadIdx.x;
+      asm volatile("" : "+v"(t));  // the cells' addresses are formed here, once per layer, not kept in registers all along
+                                   // (kept, they spill, and a reload from scratch drains the tile prefetch)
 #pragma unroll
       for (int j = 0; j < (MEAN ? 8 : 1); ++j) {
-        const int cell = threadIdx.x + kThreads * j;
+        const int cell = t + kThreads * j;
         if (cell < cells) {
-          tot[j] += fast_exp2(__uint_as_float(lds_peek(St::lds_addr_of(cell_at(cell)))));
-          *cell_at(cell) = -INFINITY;
+          const uint32_t addr = St::lds_addr_of(cell_at(cell));
+          tot[j] += fast_exp2(__uint_as_float(lds_peek(addr)));
+          lds_poke32(addr, 0xff800000u);  // -inf
         }
       }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __syncthreads();
     }
   };
