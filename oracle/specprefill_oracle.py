@@ -20,11 +20,12 @@ Steps and where the paper defines them
   select_chunks        Sec. 3.2.3  Top-K chunks
   pool_select          Algorithm 1, chunk_select_from_smoothed_attention
   gather               Sec. 3.2.4  position-id restoration (+ token ids, embedding rows)
+  keys_from_pages      Sec. 3.3 / Algorithm 1  keys fetched through the engine's slot mapping (block table)
   rope_rotate_bits     not in the paper: the rotary position encoding a Llama-family draft
                        applies to Q and K before they are cached (needed only when the
                        library is handed an un-rotated cache)
 
-Readings where the paper is silent (each listed in the design doc): softmax over the M
+Readings where the paper is silent: softmax over the M
 prompt keys only; scale is an argument; pooling window clipped at sequence edges with
 the divisor equal to the in-range count; last short chunk averaged over its own
 length; k = clamp(ceil(rate * n_chunks - 1e-9), 1, n_chunks); ties go to the lower
