@@ -113,9 +113,9 @@ typedef struct {
 
 /* Bytes of workspace sp_score needs for these shapes (pointers are not read).
  * Returns 0 if the shape fields are invalid.  The size grows with T: per-tile row statistics
- * (L*N*H*8 bytes per 64 tokens) always, plus, for batches whose KV heads have at most four
- * query rows (H/H_kv * N <= 4), 16 bytes per token, layer and KV head of logits kept between
- * the two passes (0.7 GB for 167K tokens of a 32-layer, 8-KV-head model). */
+ * (L*N*H*8 bytes per 64 tokens) always, plus, for batches whose KV heads have at most eight
+ * query rows (H/H_kv * N <= 8), 16 or 32 bytes per token, layer and KV head of logits kept
+ * between the two passes (0.7 GB for 167K tokens of a 32-layer, 8-KV-head model). */
 SP_API size_t sp_score_workspace_bytes(const sp_score_args* args);
 
 /* Enqueue the scoring on hip_stream.  Errors: SP_ENULL, SP_EINVAL (shape limits above),

@@ -31,7 +31,8 @@ constexpr int kTiledWaves = 8;
 constexpr int kTiledThreads = kTiledWaves * kWave;
 constexpr int kWaveKeys = 64;        // keys per wave = the general kernels' tile size (shared tile table)
 constexpr int kPartBufBytes = 3072;  // per wave: pass 0 collects the slabs' row statistics here before writing them out
-constexpr int kKeepRows = 4;         // "keep" mode: a KV head has at most this many query rows (16 bytes of logits per key)
+constexpr int kKeepRows = 4;         // "keep" mode: logits are kept in units of four query rows (16 bytes per key) ...
+constexpr int kKeepMaxRows = 8;      // ... one or two units per KV head
 constexpr int kKeepStageBytes = kWaveKeys * kKeepRows * 4;  // taken from the end of the statistics buffer
 #ifndef SP_TILED_TARGET_WGS
 #define SP_TILED_TARGET_WGS 2048
@@ -53,7 +54,8 @@ struct TiledDev {
   float2* part;          // [(l*N + n)*H + h][max_tiles]
   float* group_scores;   // [n_groups][N][T]: per layer group, log2 of the max probability (layer max) or the
                          // sum over its layers of the per-layer max probability (layer mean)
-  float* logits;         // keep mode: [L][H_kv][T][kKeepRows] base-2 logits (scale * log2(e) applied), else null
+  float* logits;         // keep mode: [L][H_kv][keep_units][T][kKeepRows] base-2 logits (scale * log2(e) applied), else null
+  int keep_units;        // 1 or 2: units of four query rows per KV head
   float* scores;
   const int32_t* block_table;  // paged cache: [B][blocks_per_seq] page numbers, else null
   int lg_page, blocks_per_seq;
@@ -301,11 +303,11 @@ struct TileWalker {
   // the store wants one key's rows per lane).  A slab's logits are one dense 1 KiB store; the
   // caller collects several slabs in registers and stores them together (a store per slab would
   // make the tile waits sit out a store round trip every slab).
-  __device__ __forceinline__ u32x4 transposed_logits() {
+  __device__ __forceinline__ u32x4 transposed_logits(int unit) {  // unit: query rows 4*unit .. 4*unit + 3
     const uint32_t stage = part_lds + kPartBufBytes - kKeepStageBytes;
-    int c = col, h = half, ln = lane;
+    int c = col - unit * kKeepRows, h = half, ln = lane;
     asm volatile("" : "+v"(c), "+v"(h), "+v"(ln));
-    if (c < kKeepRows) {  // (columns beyond G*N repeat row 0: finite values nobody reads)
+    if (c >= 0 && c < kKeepRows) {  // (columns beyond G*N repeat row 0: finite values nobody reads)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -315,11 +317,12 @@ struct TileWalker {
     }
     return lds_peek128(stage + ln * 16);  // (LDS operations of a wave are performed in order)
   }
-  __device__ __forceinline__ void store_logits(const u32x4& v, int l, int g) {
+  __device__ __forceinline__ void store_logits(const u32x4& v, int l, int g, int unit) {
     int ln = lane;
     asm volatile("" : "+v"(ln));
     if (ln < rows_in)  // (never empty: a tile has at least one key)
-      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.logits + (((int64_t)l * p.H_kv + g) * p.T + tok0 + ln) * kKeepRows));
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(
+          p.logits + ((((int64_t)l * p.H_kv + g) * p.keep_units + unit) * p.T + tok0 + ln) * kKeepRows));
     note_issued(1);
   }
   // write the buffered statistics of slabs [first, first + part_n) of the layer group starting
@@ -375,7 +378,7 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
 #pragma unroll
   for (int i = 0; i < ((PASS == 1 && MEAN) ? 32 : 1); ++i) tot[i] = 0.f;
 
-  // keep mode: the logits of up to kKeepHeld slabs wait here, slab held_first + k in held[k]
+  // keep mode: up to kKeepHeld 16-byte units of logits wait here, entry held_first + k in held[k]
   constexpr int kKeepHeld = 8;
   u32x4 held[PASS == 2 ? kKeepHeld : 1];
   int held_n = 0, held_first = 0;
@@ -383,8 +386,9 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
 #pragma unroll
     for (int k = 0; k < (PASS == 2 ? kKeepHeld : 1); ++k) {
       if (k < held_n) {
-        const int sl = held_first + k;
-        w.store_logits(held[k], l0 + sl / p.H_kv, sl % p.H_kv);
+        const int e = held_first + k;  // entry number: slab * keep_units + unit
+        const int sl = p.keep_units == 2 ? e >> 1 : e, unit = p.keep_units == 2 ? e & 1 : 0;
+        w.store_logits(held[k], l0 + sl / p.H_kv, sl % p.H_kv, unit);
       }
     }
     held_first += held_n;
@@ -424,7 +428,8 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
     if (PASS != 1) {
       w.stats_tile(1);
       if constexpr (PASS == 2) {
-        const u32x4 v = w.transposed_logits();
+       for (int unit = 0; unit < p.keep_units; ++unit) {
+        const u32x4 v = w.transposed_logits(unit);
         switch (held_n) {
           case 0: held[0] = v; break;
           case 1: held[1] = v; break;
@@ -437,6 +442,7 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
         }
         held_n = __builtin_amdgcn_readfirstlane(held_n + 1);
         if (held_n == kKeepHeld) flush_held();
+       }
       }
       w.keep_partial();
       if (w.partials_full(PASS == 2 ? kPartBufBytes - kKeepStageBytes : kPartBufBytes)) {
@@ -511,14 +517,14 @@ __global__ __launch_bounds__(256) void logit_score_kernel(const TiledDev p) {
   if (tok >= p.T) return;  // (the four threads of a token leave together)
   const int b = upper_segment(p.cu, p.B, (int)tok);
   const int rows = p.Gp * p.N;
-  float best[kKeepRows], tot[kKeepRows];  // per query (entries beyond N unused)
+  float best[kKeepMaxRows], tot[kKeepMaxRows];  // per query (entries beyond N unused)
 #pragma unroll
-  for (int n = 0; n < kKeepRows; ++n) { best[n] = -INFINITY; tot[n] = 0.f; }
+  for (int n = 0; n < kKeepMaxRows; ++n) { best[n] = -INFINITY; tot[n] = 0.f; }
   const float* lse_b = p.ws_lse + (int64_t)b * p.N * p.H;
   const bool one_query_four_heads = p.N == 1 && p.G == 4;  // the common shape: a KV head's four log-sum-exps are one 16-byte load
   for (int l = part; l < p.L; l += 4) {
     const float* lse_l = lse_b + (int64_t)l * p.B * p.N * p.H;
-    const float* src = p.logits + ((int64_t)l * p.H_kv * p.T + tok) * kKeepRows;
+    const float* src = p.logits + ((int64_t)l * p.H_kv * p.keep_units * p.T + tok) * kKeepRows;
     if (one_query_four_heads) {
       float m = best[0];
 #pragma unroll 8
@@ -532,27 +538,29 @@ __global__ __launch_bounds__(256) void logit_score_kernel(const TiledDev p) {
       if (MEAN) { tot[0] += fast_exp2(best[0]); best[0] = -INFINITY; }
       continue;
     }
-#pragma unroll 4
-    for (int g = 0; g < p.H_kv; ++g) {
-      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (int64_t)g * p.T * kKeepRows));
+#pragma unroll 2
+    for (int gu = 0; gu < p.H_kv * p.keep_units; ++gu) {
+      const int g = p.keep_units == 2 ? gu >> 1 : gu, unit = p.keep_units == 2 ? gu & 1 : 0;
+      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (int64_t)gu * p.T * kKeepRows));
 #pragma unroll
-      for (int r = 0; r < kKeepRows; ++r) {
+      for (int rr = 0; rr < kKeepRows; ++rr) {
+        const int r = unit * kKeepRows + rr;
         if (r < rows) {
           const int n = r >> p.lgG, h = g * p.G + ((r & (p.Gp - 1)) < p.G ? (r & (p.Gp - 1)) : 0);
-          const float x = __uint_as_float(v[r]) - 1.4426950408889634f * lse_l[n * p.H + h];
+          const float x = __uint_as_float(v[rr]) - 1.4426950408889634f * lse_l[n * p.H + h];
 #pragma unroll
-          for (int q = 0; q < kKeepRows; ++q)
+          for (int q = 0; q < kKeepMaxRows; ++q)
             if (q == n) best[q] = fmaxf(best[q], x);
         }
       }
     }
     if (MEAN) {
 #pragma unroll
-      for (int n = 0; n < kKeepRows; ++n) { tot[n] += fast_exp2(best[n]); best[n] = -INFINITY; }
+      for (int n = 0; n < kKeepMaxRows; ++n) { tot[n] += fast_exp2(best[n]); best[n] = -INFINITY; }
     }
   }
 #pragma unroll
-  for (int n = 0; n < kKeepRows; ++n) {  // fold the four threads of the token
+  for (int n = 0; n < kKeepMaxRows; ++n) {  // fold the four threads of the token
     if (MEAN) {
       tot[n] += __shfl_xor(tot[n], 1, kWave);
       tot[n] += __shfl_xor(tot[n], 2, kWave);
@@ -566,7 +574,7 @@ __global__ __launch_bounds__(256) void logit_score_kernel(const TiledDev p) {
   nv = max(1, min(nv, p.N));
   float sum = 0.f;
 #pragma unroll
-  for (int n = 0; n < kKeepRows; ++n)
+  for (int n = 0; n < kKeepMaxRows; ++n)
     if (n < nv) sum += MEAN ? tot[n] : fast_exp2(best[n]);
   p.scores[tok] = sum / (MEAN ? (float)nv * (float)p.L : (float)nv);
 }
@@ -624,11 +632,12 @@ bool tiled_supported(const sp_score_args* a) {
 #ifndef SP_TILED_KEEP_MAX_BYTES
 #define SP_TILED_KEEP_MAX_BYTES (16ull << 30)
 #endif
+static int keep_units(const sp_score_args* a) { return padded_group(a) * a->N <= kKeepRows ? 1 : 2; }
 static size_t keep_bytes(const sp_score_args* a) {
-  return sizeof(float) * kKeepRows * (size_t)a->L * a->H_kv * (size_t)a->T;
+  return sizeof(float) * kKeepRows * keep_units(a) * (size_t)a->L * a->H_kv * (size_t)a->T;
 }
 static bool keep_mode(const sp_score_args* a) {
-  return padded_group(a) * a->N <= kKeepRows && keep_bytes(a) <= SP_TILED_KEEP_MAX_BYTES;
+  return padded_group(a) * a->N <= kKeepMaxRows && keep_bytes(a) <= SP_TILED_KEEP_MAX_BYTES;
 }
 
 size_t tiled_extra_workspace_bytes(const sp_score_args* a) {
@@ -693,6 +702,7 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
   const bool keep = keep_mode(a);
   dev.group_scores = keep ? nullptr : static_cast<float*>(extra);
   dev.logits = keep ? static_cast<float*>(extra) : nullptr;
+  dev.keep_units = keep_units(a);
   dev.scores = a->d_scores;
   dev.block_table = gen.block_table; dev.lg_page = gen.lg_page; dev.blocks_per_seq = gen.blocks_per_seq;
   dev.page_stride = gen.k_page_stride;

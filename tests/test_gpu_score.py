@@ -216,6 +216,9 @@ def test_rotation_by_position_zero_changes_nothing():
     dict(H=5, H_kv=5, d=64, N=16, L=2),
     dict(H=3, H_kv=3, d=64, N=3, L=3),     # three query rows per KV head: logits kept between the passes
     dict(H=4, H_kv=2, d=128, N=2, L=2),    # four rows from two queries x two heads
+    dict(H=32, H_kv=8, d=128, N=2, L=3),   # eight rows (one look-ahead step): logits kept as two 16-byte units
+    dict(H=16, H_kv=2, d=64, N=1, L=2),    # eight heads per KV head
+    dict(H=6, H_kv=3, d=64, N=3, L=2),     # six rows: the second unit is partly padding
 ])
 def test_ragged_batch_tile_boundaries(shape):
     lens = (1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 0, 700)
