@@ -118,6 +118,33 @@ __device__ __forceinline__ int block_exclusive_scan_1024(int v, int* sh, int* to
   return incl - v;
 }
 
+// The bucket holding the need-th largest of the keys still in play: the highest bucket whose
+// count, added to the counts above it, reaches `need`.  One wave, four buckets per lane, suffix
+// sums by shuffles.  Call with threads 0..63; writes *bucket and *need_left.
+__device__ __forceinline__ void find_bucket(const int* hist, int need, int t, int* bucket_out, int* need_left) {
+  int h[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) h[u] = hist[4 * t + u];
+  const int own = h[0] + h[1] + h[2] + h[3];
+  int suffix = own;  // counts of this lane's buckets and of all higher lanes'
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int v = __shfl_down(suffix, off, kWave);
+    if (t + off < kWave) suffix += v;
+  }
+  int above = suffix - own;
+  if (above < need && need <= suffix) {  // exactly one lane: the keys still in play number at least `need`
+    int bucket = 4 * t;
+#pragma unroll
+    for (int u = 3; u >= 0; --u) {
+      if (above + h[u] >= need) { bucket = 4 * t + u; break; }
+      above += h[u];
+    }
+    *bucket_out = bucket;
+    *need_left = need - above;
+  }
+}
+
 // One workgroup per sequence.
 __global__ __launch_bounds__(1024) void select_kernel(const SelDev p) {
   __shared__ int hist[256];
@@ -150,31 +177,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const SelDev p) {
       if ((key & himask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255u)], 1);
     }
     __syncthreads();
-    // the bucket holding the need-th largest remaining key: the highest bucket whose count, added to
-    // the counts above it, reaches `need`.  One wave, four buckets per lane, suffix sums by shuffles.
-    if (t < kWave) {
-      int h[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) h[u] = hist[4 * t + u];
-      const int own = h[0] + h[1] + h[2] + h[3];
-      int suffix = own;  // counts of this lane's buckets and of all higher lanes'
-#pragma unroll
-      for (int off = 1; off < kWave; off <<= 1) {
-        const int v = __shfl_down(suffix, off, kWave);
-        if (t + off < kWave) suffix += v;
-      }
-      int above = suffix - own;
-      if (above < need && need <= suffix) {  // exactly one lane: the keys still in play number at least `need`
-        int bucket = 4 * t;
-#pragma unroll
-        for (int u = 3; u >= 0; --u) {
-          if (above + h[u] >= need) { bucket = 4 * t + u; break; }
-          above += h[u];
-        }
-        s_bucket = bucket;
-        s_need = need - above;
-      }
-    }
+    if (t < kWave) find_bucket(hist, need, t, &s_bucket, &s_need);
     __syncthreads();
     prefix |= (uint64_t)s_bucket << shift;
     need = s_need;
@@ -209,14 +212,15 @@ __global__ __launch_bounds__(1024) void select_kernel(const SelDev p) {
 }
 
 // Single sequence with at most kSingleMaxChunks chunks: top-k, compaction and the kept-index
-// list in one workgroup.  The chunks are sorted by (score descending, index ascending) with a
-// bitonic network in LDS, one compare-exchange per thread and stage; the k-th entry of the sorted
-// list is the threshold every chunk is then compared with.
+// list in one workgroup and one launch.  The k-th largest key is found by the same 8-pass radix
+// select as in select_kernel, on keys held in LDS; ties at the threshold go to the lower chunk
+// indices by an ordered scan; kept tokens are written straight away.
 constexpr int kSingleMaxChunks = 2048;
 __global__ __launch_bounds__(1024) void select_emit_single_kernel(const SelDev p) {
   __shared__ uint64_t keys[kSingleMaxChunks];
-  __shared__ uint16_t ids[kSingleMaxChunks];
+  __shared__ int hist[256];
   __shared__ int sh[1024];
+  __shared__ int s_bucket, s_need;
   const int t = threadIdx.x;
   const int M = p.T;
   const int n = (M + p.chunk - 1) / p.chunk;
@@ -228,62 +232,50 @@ __global__ __launch_bounds__(1024) void select_emit_single_kernel(const SelDev p
   const double scaled = p.keep_rate * (double)n;
   const double kd = ceil(scaled - 1e-9);
   const int k = (int)fmin((double)n, fmax(1.0, kd));
-  int N = 2;
-  while (N < n) N <<= 1;
-  uint64_t mine[kSingleMaxChunks / 1024];
-#pragma unroll
-  for (int r = 0; r < kSingleMaxChunks / 1024; ++r) {
-    const int j = t + r * 1024;
-    mine[r] = j < n ? order_key(p.cs[j]) : 0;  // padding sorts last: key 0 is below every real key, index above
-    if (j < N) {
-      keys[j] = mine[r];
-      ids[j] = (uint16_t)j;
-    }
-  }
+  for (int j = t; j < n; j += 1024) keys[j] = order_key(p.cs[j]);
   __syncthreads();
-  // "a goes before b"
-  auto before = [](uint64_t ka, int ia, uint64_t kb, int ib) { return ka > kb || (ka == kb && ia < ib); };
-  for (int size = 2; size <= N; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int e = t; e < N / 2; e += 1024) {
-        const int i = 2 * e - (e & (stride - 1));  // lower partner: bit `stride` clear
-        const int j = i + stride;
-        const bool ascending_block = (i & size) != 0;  // alternate blocks are sorted the other way round
-        const uint64_t ki = keys[i], kj = keys[j];
-        const int ii = ids[i], ij = ids[j];
-        const bool in_order = before(ki, ii, kj, ij);
-        if (in_order == ascending_block) {
-          keys[i] = kj; keys[j] = ki;
-          ids[i] = (uint16_t)ij; ids[j] = (uint16_t)ii;
-        }
-      }
-      // pairs up to 64 apart stay inside the 128 elements one wave works on, and a wave's LDS
-      // accesses are performed in order: only wider strides (and the step down from them) need
-      // the whole workgroup to meet
-      if (stride > 64) __syncthreads(); else __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+
+  uint64_t prefix = 0;
+  int need = k;
+  for (int pass = 7; pass >= 0; --pass) {
+    if (t < 256) hist[t] = 0;
+    __syncthreads();
+    const int shift = pass * 8;
+    const uint64_t himask = (pass == 7) ? 0ull : (~0ull << (shift + 8));
+    for (int j = t; j < n; j += 1024) {
+      const uint64_t key = keys[j];
+      if ((key & himask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255u)], 1);
     }
     __syncthreads();
+    if (t < kWave) find_bucket(hist, need, t, &s_bucket, &s_need);
+    __syncthreads();
+    prefix |= (uint64_t)s_bucket << shift;
+    need = s_need;
+    __syncthreads();
   }
-  const uint64_t thr_key = keys[k - 1];
-  const int thr_id = ids[k - 1];
-  __syncthreads();
-  // keep flags by chunk index (reuse ids[] as the flag array)
-#pragma unroll
-  for (int r = 0; r < kSingleMaxChunks / 1024; ++r) {
-    const int j = t + r * 1024;
-    if (j < n) ids[j] = (mine[r] > thr_key || (mine[r] == thr_key && j <= thr_id)) ? 1 : 0;
-  }
-  __syncthreads();
+
   // ordered pass: thread t owns chunks [j0, j1) in index order
   const int per = (n + 1023) / 1024;
   const int j0 = min(n, t * per), j1 = min(n, j0 + per);
+  int eq = 0;
+  for (int j = j0; j < j1; ++j) eq += (keys[j] == prefix) ? 1 : 0;
+  int total_eq;
+  int eq_rank = block_exclusive_scan_1024(eq, sh, &total_eq);
   int tokens = 0;
-  for (int j = j0; j < j1; ++j)
-    if (ids[j]) tokens += min(p.chunk, M - j * p.chunk);
+  {
+    int r = eq_rank;
+    for (int j = j0; j < j1; ++j) {
+      const uint64_t key = keys[j];
+      const bool keep = key > prefix || (key == prefix && r++ < need);
+      if (keep) tokens += min(p.chunk, M - j * p.chunk);
+    }
+  }
   int total_tokens;
   int off = block_exclusive_scan_1024(tokens, sh, &total_tokens);
   for (int j = j0; j < j1; ++j) {
-    if (!ids[j]) continue;
+    const uint64_t key = keys[j];
+    const bool keep = key > prefix || (key == prefix && eq_rank++ < need);
+    if (!keep) continue;
     const int len = min(p.chunk, M - j * p.chunk);
     for (int r = 0; r < len; ++r)
       if ((int64_t)off + r < p.capacity) p.kept_idx[off + r] = j * p.chunk + r;
