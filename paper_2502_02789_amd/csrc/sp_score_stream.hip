@@ -827,7 +827,6 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   const int G = a->H / a->H_kv;
   if (a->B != 1 || a->H_kv != 8 || a->T < 1) return pl;
   if (a->rope_theta != 0.f) return pl;  // un-rotated caches take the general kernels
-  if (a->d_block_table && a->layer_reduce == SP_LAYER_MEAN) return pl;  // (no paged form of the layer-mean kernel)
   if (G != 1 && G != 2 && G != 4 && G != 8) return pl;
   if (G * a->N > 32 || a->N > 8) return pl;
   nwg = std::min(nwg, kMaxWG);
@@ -929,8 +928,12 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   if (hipGetLastError() != hipSuccess) return SP_ELAUNCH;
   const bool mean = a->layer_reduce == SP_LAYER_MEAN;
   if (a->d_block_table) {
-    if (a->d == 128) return pl.TPW == 1 ? launch_stream<128, 1, false, true>(dev, pl, stream) : launch_stream<128, 2, false, true>(dev, pl, stream);
-    return pl.TPW == 1 ? launch_stream<64, 1, false, true>(dev, pl, stream) : launch_stream<64, 2, false, true>(dev, pl, stream);
+    if (a->d == 128) {
+      if (pl.TPW == 1) return mean ? launch_stream<128, 1, true, true>(dev, pl, stream) : launch_stream<128, 1, false, true>(dev, pl, stream);
+      return mean ? launch_stream<128, 2, true, true>(dev, pl, stream) : launch_stream<128, 2, false, true>(dev, pl, stream);
+    }
+    if (pl.TPW == 1) return mean ? launch_stream<64, 1, true, true>(dev, pl, stream) : launch_stream<64, 1, false, true>(dev, pl, stream);
+    return mean ? launch_stream<64, 2, true, true>(dev, pl, stream) : launch_stream<64, 2, false, true>(dev, pl, stream);
   }
   if (a->d == 128) {
     if (pl.TPW == 1) return mean ? launch_stream<128, 1, true>(dev, pl, stream) : launch_stream<128, 1, false>(dev, pl, stream);

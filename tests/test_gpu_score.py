@@ -297,8 +297,8 @@ def test_paged_cache(page_size, n_queries):
 
 @pytest.mark.parametrize("page_size", [8, 16, 128])
 def test_paged_single_prompt(page_size):
-    """One long prompt behind a block table: the single-pass kernel reads the table itself (layer
-    max); layer mean takes the two-pass kernels.  Ragged tail, several key tiles per workgroup."""
+    """One long prompt behind a block table: the single-pass kernel reads the table itself.
+    Ragged tail, several key tiles per workgroup."""
     w = synth.scaled(synth.workload(3), seqlens=(16500,), L=3)
     inp = synth.make_qk(w)
     scale = 1.0 / math.sqrt(w.d)
