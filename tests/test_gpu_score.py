@@ -310,3 +310,37 @@ def test_paged_single_prompt(page_size):
         np.testing.assert_allclose(lse, want_lse, rtol=0, atol=2e-4)
         again, _ = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], w.H_kv, scale, mode)
         assert np.array_equal(got, again)
+
+
+def test_seeded_shape_sweep_fast_paths_agree_with_the_plain_kernels():
+    """Forty seeded shapes (group sizes 1..8, ragged batches with empty and one-key sequences,
+    both head dims, contiguous and paged caches, both modes): whatever kernels sp_score picks must
+    agree with the plain two-pass kernels, which the other tests pin to the oracle."""
+    rng = np.random.default_rng(20250207)
+    for case in range(40):
+        G = int(rng.integers(1, 9))
+        Gp = 1 if G == 1 else 2 if G == 2 else 4 if G <= 4 else 8
+        H_kv = int(rng.choice([1, 2, 3, 8]))
+        N = int(rng.integers(1, min(16, 32 // Gp) + 1))
+        d = int(rng.choice([64, 128]))
+        L = int(rng.integers(1, 5))
+        B = int(rng.integers(1, 6))
+        lens = tuple(int(x) for x in rng.choice([0, 1, 31, 64, 65, 200, 777, 1500], size=B))
+        if sum(lens) == 0:
+            lens = lens[:-1] + (97,)
+        mode = MODES[case % 2]
+        paged = case % 3 == 0
+        w = synth.scaled(synth.workload(2), seqlens=lens, L=L, N=N, H=G * H_kv, H_kv=H_kv, d=d,
+                         salient_frac=0.02, salient_run=1)
+        inp = synth.make_qk(w)
+        scale = 1.0 / math.sqrt(d)
+        what = f"case {case}: lens={lens} G={G} H_kv={H_kv} N={N} d={d} L={L} mode={mode} paged={paged}"
+        if paged:
+            pools, table = hp.paged_copy(inp["k"], inp["cu_seqlens"], int(rng.choice([8, 16, 32])), seed=case)
+            a, la = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], H_kv, scale, mode)
+            g, lg = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], H_kv, scale, mode, general=True)
+        else:
+            a, la = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], H_kv, scale, mode)
+            g, lg = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], H_kv, scale, mode, general=True)
+        np.testing.assert_allclose(a, g, rtol=2e-3, atol=1e-30, err_msg=what)
+        np.testing.assert_allclose(la, lg, rtol=0, atol=2e-4, err_msg=what)
