@@ -99,3 +99,45 @@ def test_paper_variants_as_presets(variant):
     w = synth.scaled(synth.workload(3), seqlens=(3000, 1111), L=3, N=v["n_queries"], chunk=v["chunk"],
                      pool_window=v["pool_window"], keep_rate=0.2, salient_frac=0.02, salient_run=1)
     _run_whole_path(w, orc.LAYER_MAX)
+
+
+def test_whole_step_replays_from_a_hip_graph():
+    """The three calls only enqueue kernels (no allocation, no memset, no synchronisation), so a
+    step can be captured once and replayed: three replays, with eager work and synchronisations of
+    the program's own in between, must each reproduce the eager result bit for bit."""
+    import torch
+    from paper_2502_02789_amd import binding as sp, device as dev
+    w = synth.scaled(synth.workload(3), seqlens=(9000,), L=4)
+    inp = synth.make_qk(w)
+    cu = torch.from_numpy(inp["cu_seqlens"]).cuda()
+    ids = torch.from_numpy(synth.make_token_ids(w)).cuda()
+    scorer = dev.Scorer(dev.bf16_from_bits(inp["q"]), [dev.bf16_from_bits(k) for k in inp["k"]], cu,
+                        H_kv=w.H_kv, scale=1.0 / math.sqrt(w.d))
+    sel = dev.Selector(scorer.scores, cu, chunk=w.chunk, pool_window=w.pool_window, keep_rate=w.keep_rate)
+    gat = dev.Gatherer(sel, token_ids=ids)
+
+    def step():
+        scorer.run()
+        sel.run()
+        gat.run()
+
+    step()                                  # eager: also does the one-time kernel set-up
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (scorer.scores, sel.kept_idx, sel.cu_keep, gat.kept_pos, gat.kept_ids)]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in (scorer.scores, sel.kept_idx, gat.kept_pos, gat.kept_ids):
+            t.fill_(-3)                     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        sp.sp_score_check(scorer.args)
+        n = int(sel.cu_keep[-1])            # (entries beyond the kept count are nobody's to write)
+        got = (scorer.scores, sel.kept_idx[:n], sel.cu_keep, gat.kept_pos[:n], gat.kept_ids[:n])
+        for a, b in zip(got, (want[0], want[1][:n], want[2], want[3][:n], want[4][:n])):
+            assert torch.equal(a, b), f"replay {replay}"
