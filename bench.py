@@ -4,7 +4,9 @@
 One "step" = sp_score + sp_pool_select + sp_gather over one synthetic prompt batch whose
 queries and K cache are already resident in HBM.  The default workload is the 8B-draft /
 32K-token scoring configuration (32 layers, 32 query / 8 KV heads, head dim 128, 8 look-ahead
-queries, 2 GiB bf16 K cache).  Prints ONE JSON line.
+queries, 2 GiB bf16 K cache).  Prints ONE JSON line.  After the timed loop the run checks what
+it timed: sp_score_check, the scores against the fp64 oracle (the cpu_baseline leg computes them
+anyway) and the keep set against the oracle's; a miss makes the process exit non-zero.
 
   python bench.py --gpus 1 --steps 20 --warmup 5
 """
@@ -20,17 +22,18 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+SCORE_RTOL = 2e-3        # score tolerance against the fp64 oracle (the same as the parity tests)
 
 
-def measured_traffic(workload, general):
+def measured_traffic(workload, general, layer_reduce):
     """HBM bytes per sp_score launch as read from the FETCH_SIZE / WRITE_SIZE counter runs whose
     summaries sit under profiles/ (counters cannot be collected from inside this process)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if general or not os.path.exists(path):
+    if general or layer_reduce != "max" or not os.path.exists(path):
         return None
     with open(path) as f:
         table = json.load(f)
-    entry = table.get(f"workload{workload}:stream_score_kernel") or table.get(f"workload{workload}:sp_score")
+    entry = table.get(f"workload{workload}:sp_score")
     return None if entry is None else entry["traffic_bytes_per_launch"]
 
 
@@ -38,7 +41,8 @@ def cpu_baseline(w, inp, layer_reduce, sample_layers):
     """Times the fp64 oracle, unchanged, on the same inputs (full prompt, all heads and queries)
     plus selection and gather on its scores.  sample_layers = 0: a two-layer pilot decides how
     many layers fit about 15 s (cost is linear in layers); when the whole depth fits, whole
-    passes are repeated until about 10 s have been spent and their mean is reported."""
+    passes are repeated until about 10 s have been spent and their mean is reported.
+    Returns (json object, oracle scores or None if only a layer subset was run)."""
     import numpy as np
     from oracle import specprefill_oracle as orc
     try:
@@ -77,11 +81,147 @@ def cpu_baseline(w, inp, layer_reduce, sample_layers):
     est_full = t_score * (w.L / sample_layers) + t_sel
     what = (f"all {w.L} layers, mean of {passes} whole passes of {t_score:.2f} s" if sample_layers == w.L else
             f"{sample_layers} of {w.L} layers in {t_score:.2f} s, scaled linearly in layers")
-    return {
+    out = {
         "value": w.T / est_full, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
         "sample": f"{what}{note}; same inputs (full {w.T}-token prompt, all heads and queries); "
                   f"plus selection+gather {t_sel:.3f} s",
     }
+    return out, (scores if sample_layers == w.L else None)
+
+
+def check_against(w, inp, gpu_scores, gpu_kept, gpu_cu_keep, ref_scores, ref_name):
+    """Scores element by element (tolerance of the parity tests), then the keep set: selection by the
+    oracle on the reference scores against what the GPU kept; chunks may differ only if their
+    reference chunk score lies within the score tolerance of the k-th."""
+    import numpy as np
+    from oracle import specprefill_oracle as orc
+    ref = np.asarray(ref_scores, dtype=np.float64)
+    got = np.asarray(gpu_scores, dtype=np.float64)
+    finite = bool(np.isfinite(got).all())
+    err = np.abs(got - ref) / np.maximum(np.abs(ref), 1e-300)
+    scores_ok = finite and bool((np.abs(got - ref) <= SCORE_RTOL * np.abs(ref) + 1e-30).all())
+    kept_o, cu_keep_o, cs, cu_chunks = orc.pool_select(ref.astype(np.float32), inp["cu_seqlens"], w.chunk,
+                                                       w.pool_window, w.keep_rate)
+    cu = inp["cu_seqlens"]
+    equal, swapped, keep_ok = True, 0, True
+    for b in range(w.B):
+        g = gpu_kept[int(gpu_cu_keep[b]):int(gpu_cu_keep[b + 1])].astype(np.int64)
+        o = kept_o[int(cu_keep_o[b]):int(cu_keep_o[b + 1])]
+        if len(g) == len(o) and (g == o).all():
+            continue
+        equal = False
+        seg = cs[cu_chunks[b]:cu_chunks[b + 1]]
+        k = orc.keep_count(len(seg), w.keep_rate)
+        kth = np.sort(seg)[::-1][k - 1]
+        gc = set(((g - int(cu[b])) // w.chunk).tolist())
+        oc = set(((o - int(cu[b])) // w.chunk).tolist())
+        if len(gc) != len(oc):
+            keep_ok = False
+        for j in gc ^ oc:
+            swapped += 1
+            if abs(seg[j] - kth) > SCORE_RTOL * abs(kth):
+                keep_ok = False
+    return {
+        "checked_against": ref_name, "score_max_rel_err": float(err.max()) if finite else None,
+        "scores_within_tolerance": scores_ok, "keep_set_equal": equal, "swapped_chunks": swapped,
+        "ok": bool(scores_ok and keep_ok),
+    }
+
+
+class Problem:
+    """One workload resident on the GPU with the three calls' argument structs."""
+
+    def __init__(self, number, layer_reduce, threads=16):
+        import torch
+        from paper_2502_02789_amd import binding as sp, device as dev, synth
+        self.w = w = synth.workload(number)
+        self.mode_name = layer_reduce
+        mode = sp.SP_LAYER_MAX if layer_reduce == "max" else sp.SP_LAYER_MEAN
+        t0 = time.perf_counter()
+        self.inp = inp = synth.make_qk(w, threads=threads)
+        inp["token_ids"] = synth.make_token_ids(w)
+        q = dev.bf16_from_bits(inp["q"])
+        ks = [dev.bf16_from_bits(k) for k in inp["k"]]
+        cu = torch.from_numpy(inp["cu_seqlens"]).cuda()
+        ids = torch.from_numpy(inp["token_ids"]).cuda()
+        embed = None
+        if w.embed_dim:
+            embed = dev.bf16_from_bits(synth.make_embedding(w.vocab, w.embed_dim, w.seed, threads=threads))
+        self.t_gen = time.perf_counter() - t0
+        # the benchmark box runs nothing else on its GPU: the single-pass kernels may be used
+        self.scorer = dev.Scorer(q, ks, cu, H_kv=w.H_kv, scale=1.0 / math.sqrt(w.d), layer_reduce=mode,
+                                 exclusive_device=True)
+        cap = sp.sp_keep_upper_bound(list(w.seqlens), w.chunk, w.keep_rate)
+        self.sel = dev.Selector(self.scorer.scores, cu, chunk=w.chunk, pool_window=w.pool_window,
+                                keep_rate=w.keep_rate, capacity=cap)
+        self.gat = dev.Gatherer(self.sel, token_ids=ids, embed=embed)
+        self.stream = torch.cuda.current_stream()
+
+    def step(self, ev=None, general=False):
+        s = self.stream
+        if ev is not None:
+            ev[0].record(s)
+        self.scorer.run(s, general=general)
+        if ev is not None:
+            ev[1].record(s)
+        self.sel.run(s)
+        if ev is not None:
+            ev[2].record(s)
+        self.gat.run(s)
+        if ev is not None:
+            ev[3].record(s)
+
+    def timed(self, steps, warmup, general=False):
+        """-> (wall ms per step, sorted sp_score ms, sorted select ms, sorted gather ms)"""
+        import torch
+        for _ in range(warmup):
+            self.step(general=general)
+        torch.cuda.synchronize()
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(events[i], general=general)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        return (wall_ms, sorted(e[0].elapsed_time(e[1]) for e in events),
+                sorted(e[1].elapsed_time(e[2]) for e in events), sorted(e[2].elapsed_time(e[3]) for e in events))
+
+    def gather_bytes(self):
+        """Algorithmic bytes of sp_gather: per kept token its row read and written, ids and positions."""
+        n_keep = int(self.sel.cu_keep[-1])
+        row = 2 * self.w.embed_dim * 2 if self.w.embed_dim else 0
+        return n_keep * (row + 4 * 4)
+
+
+def side_measurement(number, layer_reduce, steps, warmup):
+    """GPU-only timing of another workload / layer reduction (no oracle leg), cross-checked
+    against the library's plain two-pass kernels on the same inputs."""
+    import numpy as np
+    import torch
+    from paper_2502_02789_amd import binding as sp
+    pr = Problem(number, layer_reduce)
+    w = pr.w
+    _, score_ms, sel_ms, gat_ms = pr.timed(steps, warmup)
+    sp.sp_score_check(pr.scorer.args)
+    fast = pr.scorer.scores.cpu().numpy().astype(np.float64)
+    pr.scorer.run(pr.stream, general=True)
+    torch.cuda.synchronize()
+    plain = pr.scorer.scores.cpu().numpy().astype(np.float64)
+    rel = float((np.abs(fast - plain) / np.maximum(np.abs(plain), 1e-300)).max())
+    avg = sum(score_ms) / len(score_ms)
+    algo = w.k_bytes() + 4 * w.T
+    g_avg = sum(gat_ms) / len(gat_ms)
+    out = {
+        "workload": f"{w.name}: B={w.B} T={w.T} L={w.L} H={w.H} H_kv={w.H_kv} d={w.d} N={w.N}",
+        "layer_reduce": layer_reduce, "sp_score_us": avg * 1e3, "sp_score_gbps": algo / (avg * 1e-3) / 1e9,
+        "frac_of_hbm_peak": algo / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "sp_pool_select_us": sum(sel_ms) / len(sel_ms) * 1e3, "sp_gather_us": g_avg * 1e3,
+        "sp_gather_gbps": pr.gather_bytes() / (g_avg * 1e-3) / 1e9,
+        "max_rel_diff_vs_plain_kernels": rel, "ok": bool(rel <= 2 * SCORE_RTOL),
+    }
+    del pr
+    torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -95,6 +235,8 @@ def main():
     ap.add_argument("--cpu-sample-layers", type=int, default=0,
                     help="layers the oracle is timed on (0: as many as fit about 15 s, all of them if possible)")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--no-also", action="store_true",
+                    help="skip the GPU-only side measurements of the other workloads and of the layer-mean mode")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="also launch a plain device copy of MIB MiB three times outside the timed region, so a "
                          "counter run of this command shows what FETCH_SIZE/WRITE_SIZE read for known traffic")
@@ -106,70 +248,42 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2502_02789_amd import binding as sp, device as dev, synth
+    from paper_2502_02789_amd import binding as sp
 
     sp.load_library()                       # fails loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    w = synth.workload(args.workload)
-    mode = sp.SP_LAYER_MAX if args.layer_reduce == "max" else sp.SP_LAYER_MEAN
 
-    t_gen = time.perf_counter()
-    inp = synth.make_qk(w, threads=16)
-    inp["token_ids"] = synth.make_token_ids(w)
-    q = dev.bf16_from_bits(inp["q"])
-    ks = [dev.bf16_from_bits(k) for k in inp["k"]]
-    cu = torch.from_numpy(inp["cu_seqlens"]).cuda()
-    ids = torch.from_numpy(inp["token_ids"]).cuda()
-    embed = None
-    if w.embed_dim:
-        embed = dev.bf16_from_bits(synth.make_embedding(w.vocab, w.embed_dim, w.seed, threads=16))
-    t_gen = time.perf_counter() - t_gen
-
-    scorer = dev.Scorer(q, ks, cu, H_kv=w.H_kv, scale=1.0 / math.sqrt(w.d), layer_reduce=mode)
-    cap = sp.sp_keep_upper_bound(list(w.seqlens), w.chunk, w.keep_rate)
-    sel = dev.Selector(scorer.scores, cu, chunk=w.chunk, pool_window=w.pool_window, keep_rate=w.keep_rate,
-                       capacity=cap)
-    gat = dev.Gatherer(sel, token_ids=ids, embed=embed)
-    stream = torch.cuda.current_stream()
-
-    def step(ev=None):
-        if ev is not None:
-            ev[0].record(stream)
-        scorer.run(stream, general=args.general)
-        if ev is not None:
-            ev[1].record(stream)
-        sel.run(stream)
-        gat.run(stream)
-        if ev is not None:
-            ev[2].record(stream)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+    pr = Problem(args.workload, args.layer_reduce)
+    w = pr.w
     if args.calibrate_copy:
+        pr.step(general=args.general)
+        torch.cuda.synchronize()
         src = torch.empty(args.calibrate_copy << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(events[i])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    score_ms = sorted(e[0].elapsed_time(e[1]) for e in events)
-    tail_ms = sorted(e[1].elapsed_time(e[2]) for e in events)
+    ms_per_step, score_ms, sel_ms, gat_ms = pr.timed(args.steps, args.warmup, general=args.general)
     score_avg_ms = sum(score_ms) / len(score_ms)
-    tail_avg_ms = sum(tail_ms) / len(tail_ms)
+    gat_avg_ms = sum(gat_ms) / len(gat_ms)
+    sel_avg_ms = sum(sel_ms) / len(sel_ms)
+
+    # what was timed is what gets checked: the outputs of the last timed step
+    timeout_status = "ok"
+    try:
+        sp.sp_score_check(pr.scorer.args)
+    except sp.SpError as e:
+        timeout_status = str(e)
+    gpu_scores = pr.scorer.scores.cpu().numpy()
+    gpu_kept = pr.sel.kept_idx.cpu().numpy()
+    gpu_cu_keep = pr.sel.cu_keep.cpu().numpy()
 
     k_bytes = w.k_bytes()
     algo_bytes = k_bytes + 4 * w.T                  # K cache read once + fp32 score per token written
     achieved = algo_bytes / (score_avg_ms * 1e-3) / 1e9
-    n_keep = int(sel.cu_keep[-1])
+    n_keep = int(gpu_cu_keep[-1])
 
     out = {
         "metric": "prompt tokens scored+selected/sec (sp_score + sp_pool_select + sp_gather)",
@@ -182,22 +296,57 @@ def main():
             "workload": f"{w.name}: B={w.B} T={w.T} L={w.L} H={w.H} H_kv={w.H_kv} d={w.d} N={w.N} "
                         f"chunk={w.chunk} keep_rate={w.keep_rate} pool_window={w.pool_window}",
             "layer_reduce": args.layer_reduce, "k_cache_bytes": k_bytes, "kept_tokens": n_keep,
-            "score_kernels": "general" if args.general else "auto",
+            "score_kernels": "general" if args.general else "auto", "flags": "SP_SCORE_EXCLUSIVE_DEVICE",
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(args.workload, args.general),
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": measured_traffic(args.workload, args.general, args.layer_reduce),
             "kernel": "sp_score (all its launches)", "avg_ms": score_avg_ms, "median_ms": score_ms[len(score_ms) // 2],
             "algorithmic_bytes": algo_bytes,
         },
-        "select_gather_ms": tail_avg_ms,
+        "select_gather_ms": sel_avg_ms + gat_avg_ms,
+        "sp_pool_select_us": sel_avg_ms * 1e3, "sp_gather_us": gat_avg_ms * 1e3,
+        "sp_gather_gbps": pr.gather_bytes() / (gat_avg_ms * 1e-3) / 1e9,
         "k_cache_gbps": k_bytes / (score_avg_ms * 1e-3) / 1e9,
-        "input_generation_s": t_gen,
+        "input_generation_s": pr.t_gen,
     }
+    try:
+        from paper_2502_02789_amd import probe
+        out["roofline"].update(probe.stream_ceiling(pr.scorer))
+    except ImportError:
+        pass
+
+    ok = timeout_status == "ok"
+    oracle_scores = None
     if not args.skip_cpu:
-        out["cpu_baseline"] = cpu_baseline(w, inp, 0 if args.layer_reduce == "max" else 1,
-                                           args.cpu_sample_layers)
+        out["cpu_baseline"], oracle_scores = cpu_baseline(w, pr.inp, 0 if args.layer_reduce == "max" else 1,
+                                                           args.cpu_sample_layers)
+    if oracle_scores is not None:
+        parity = check_against(w, pr.inp, gpu_scores, gpu_kept, gpu_cu_keep, oracle_scores, "fp64 oracle, same inputs")
+    else:
+        # the oracle did not run the whole depth: the library's plain two-pass kernels (pinned to the
+        # oracle by the parity tests) stand in, on the same device buffers
+        pr.scorer.run(pr.stream, general=True)
+        torch.cuda.synchronize()
+        parity = check_against(w, pr.inp, gpu_scores, gpu_kept, gpu_cu_keep, pr.scorer.scores.cpu().numpy(),
+                               "plain two-pass kernels of the library, same inputs")
+    parity["sp_score_check"] = timeout_status
+    out["parity"] = parity
+    ok = ok and parity["ok"]
+
+    if not args.no_also and args.workload == 3 and not args.general:
+        del pr
+        torch.cuda.empty_cache()
+        also = []
+        for number, mode in ((3, "mean" if args.layer_reduce == "max" else "max"), (2, "max"), (5, "max"), (4, "max")):
+            also.append(side_measurement(number, mode, steps=10, warmup=3))
+            ok = ok and also[-1]["ok"]
+        out["also"] = also
     print(json.dumps(out), flush=True)
+    if not ok:
+        print("bench.py: the timed run FAILED its own check (see \"parity\" / \"also\")", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

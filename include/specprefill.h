@@ -24,6 +24,9 @@
  *   - NaN/Inf in Q or K, and token ids outside [0, V), are precondition violations
  *     (undefined values, no fault for NaN/Inf; ids are NOT range-checked on device).
  *   - Calls that share a workspace must not overlap in time.
+ *   - One-time set-up per device (kernel attributes, occupancy queries, the address of the
+ *     library's static scratch) happens inside the first call made on that device, under a
+ *     lock; that first call must not be made while the stream is being captured into a graph.
  */
 #ifndef SPECPREFILL_H
 #define SPECPREFILL_H
@@ -54,6 +57,18 @@ typedef enum { SP_LAYER_MAX = 0, SP_LAYER_MEAN = 1 } sp_layer_reduce;
 
 #define SP_MAX_LAYERS 128
 #define SP_MAX_QUERIES 16
+
+/* sp_score_args.flags */
+#define SP_SCORE_EXCLUSIVE_DEVICE 1u /* The caller promises that nothing else runs on the GPU while
+                                        sp_score runs (no other stream, no other process).  Only
+                                        then may sp_score use its single-pass kernels, which read
+                                        the K cache once but exchange softmax row statistics
+                                        between workgroups that must all be resident together.
+                                        Without the flag sp_score uses kernels that never wait for
+                                        another workgroup (two passes over K or kept logits).
+                                        If the promise is broken a bounded wait can expire; the
+                                        affected scores are then NaN (see sp_score_check and
+                                        sp_pool_select), never silently wrong. */
 
 /* ---------------------------------------------------------------------------
  * sp_score: compute_attention_score + aggregate_attention_score (Algorithm 1),
@@ -109,6 +124,7 @@ typedef struct {
   int32_t page_size;         /* tokens per page: a power of two >= 8 (ignored if not paged)   */
   int32_t blocks_per_seq;    /* row length of the table, >= 1                                 */
   int64_t k_page_stride;     /* elements, multiple of 8                                       */
+  uint32_t flags;            /* SP_SCORE_* bits, 0 = none                                     */
 } sp_score_args;
 
 /* Bytes of workspace sp_score needs for these shapes (pointers are not read).
@@ -128,12 +144,20 @@ SP_API sp_status sp_score(const sp_score_args* args, void* hip_stream);
 SP_API sp_status sp_score_general(const sp_score_args* args, void* hip_stream);
 
 /* Optional post-check of the most recent sp_score call that used args->d_workspace.  The
- * single-pass kernel exchanges row statistics between workgroups that must all be resident
- * on the device at once; that holds when nothing else occupies the GPU.  Its waits are
- * bounded, and an expired wait is recorded in the workspace instead of hanging.  This call
- * SYNCHRONISES hip_stream (the only entry point that does), reads that record and returns
- * SP_ETIMEOUT if a wait expired (the scores are then invalid), SP_OK otherwise. */
+ * single-pass kernels (SP_SCORE_EXCLUSIVE_DEVICE) exchange row statistics between workgroups
+ * that must all be resident on the device at once.  Their waits are bounded: a workgroup whose
+ * wait expired writes NaN for all of its tokens' scores and records the event in the workspace
+ * instead of hanging.  This call SYNCHRONISES hip_stream (the only entry point that does), reads
+ * that record and returns SP_ETIMEOUT if a wait expired, SP_OK otherwise.  Recovery: call
+ * sp_score again without the flag (or sp_score_general). */
 SP_API sp_status sp_score_check(const sp_score_args* args, void* hip_stream);
+
+/* Upper bound on the polls one wave may spend waiting for other workgroups during one sp_score
+ * call (process-wide, applies to later calls; default 65536, about 0.1 s).  0 makes every wait
+ * give up at once, which turns every score of a single-pass call into NaN: that is how the
+ * failure path is exercised without ever making a kernel hang.  Returns the previous value;
+ * a negative argument only queries. */
+SP_API int32_t sp_set_wait_budget(int32_t polls);
 
 /* ---------------------------------------------------------------------------
  * sp_pool_select: chunk_select_from_smoothed_attention (Algorithm 1, Sec. 3.2.3).
@@ -143,6 +167,9 @@ SP_API sp_status sp_score_check(const sp_score_args* args, void* hip_stream);
  * k = clamp(ceil(keep_rate * n_chunks - 1e-9), 1, n_chunks) best chunks (keep rate =
  * ratio of chunks, Sec. 4.1), equal scores resolved to the lower chunk index; emit the
  * tokens of the kept chunks in ascending order.  Arithmetic is fp64 on the fp32 input.
+ * A NaN among the scores (sp_score writes NaN where a device-side wait expired) is reported
+ * in band: cu_keep[0] = 0, cu_keep[1..B] = -1, and no kept index is written, so that neither
+ * this call nor sp_gather after it hands on a keep set made from invalid scores.
  * --------------------------------------------------------------------------- */
 typedef struct {
   int32_t B;

@@ -15,11 +15,12 @@ SP_OK = 0
 SP_EINVAL, SP_ENULL, SP_EALIGN, SP_EWORKSPACE, SP_EUNSUPPORTED, SP_ELAUNCH, SP_ETIMEOUT = -1, -2, -3, -4, -5, -6, -7
 SP_LAYER_MAX, SP_LAYER_MEAN = 0, 1
 SP_MAX_LAYERS, SP_MAX_QUERIES = 128, 16
+SP_SCORE_EXCLUSIVE_DEVICE = 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecprefill.so")
 
 EXPORTS = (
-    "sp_score_workspace_bytes", "sp_score", "sp_score_general", "sp_score_check",
+    "sp_score_workspace_bytes", "sp_score", "sp_score_general", "sp_score_check", "sp_set_wait_budget",
     "sp_keep_upper_bound", "sp_pool_select_workspace_bytes", "sp_pool_select",
     "sp_gather", "sp_strerror", "sp_version",
 )
@@ -40,7 +41,7 @@ class ScoreArgs(C.Structure):
         ("rope_theta", C.c_float), ("d_q_pos", C.c_void_p), ("d_scores", C.c_void_p), ("d_lse", C.c_void_p),
         ("d_workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
         ("d_block_table", C.c_void_p), ("page_size", C.c_int32), ("blocks_per_seq", C.c_int32),
-        ("k_page_stride", C.c_int64),
+        ("k_page_stride", C.c_int64), ("flags", C.c_uint32),
     ]
 
 
@@ -82,6 +83,8 @@ def load_library() -> C.CDLL:
     lib.sp_score_general.argtypes = [C.POINTER(ScoreArgs), C.c_void_p]
     lib.sp_score_check.restype = C.c_int
     lib.sp_score_check.argtypes = [C.POINTER(ScoreArgs), C.c_void_p]
+    lib.sp_set_wait_budget.restype = C.c_int32
+    lib.sp_set_wait_budget.argtypes = [C.c_int32]
     lib.sp_keep_upper_bound.restype = C.c_int64
     lib.sp_keep_upper_bound.argtypes = [C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.c_double]
     lib.sp_pool_select_workspace_bytes.restype = C.c_size_t
@@ -128,7 +131,7 @@ def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, sca
                     layer_reduce: int = SP_LAYER_MAX, n_valid=None, lse=None, workspace=None,
                     k_token_stride: Optional[int] = None, k_head_stride: Optional[int] = None,
                     T: Optional[int] = None, rope_theta: float = 0.0, q_pos=None,
-                    block_table=None, page_size: int = 0) -> ScoreArgs:
+                    block_table=None, page_size: int = 0, flags: int = 0) -> ScoreArgs:
     """q: bf16 [L,B,N,H,d]; k_layers: L bf16 tensors [T,H_kv,d] (any token/head strides), or, with
     block_table (int32 [B, blocks_per_seq]), L page pools [pages, page_size, H_kv, d] (then T must be given)."""
     L, B, N, H, d = q.shape
@@ -162,6 +165,7 @@ def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, sca
     a.d_lse = _ptr(lse)
     a.d_workspace = _ptr(workspace)
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    a.flags = int(flags)
     return a
 
 
@@ -176,6 +180,11 @@ def sp_score(args: ScoreArgs, stream=None) -> None:
 def sp_score_check(args: ScoreArgs, stream=None) -> None:
     """Synchronises the stream; raises SpError(SP_ETIMEOUT) if a device-side wait expired."""
     _check("sp_score_check", load_library().sp_score_check(C.byref(args), _stream_handle(stream)))
+
+
+def sp_set_wait_budget(polls: int) -> int:
+    """Sets the bound on polls per wave of the single-pass kernels' waits; returns the previous one."""
+    return int(load_library().sp_set_wait_budget(int(polls)))
 
 
 def sp_score_general(args: ScoreArgs, stream=None) -> None:

@@ -1,21 +1,24 @@
-"""Builds libspecprefill.so (gfx950 only) in-tree with hipcc."""
+"""Builds libspecprefill.so (gfx950 only) in-tree with hipcc.
+
+Every translation unit under csrc/ is compiled on its own (in parallel) into _build/, then the
+objects are linked into the shared library next to this file."""
 from __future__ import annotations
 
 import glob
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
+OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libspecprefill.so")
 
-HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+COMMON_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-fvisibility=hidden",
-    # no NaN canonicalisation around fmax (NaN inputs are a documented precondition violation)
-    "-fno-honor-nans",
     # packed fp32 VALU forms are kept off on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # the kernel-argument struct is read through a by-value copy; without this the copy stays in
@@ -23,15 +26,16 @@ HIPCC_FLAGS = [
     "-mllvm", "-instcombine-max-copied-from-constant-users=1000000",
     "-Wall", "-Wno-unused-function",
 ]
+# no NaN canonicalisation around fmax in DEVICE code only (NaN inputs are a documented
+# precondition violation there); the host-side argument checks must still see NaNs
+DEVICE_ONLY_FLAGS = ["-Xarch_device", "-fno-honor-nans"]
 
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build_library(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, *sources(), "-o", LIB_PATH]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -39,10 +43,36 @@ def build_library(verbose: bool = False) -> str:
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
-        print(out)
-    return LIB_PATH
+        print(out, flush=True)
+
+
+def _headers_mtime():
+    hdrs = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h")) + [__file__]
+    return max(os.path.getmtime(h) for h in hdrs)
+
+
+def build_library(verbose: bool = False, extra_flags=(), lib_path: str = LIB_PATH, incremental: bool = False) -> str:
+    """incremental=True skips translation units whose object is newer than the source and every
+    header (a developer convenience; the default recompiles everything)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    tag = os.path.splitext(os.path.basename(lib_path))[0]
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    jobs, objs = [], []
+    newest_header = _headers_mtime()
+    for src in sources():
+        obj = os.path.join(OBJ_DIR, f"{tag}.{os.path.splitext(os.path.basename(src))[0]}.o")
+        objs.append(obj)
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+            continue
+        jobs.append((obj, [hipcc, *COMMON_FLAGS, *DEVICE_ONLY_FLAGS, *extra_flags, *inc, "-c", src, "-o", obj]))
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        list(pool.map(lambda j: _run(j[1], verbose), jobs))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden", *objs, "-o", lib_path],
+         verbose)
+    return lib_path
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose=True, incremental="--incremental" in sys.argv[1:]))
     sys.exit(0)

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include "specprefill.h"
 
@@ -14,6 +15,27 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// finite (neither NaN nor infinite), decided on the bit pattern so that no floating-point
+// compile option can fold the test away
+inline bool finite_f32(float x) {
+  uint32_t u;
+  memcpy(&u, &x, sizeof(u));
+  return (u & 0x7f800000u) != 0x7f800000u;
+}
+inline bool finite_f64(double x) {
+  uint64_t u;
+  memcpy(&u, &x, sizeof(u));
+  return (u & 0x7ff0000000000000ull) != 0x7ff0000000000000ull;
+}
+
+// Index of the current device, clamped into [0, kMaxDevices) (per-device set-up is cached by it).
+constexpr int kMaxDevices = 64;
+inline int current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = 0; }
+  return dev < 0 ? 0 : (dev >= kMaxDevices ? kMaxDevices - 1 : dev);
+}
 
 inline sp_status launch_status() { return hipGetLastError() == hipSuccess ? SP_OK : SP_ELAUNCH; }
 

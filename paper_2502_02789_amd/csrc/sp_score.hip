@@ -265,7 +265,12 @@ static bool shape_ok(const sp_score_args* a) {
 
 static int general_max_tiles(const sp_score_args* a) { return (int)(a->T / kTileKeys) + a->B; }
 
-size_t general_workspace_bytes(const sp_score_args* a) {
+// the single-pass kernels are taken only on the caller's promise of an otherwise idle device
+bool single_pass_wanted(const sp_score_args* a) {
+  return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && stream_supported(a);
+}
+
+size_t general_workspace_bytes(const sp_score_args* a, bool with_tiled) {
   size_t bytes = align_up(sizeof(int32_t) * ((size_t)a->B + 1), 256);
   bytes += align_up(sizeof(float) * (size_t)a->L * a->B * a->N * a->H, 256);
   bytes += align_up(sizeof(float2) * (size_t)a->L * a->N * a->H * general_max_tiles(a), 256);
@@ -273,7 +278,7 @@ size_t general_workspace_bytes(const sp_score_args* a) {
     bytes += align_up(sizeof(float2) * (size_t)a->T * (a->d / 2), 256);
     bytes += align_up(sizeof(uint16_t) * (size_t)a->L * a->B * a->N * a->H * a->d, 256);
   }
-  bytes += tiled_extra_workspace_bytes(a);
+  if (with_tiled) bytes += tiled_extra_workspace_bytes(a);
   return bytes;
 }
 
@@ -283,7 +288,7 @@ void launch_lse_combine(const ScoreDev& p, hipStream_t stream) {
 
 // these paths have no bounded waits: leave "no wait expired" where sp_score_check looks
 static void clear_stream_status(const sp_score_args* a, hipStream_t stream) {
-  const size_t status_off = stream_supported(a) ? stream_status_offset(a) : 0;
+  const size_t status_off = single_pass_wanted(a) ? stream_status_offset(a) : 0;
   if (status_off)
     hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, stream,
                        reinterpret_cast<uint32_t*>(static_cast<char*>(a->d_workspace) + status_off));
@@ -366,8 +371,11 @@ void fill_score_dev(const sp_score_args* a, ScoreDev* p) {
 
 extern "C" size_t sp_score_workspace_bytes(const sp_score_args* a) {
   if (!a || !sp::shape_ok(a)) return 0;
-  size_t general = sp::general_workspace_bytes(a);
-  size_t stream = sp::stream_workspace_bytes(a);
+  // a shape that goes to the single-pass kernel never runs the tiled kernels on this workspace
+  // (sp_score_general uses the plain kernels), so their kept-logits buffer is not asked for
+  const bool single = sp::single_pass_wanted(a);
+  const size_t general = sp::general_workspace_bytes(a, /*with_tiled=*/!single);
+  const size_t stream = single ? sp::stream_workspace_bytes(a) : 0;
   return general > stream ? general : stream;
 }
 
@@ -377,10 +385,11 @@ static sp_status check_score_args(const sp_score_args* a) {
   if (!a->d_q || !a->k_layers || !a->d_cu_seqlens || !a->d_scores) return SP_ENULL;
   for (int l = 0; l < a->L; ++l)
     if (!a->k_layers[l]) return SP_ENULL;
-  if (!(a->rope_theta >= 0.f)) return SP_EINVAL;
+  if (!sp::finite_f32(a->rope_theta) || a->rope_theta < 0.f) return SP_EINVAL;
   if (a->rope_theta == 0.f && a->d_q_pos != nullptr) return SP_EINVAL;
   if (a->rope_theta > 0.f && a->d_q_pos == nullptr) return SP_ENULL;
-  if (!(a->scale == a->scale) || a->scale <= 0.f) return SP_EINVAL;
+  if (!sp::finite_f32(a->scale) || a->scale <= 0.f) return SP_EINVAL;
+  if (a->flags & ~(uint32_t)SP_SCORE_EXCLUSIVE_DEVICE) return SP_EINVAL;
   if (a->k_token_stride < 0 || a->k_head_stride < 0) return SP_EINVAL;
   if (a->d_block_table) {
     if (a->page_size < 8 || (a->page_size & (a->page_size - 1)) != 0 || a->blocks_per_seq < 1) return SP_EINVAL;
@@ -399,7 +408,7 @@ extern "C" sp_status sp_score(const sp_score_args* a, void* hip_stream) {
   const sp_status st = check_score_args(a);
   if (st != SP_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (sp::stream_supported(a)) return sp::stream_score(a, stream);
+  if (sp::single_pass_wanted(a)) return sp::stream_score(a, stream);
   return sp::general_score(a, stream, /*allow_mfma=*/true);
 }
 
@@ -408,7 +417,7 @@ extern "C" sp_status sp_score_check(const sp_score_args* a, void* hip_stream) {
   if (st != SP_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (hipStreamSynchronize(stream) != hipSuccess) return SP_ELAUNCH;
-  const size_t off = sp::stream_supported(a) ? sp::stream_status_offset(a) : 0;
+  const size_t off = sp::single_pass_wanted(a) ? sp::stream_status_offset(a) : 0;
   if (off == 0) return SP_OK;
   uint32_t word = 0;
   if (hipMemcpy(&word, static_cast<const char*>(a->d_workspace) + off, sizeof(word), hipMemcpyDeviceToHost) !=

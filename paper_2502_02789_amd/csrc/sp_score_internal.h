@@ -31,7 +31,8 @@ struct ScoreDev {
 void fill_score_dev(const sp_score_args* a, ScoreDev* p);
 
 // general two-pass kernels (sp_score.hip)
-size_t general_workspace_bytes(const sp_score_args* a);
+size_t general_workspace_bytes(const sp_score_args* a, bool with_tiled);
+bool single_pass_wanted(const sp_score_args* a);
 // allow_mfma: hand the two passes to the tiled MFMA kernels when the shape fits them
 sp_status general_score(const sp_score_args* a, hipStream_t stream, bool allow_mfma);
 void launch_lse_combine(const ScoreDev& p, hipStream_t stream);

@@ -48,6 +48,9 @@
 // duties, so waiting waves cannot starve each other.  The grid is one workgroup per CU, each
 // needing more than half of a CU's LDS, so all of them are resident together on an otherwise
 // idle device; that residency is what every wait relies on.
+#include <atomic>
+#include <mutex>
+
 #include "sp_score_internal.h"
 #include "sp_lds.h"
 
@@ -61,11 +64,12 @@ constexpr uint32_t kEmpty32 = ~0u;
 constexpr uint32_t kPending32 = ~0u - 1;  // in an LDS landing zone: the sample has not arrived yet
 constexpr int kCtlBytes = 128;         // arrival counters and the workgroup's duty words
 constexpr int kStageBytes = kMaxWG * 16;  // landing zone of a reducer's sample: 4 rows x 4 bytes per workgroup
-constexpr int kSpinBudget = 1 << 16;  // polls per wave over the whole call before giving up (~0.1 s)
+constexpr int kDefaultSpinBudget = 1 << 16;  // polls per wave over the whole call before giving up (~0.1 s)
 constexpr int kDepSlotBytes = 8 * 32 * 8;  // one slab's deposits: 8 waves x 32 rows x (max, sum)
 
 struct StreamDev {
   int M, L, N, H, G, lgG, S, lgS, slabs_per_layer, lgSPL, n_slabs, KPW, lgKPW, nwg, wpr, layer_reduce;  // S, slabs_per_layer: powers of two
+  int spin_budget;  // polls a wave may spend waiting for other workgroups over the whole call
   float c;  // scale * log2(e): logits are handled in the base-2 domain
   int64_t ts, hs;
   const uint16_t* q;
@@ -124,7 +128,8 @@ struct Streamer {
   int wave, lane, half, col, wg;
   int kvh_local, kbg;
   int keys_wg;           // valid keys owned by this workgroup
-  int budget;
+  int budget;            // polls left; a wait that finds it used up gives up and sets `expired`
+  bool expired;
   int issued;            // vector-memory instructions issued so far by this wave (never over-counted)
   int seq0, seq1;        // value of `issued` right after the loads of the tile in ring slot 0 / 1
   int duty_k;            // reducer rotation: this workgroup reduces quad duty_k of the slab if duty_k < quads
@@ -161,7 +166,8 @@ struct Streamer {
     stage_lds = cnt_lds + kCtlBytes + kWaves * 256;
     smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + kCtlBytes + kWaves * 256 + kStageBytes);
     keys_wg = max(0, min(p.KPW, p.M - wg * p.KPW));
-    budget = kSpinBudget;
+    budget = p.spin_budget;
+    expired = false;
     issued = 0;
     seq0 = seq1 = 0;
     duty_k = wg;
@@ -189,6 +195,13 @@ struct Streamer {
   }
   __device__ __forceinline__ static uint32_t lds_addr_of(const void* generic) {
     return (uint32_t)reinterpret_cast<uintptr_t>(generic);
+  }
+
+  // One more round of a bounded wait?  False (and the wave remembers it) once the budget is gone.
+  __device__ __forceinline__ bool may_poll() {
+    if (budget > 0) { --budget; return true; }
+    expired = true;
+    return false;
   }
 
   __device__ __forceinline__ int layer_of(int slab) const { return slab >> p.lgSPL; }
@@ -439,10 +452,9 @@ struct Streamer {
   __device__ __forceinline__ void advance_duty(int slab, bool post) {
     const int quads = p.S * 8;
     if (post && duty_k < quads) {
-      while ((int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 32)) >= 0 && budget > 0) {
+      while ((int)__builtin_amdgcn_readfirstlane(lds_peek(cnt_lds + 32)) >= 0 && may_poll()) {
         service_reduce();  // the previous duty is still open: cannot happen unless the exchange is badly late
         __builtin_amdgcn_s_sleep(4);
-        --budget;
       }
       if (lane == 0) {
         lds_poke32(cnt_lds + 48, 0);                               // nothing sampled yet
@@ -595,11 +607,10 @@ struct Streamer {
     asm volatile("" : "+v"(c));
     const uint32_t addr = lse_lds + (slab & 1) * 128 + c * 4;
     uint32_t bits = lds_peek(addr);
-    while (__any(bits == kPending32 || bits == kEmpty32) && budget > 0) {
+    while (__any(bits == kPending32 || bits == kEmpty32) && may_poll()) {
       if (!__any(bits == kPending32)) request_lse(slab);
       service_reduce();
       __builtin_amdgcn_s_sleep(4);
-      --budget;
       bits = lds_peek(addr);
     }
     return __uint_as_float(bits);
@@ -669,10 +680,9 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
     if (MEAN && ((done + 1) & (p.slabs_per_layer - 1)) == 0 && done + 1 < p.n_slabs) {
       // a wave parked at a barrier serves nobody: finish the reducer duty first (it only needs
       // publications of slabs every wave of the grid has already left behind)
-      while (st.duty_open() && st.budget > 0) {
+      while (st.duty_open() && st.may_poll()) {
         st.service_reduce();
         __builtin_amdgcn_s_sleep(4);
-        --st.budget;
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
       __syncthreads();
@@ -765,13 +775,14 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
     }
     close_layer(s);
   }
-  while (st.duty_open() && st.budget > 0) {  // nobody gets its log-sum-exps before this duty is done
+  while (st.duty_open() && st.may_poll()) {  // nobody gets its log-sum-exps before this duty is done
     st.service_reduce();
     __builtin_amdgcn_s_sleep(4);
-    --st.budget;
   }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
-  __syncthreads();
+  // A wait of any wave of this workgroup gave up: its tokens' scores may rest on statistics that
+  // never arrived.  They are written as NaN so that no consumer can take them for scores.
+  const bool gave_up = __syncthreads_or(st.expired ? 1 : 0) != 0;
 
   int nv = p.n_valid ? p.n_valid[0] : p.N;
   nv = max(1, min(nv, p.N));
@@ -790,9 +801,9 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
       sum += MEAN ? v : fast_exp2(v);
     }
     const float denom = MEAN ? (float)nv * (float)p.L : (float)nv;
-    p.scores[(int64_t)blockIdx.x * p.KPW + key] = sum / denom;
+    p.scores[(int64_t)blockIdx.x * p.KPW + key] = gave_up ? __uint_as_float(0x7fc00000u) : sum / denom;
   }
-  if (st.budget <= 0 && st.lane == 0) atomicOr(p.status, 1u);
+  if (gave_up && threadIdx.x == 0) atomicOr(p.status, 1u);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -804,18 +815,23 @@ struct StreamPlan {
   size_t rows, partial_bytes, lse_bytes, smem_bytes;
 };
 
+// compute units of the current device; cached per device (0 = not asked yet)
 static int device_cu_count() {
-  static int cached = -1;
-  if (cached >= 0) return cached;
+  static std::atomic<int> cached[kMaxDevices];
+  const int slot = current_device();
+  const int have = cached[slot].load(std::memory_order_relaxed);
+  if (have > 0) return have;
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
     (void)hipGetLastError();
     return kMaxWG;  // no device visible (sizing queries on a CPU-only host): assume the full chip
   }
-  cached = cus;
-  return cached;
+  cached[slot].store(cus, std::memory_order_relaxed);
+  return cus;
 }
+
+static std::atomic<int> g_spin_budget{kDefaultSpinBudget};
 
 #ifndef SP_STREAM_TPW_PREF
 #define SP_STREAM_TPW_PREF 2  // preferred key tiles per wave per slab (smaller = longer exchange window)
@@ -877,17 +893,23 @@ size_t stream_status_offset(const sp_score_args* a) {
 template <int D, int TPW, bool MEAN, bool PAGED = false>
 static sp_status launch_stream(const StreamDev& dev, const StreamPlan& pl, hipStream_t stream) {
   auto kernel = stream_score_kernel<D, TPW, MEAN, PAGED>;
-  // once per kernel: allow the large dynamic LDS size and make sure one workgroup fits on a CU
-  static int prepared_for = -1;
-  if (prepared_for < (int)pl.smem_bytes) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            160 * 1024) != hipSuccess)
-      return SP_ELAUNCH;
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kernel), kThreads,
-                                                     pl.smem_bytes) != hipSuccess || per_cu < 1)
-      return SP_ELAUNCH;
-    prepared_for = 160 * 1024;
+  // once per kernel and device, under a lock: allow the large dynamic LDS size and make sure a
+  // workgroup of the largest size fits on a compute unit (the grid is one workgroup per unit)
+  static std::mutex mu;
+  static bool prepared[kMaxDevices] = {};
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    const int slot = current_device();
+    if (!prepared[slot]) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              160 * 1024) != hipSuccess)
+        return SP_ELAUNCH;
+      int per_cu = 0;
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kernel), kThreads,
+                                                       160 * 1024) != hipSuccess || per_cu < 1)
+        return SP_ELAUNCH;
+      prepared[slot] = true;
+    }
   }
   hipLaunchKernelGGL(kernel, dim3(pl.nwg), dim3(kThreads), pl.smem_bytes, stream, dev);
   return launch_status();
@@ -905,6 +927,7 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   dev.lgKPW = 0;
   while ((1 << dev.lgKPW) < pl.KPW) ++dev.lgKPW;
   dev.wpr = pl.wpr; dev.layer_reduce = a->layer_reduce;
+  dev.spin_budget = g_spin_budget.load(std::memory_order_relaxed);
   dev.c = a->scale * 1.4426950408889634f;
   dev.ts = a->k_token_stride; dev.hs = a->k_head_stride;
   dev.q = static_cast<const uint16_t*>(a->d_q);
@@ -944,3 +967,8 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
 }
 
 }  // namespace sp
+
+extern "C" int32_t sp_set_wait_budget(int32_t polls) {
+  if (polls < 0) return sp::g_spin_budget.load(std::memory_order_relaxed);
+  return sp::g_spin_budget.exchange(polls, std::memory_order_relaxed);
+}

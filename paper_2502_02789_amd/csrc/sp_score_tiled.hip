@@ -22,6 +22,8 @@
 //           several workgroups per CU to balance) are merged and averaged over the queries.
 //
 // No wave waits for another one: there is no cross-workgroup exchange in this path.
+#include <mutex>
+
 #include "sp_score_internal.h"
 #include "sp_lds.h"
 
@@ -652,12 +654,17 @@ template <int D, int PASS, bool MEAN>
 static sp_status launch_tiled(const TiledDev& dev, hipStream_t stream) {
   auto kernel = tiled_score_kernel<D, PASS, MEAN>;
   const size_t smem = TileWalker<D>::smem_bytes();
-  static bool prepared = false;
-  if (!prepared) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)smem) != hipSuccess)
-      return SP_ELAUNCH;
-    prepared = true;
+  static std::mutex mu;  // once per kernel and device
+  static bool prepared[kMaxDevices] = {};
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    const int slot = current_device();
+    if (!prepared[slot]) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)smem) != hipSuccess)
+        return SP_ELAUNCH;
+      prepared[slot] = true;
+    }
   }
   const dim3 grid((dev.max_tiles + kTiledWaves - 1) / kTiledWaves, dev.n_groups);
   hipLaunchKernelGGL(kernel, grid, dim3(kTiledThreads), smem, stream, dev);

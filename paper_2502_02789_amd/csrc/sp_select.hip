@@ -96,6 +96,12 @@ __global__ __launch_bounds__(256) void pool_chunk_kernel(const SelDev p) {
   }
 }
 
+// NaN, decided on the bit pattern (device code is compiled on the assumption that there are none)
+__device__ __forceinline__ bool is_nan_bits(double v) {
+  const uint64_t u = (uint64_t)__double_as_longlong(v);
+  return (u & 0x7ff0000000000000ull) == 0x7ff0000000000000ull && (u & 0x000fffffffffffffull) != 0;
+}
+
 // monotone map double -> uint64 (larger value <-> larger key)
 __device__ __forceinline__ uint64_t order_key(double v) {
   const uint64_t u = (uint64_t)__double_as_longlong(v);
@@ -162,6 +168,18 @@ __global__ __launch_bounds__(1024) void select_kernel(const SelDev p) {
   const double kd = ceil(scaled - 1e-9);
   const int k = (int)fmin((double)n, fmax(1.0, kd));
   const double* cs = p.cs + c0;
+
+  // invalid scores (NaN: the scorer's mark for "a device-side wait expired") are reported in band:
+  // a negative count here turns every cu_keep entry after the first into -1
+  {
+    int bad = 0;
+    for (int j = t; j < n; j += 1024) bad |= is_nan_bits(cs[j]) ? 1 : 0;
+    if (__syncthreads_or(bad)) {
+      for (int j = t; j < n; j += 1024) p.chunk_off[c0 + j] = -1;
+      if (t == 0) p.seq_keep[b] = -1;
+      return;
+    }
+  }
 
   // radix select: after the loop `prefix` is the key of the k-th largest chunk score and
   // `need` is how many chunks with exactly that score are still to be taken
@@ -232,8 +250,16 @@ __global__ __launch_bounds__(1024) void select_emit_single_kernel(const SelDev p
   const double scaled = p.keep_rate * (double)n;
   const double kd = ceil(scaled - 1e-9);
   const int k = (int)fmin((double)n, fmax(1.0, kd));
-  for (int j = t; j < n; j += 1024) keys[j] = order_key(p.cs[j]);
-  __syncthreads();
+  int bad = 0;
+  for (int j = t; j < n; j += 1024) {
+    const double v = p.cs[j];
+    bad |= is_nan_bits(v) ? 1 : 0;
+    keys[j] = order_key(v);
+  }
+  if (__syncthreads_or(bad)) {  // invalid scores: reported in band, nothing kept
+    if (t == 0) p.cu_keep[1] = -1;
+    return;
+  }
 
   uint64_t prefix = 0;
   int need = k;
@@ -285,13 +311,18 @@ __global__ __launch_bounds__(1024) void select_emit_single_kernel(const SelDev p
 }
 
 __global__ __launch_bounds__(1024) void cu_keep_kernel(const SelDev p) {
-  block_prefix_table(p.B, [&](int b) { return p.seq_keep[b]; }, p.cu_keep);
+  int bad = 0;
+  for (int b = threadIdx.x; b < p.B; b += 1024) bad |= p.seq_keep[b] < 0 ? 1 : 0;
+  bad = __syncthreads_or(bad);
+  block_prefix_table(p.B, [&](int b) { return max(p.seq_keep[b], 0); }, p.cu_keep);
+  if (bad)  // some sequence had invalid scores: no keep set is handed on
+    for (int b = 1 + threadIdx.x; b <= p.B; b += 1024) p.cu_keep[b] = -1;
 }
 
 // one thread per prompt token: if its chunk is kept, write its flat index to its slot
 __global__ __launch_bounds__(256) void emit_kernel(const SelDev p) {
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= p.T) return;
+  if (i >= p.T || p.cu_keep[p.B] < 0) return;
   const int b = upper_segment(p.cu, p.B, i);
   const int in_seq = i - p.cu[b];
   const int j = in_seq / p.chunk;
@@ -304,7 +335,7 @@ __global__ __launch_bounds__(256) void emit_kernel(const SelDev p) {
 static bool select_shape_ok(const sp_pool_select_args* a) {
   if (a->B < 1 || a->T < 0 || a->T >= (int64_t)INT32_MAX) return false;
   if (a->chunk < 1 || a->pool_window < 1 || (a->pool_window & 1) == 0) return false;
-  if (!(a->keep_rate > 0.0) || !(a->keep_rate <= 1.0)) return false;
+  if (!finite_f64(a->keep_rate) || a->keep_rate <= 0.0 || a->keep_rate > 1.0) return false;
   return true;
 }
 static size_t select_max_chunks(const sp_pool_select_args* a) { return (size_t)(a->T / a->chunk) + a->B; }
@@ -312,7 +343,8 @@ static size_t select_max_chunks(const sp_pool_select_args* a) { return (size_t)(
 }  // namespace sp
 
 extern "C" int64_t sp_keep_upper_bound(int32_t B, const int32_t* h_seqlens, int32_t chunk, double keep_rate) {
-  if (B < 0 || (B > 0 && !h_seqlens) || chunk < 1 || !(keep_rate > 0.0) || !(keep_rate <= 1.0)) return -1;
+  if (B < 0 || (B > 0 && !h_seqlens) || chunk < 1 || !sp::finite_f64(keep_rate) || keep_rate <= 0.0 || keep_rate > 1.0)
+    return -1;
   int64_t total = 0;
   for (int b = 0; b < B; ++b) {
     const int64_t M = h_seqlens[b];

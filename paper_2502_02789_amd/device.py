@@ -38,7 +38,10 @@ class Scorer:
                  H_kv: int, scale: float, layer_reduce: int = sp.SP_LAYER_MAX,
                  n_valid: Optional[torch.Tensor] = None, want_lse: bool = False,
                  rope_theta: float = 0.0, q_pos: Optional[torch.Tensor] = None,
-                 block_table: Optional[torch.Tensor] = None, page_size: int = 0, total_tokens: Optional[int] = None):
+                 block_table: Optional[torch.Tensor] = None, page_size: int = 0, total_tokens: Optional[int] = None,
+                 exclusive_device: bool = True):
+        """exclusive_device: promise that nothing else runs on the GPU during the call
+        (SP_SCORE_EXCLUSIVE_DEVICE), which lets sp_score take its single-pass kernels."""
         L, B, N, H, d = q.shape
         T = int(k_layers[0].shape[0]) if block_table is None else int(total_tokens)
         self.block_table = block_table
@@ -46,10 +49,11 @@ class Scorer:
         self.q, self.k_layers, self.cu, self.n_valid, self.q_pos = q, list(k_layers), cu_seqlens, n_valid, q_pos
         self.scores = torch.empty(T, dtype=torch.float32, device=dev)
         self.lse = torch.empty((L, B, N, H), dtype=torch.float32, device=dev) if want_lse else None
+        flags = sp.SP_SCORE_EXCLUSIVE_DEVICE if exclusive_device else 0
         probe = sp.make_score_args(q, self.k_layers, cu_seqlens, self.scores, H_kv=H_kv, scale=scale,
                                    layer_reduce=layer_reduce, n_valid=n_valid, lse=self.lse,
                                    rope_theta=rope_theta, q_pos=q_pos, T=T, block_table=block_table,
-                                   page_size=page_size)
+                                   page_size=page_size, flags=flags)
         need = sp.sp_score_workspace_bytes(probe)
         if need == 0:
             raise sp.SpError("sp_score_workspace_bytes", sp.SP_EINVAL)
@@ -57,7 +61,7 @@ class Scorer:
         self.args = sp.make_score_args(q, self.k_layers, cu_seqlens, self.scores, H_kv=H_kv, scale=scale,
                                        layer_reduce=layer_reduce, n_valid=n_valid, lse=self.lse,
                                        workspace=self.workspace, rope_theta=rope_theta, q_pos=q_pos, T=T,
-                                       block_table=block_table, page_size=page_size)
+                                       block_table=block_table, page_size=page_size, flags=flags)
 
     def run(self, stream=None, general: bool = False) -> torch.Tensor:
         (sp.sp_score_general if general else sp.sp_score)(self.args, stream)

@@ -53,6 +53,45 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.sp_score(C.byref(a), None) == sp.SP_ENULL
 
 
+def _fake_score_args():
+    """A fully populated sp_score_args whose device pointers are made-up, aligned addresses: good
+    enough for every host-side check (which come before any launch), never dereferenced."""
+    a = sp.ScoreArgs()
+    a.B, a.N, a.L, a.H, a.H_kv, a.d, a.T = 1, 8, 2, 32, 8, 128, 4096
+    arr = (C.c_void_p * 2)(0x7000_0000_0000, 0x7000_1000_0000)
+    a._keepalive = arr
+    a.k_layers = C.cast(arr, C.POINTER(C.c_void_p))
+    a.d_q, a.d_cu_seqlens, a.d_scores = 0x7000_2000_0000, 0x7000_2100_0000, 0x7000_2200_0000
+    a.k_token_stride, a.k_head_stride = 1024, 128
+    a.scale, a.layer_reduce = 0.088, sp.SP_LAYER_MAX
+    return a
+
+
+def test_nan_arguments_are_refused_before_anything_is_launched():
+    lib = sp.load_library()
+    nan = float("nan")
+    a = _fake_score_args()
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EWORKSPACE          # everything else is acceptable
+    a.scale = nan
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EINVAL
+    assert lib.sp_score_general(C.byref(a), None) == sp.SP_EINVAL
+    a = _fake_score_args()
+    a.rope_theta = nan
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EINVAL
+    a = _fake_score_args()
+    a.scale = float("inf")
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EINVAL
+    s = sp.PoolSelectArgs()
+    s.B, s.T, s.chunk, s.pool_window, s.keep_rate, s.kept_capacity = 1, 4096, 32, 13, 0.1, 4096
+    s.d_cu_seqlens, s.d_scores, s.d_kept_idx, s.d_cu_keep = 0x7000_0000_0000, 0x7000_1000_0000, 0x7000_2000_0000, 0x7000_3000_0000
+    assert lib.sp_pool_select(C.byref(s), None) == sp.SP_EWORKSPACE
+    for bad in (nan, 0.0, -0.5, 1.5, float("inf")):
+        s.keep_rate = bad
+        assert lib.sp_pool_select(C.byref(s), None) == sp.SP_EINVAL, bad
+        assert lib.sp_pool_select_workspace_bytes(C.byref(s)) == 0, bad
+    assert sp.sp_keep_upper_bound([10], 4, nan) == -1
+
+
 def test_keep_upper_bound_follows_the_chunk_ratio_rule():
     assert sp.sp_keep_upper_bound([1024], 32, 0.25) == 256
     assert sp.sp_keep_upper_bound([8192], 32, 0.1) == 26 * 32

@@ -60,6 +60,29 @@ def test_valid_query_counts(general):
         _check(w, inp, mode, general, n_valid=np.array([3, 1], dtype=np.int32))
 
 
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("n_valid", [1, 5])
+def test_valid_query_count_on_one_long_prompt(n_valid, mode, paged):
+    """One prompt, eight KV heads, eight look-ahead rows of which only the first n_valid count
+    (Sec. 3.3: look-ahead tokens after an end-of-sequence are not valid): the shape the single-pass
+    kernels take, contiguous and behind a block table, against the oracle."""
+    w = synth.scaled(synth.workload(3), seqlens=(6000 + 13,), L=3)
+    inp = synth.make_qk(w)
+    scale = 1.0 / math.sqrt(w.d)
+    nv = np.array([n_valid], dtype=np.int32)
+    want, want_lse = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, mode, nv)
+    full, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, mode)
+    assert np.abs(want - full).max() > 1e-3 * np.abs(full).max()      # the rows left out do matter here
+    if paged:
+        pools, table = hp.paged_copy(inp["k"], inp["cu_seqlens"], 16, seed=n_valid)
+        got, lse = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], w.H_kv, scale, mode, n_valid=nv)
+    else:
+        got, lse = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, scale, mode, n_valid=nv)
+    hp.assert_scores_close(got, want, f"n_valid={n_valid} mode={mode} paged={paged}")
+    np.testing.assert_allclose(lse, want_lse, rtol=0, atol=2e-4)
+
+
 @pytest.mark.parametrize("shape", [dict(H=8, H_kv=8), dict(H=16, H_kv=2), dict(H=6, H_kv=3, N=16), dict(H=4, H_kv=1, N=3)])
 def test_other_head_groupings(shape):
     w = synth.scaled(synth.workload(2), seqlens=(517,), L=2, **shape)
@@ -116,6 +139,8 @@ def test_argument_errors_launch_nothing():
     assert status(N=17) == sp.SP_EINVAL
     assert status(H_kv=3) == sp.SP_EINVAL
     assert status(layer_reduce=2) == sp.SP_EINVAL
+    assert status(flags=2) == sp.SP_EINVAL                        # an unknown flag bit
+    assert status(scale=float("nan")) == sp.SP_EINVAL
     assert status(d_q=None) == sp.SP_ENULL
     assert status(d_scores=None) == sp.SP_ENULL
     assert status(k_token_stride=w.H_kv * w.d + 4) == sp.SP_EALIGN
@@ -161,6 +186,62 @@ def test_deep_prompt_three_calls_on_one_workspace(mode):
         if first is None:
             first = got
         assert (got.view(np.uint32) == first.view(np.uint32)).all()
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_one_long_prompt_without_the_exclusive_device_promise(mode):
+    """Without SP_SCORE_EXCLUSIVE_DEVICE the same shape is scored by kernels that never wait for
+    another workgroup; same result (to tolerance) as the oracle and as the single-pass kernel."""
+    w = synth.scaled(synth.workload(3), seqlens=(5003,), L=3)
+    inp = synth.make_qk(w)
+    scale = 1.0 / math.sqrt(w.d)
+    want, want_lse = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, mode)
+    got, lse = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, scale, mode, exclusive_device=False)
+    hp.assert_scores_close(got, want, f"shared device, mode={mode}")
+    np.testing.assert_allclose(lse, want_lse, rtol=0, atol=2e-4)
+
+
+def test_expired_wait_is_impossible_to_miss():
+    """The single-pass kernel's waits for other workgroups are bounded.  With the bound set to
+    zero from the host every wait gives up at once (all kernels still run to their end): the scores
+    must then be NaN, sp_score_check must report SP_ETIMEOUT, and selection and gather must hand on
+    no keep set.  With the bound restored the same objects give the oracle's result again."""
+    import torch
+    from paper_2502_02789_amd import binding as sp, device as dev
+    w = synth.scaled(synth.workload(3), seqlens=(4096 + 40,), L=3)
+    inp = synth.make_qk(w)
+    scale = 1.0 / math.sqrt(w.d)
+    q = dev.bf16_from_bits(inp["q"])
+    ks = [dev.bf16_from_bits(k) for k in inp["k"]]
+    cu = torch.from_numpy(inp["cu_seqlens"]).cuda()
+    s = dev.Scorer(q, ks, cu, H_kv=w.H_kv, scale=scale)
+    sel = dev.Selector(s.scores, cu, chunk=32, pool_window=13, keep_rate=0.1)
+    gat = dev.Gatherer(sel, token_ids=torch.zeros(w.T, dtype=torch.int32, device="cuda"))
+    before = sp.sp_set_wait_budget(0)
+    try:
+        assert before > 0 and sp.sp_set_wait_budget(-1) == 0
+        s.scores.fill_(1.0)
+        sel.kept_idx.fill_(-5)
+        s.run()
+        sel.run()
+        gat.kept_pos.fill_(-5)
+        gat.run()
+        with pytest.raises(sp.SpError) as e:
+            sp.sp_score_check(s.args)
+        assert e.value.status == sp.SP_ETIMEOUT
+        assert torch.isnan(s.scores).all()
+        assert sel.cu_keep.cpu().tolist() == [0, -1]
+        assert (sel.kept_idx == -5).all() and (gat.kept_pos == -5).all()
+        assert gat.decode_pos.cpu().tolist() == [w.T]
+    finally:
+        sp.sp_set_wait_budget(before)
+    s.run()
+    sel.run()
+    gat.run()
+    sp.sp_score_check(s.args)
+    want, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, orc.LAYER_MAX)
+    hp.assert_scores_close(s.scores.cpu().numpy(), want, "after the bound was restored")
+    assert int(sel.cu_keep[1]) > 0 and (gat.kept_pos[:int(sel.cu_keep[1])] >= 0).all()
 
 
 def _raw_inputs(seed, seqlens, L, H, H_kv, d, N):
@@ -314,7 +395,7 @@ def test_paged_single_prompt(page_size):
 
 def test_seeded_shape_sweep_fast_paths_agree_with_the_plain_kernels():
     """Forty seeded shapes (group sizes 1..8, ragged batches with empty and one-key sequences,
-    both head dims, contiguous and paged caches, both modes): whatever kernels sp_score picks must
+    both head dims, contiguous and paged caches, both modes, valid-row counts): whatever kernels sp_score picks must
     agree with the plain two-pass kernels, which the other tests pin to the oracle."""
     rng = np.random.default_rng(20250207)
     for case in range(40):
@@ -334,13 +415,15 @@ def test_seeded_shape_sweep_fast_paths_agree_with_the_plain_kernels():
                          salient_frac=0.02, salient_run=1)
         inp = synth.make_qk(w)
         scale = 1.0 / math.sqrt(d)
-        what = f"case {case}: lens={lens} G={G} H_kv={H_kv} N={N} d={d} L={L} mode={mode} paged={paged}"
+        nv = None if case % 4 == 3 else rng.integers(1, N + 1, size=B).astype(np.int32)   # valid look-ahead rows
+        what = f"case {case}: lens={lens} G={G} H_kv={H_kv} N={N} d={d} L={L} mode={mode} paged={paged} n_valid={nv}"
         if paged:
             pools, table = hp.paged_copy(inp["k"], inp["cu_seqlens"], int(rng.choice([8, 16, 32])), seed=case)
-            a, la = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], H_kv, scale, mode)
-            g, lg = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], H_kv, scale, mode, general=True)
+            a, la = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], H_kv, scale, mode, n_valid=nv)
+            g, lg = hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], H_kv, scale, mode, general=True,
+                                       n_valid=nv)
         else:
-            a, la = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], H_kv, scale, mode)
-            g, lg = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], H_kv, scale, mode, general=True)
+            a, la = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], H_kv, scale, mode, n_valid=nv)
+            g, lg = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], H_kv, scale, mode, general=True, n_valid=nv)
         np.testing.assert_allclose(a, g, rtol=2e-3, atol=1e-30, err_msg=what)
         np.testing.assert_allclose(la, lg, rtol=0, atol=2e-4, err_msg=what)

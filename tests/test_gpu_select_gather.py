@@ -153,3 +153,15 @@ def test_single_sequence_fast_path_equals_general_path(T, chunk, rate, ties):
     assert (a.kept_idx.cpu().numpy()[:na] == b.kept_idx.cpu().numpy()[:nb]).all()
     np.testing.assert_array_equal(a.chunk_scores.cpu().numpy()[: (T + chunk - 1) // chunk],
                                   b.chunk_scores.cpu().numpy()[: (T + chunk - 1) // chunk])
+
+
+@pytest.mark.parametrize("cu", [(0, 700), (0, 300, 300, 1000, 1700)])
+def test_nan_scores_are_reported_in_band(cu):
+    """A NaN among the scores (the scorer's mark for an expired device-side wait): cu_keep[1..B]
+    = -1 and no kept index written, on the single-sequence and on the batched path."""
+    rng = np.random.default_rng(3)
+    scores = rng.random(cu[-1]).astype(np.float32)
+    scores[cu[-1] - 5] = np.nan
+    sel = hp.gpu_pool_select(scores, np.array(cu, dtype=np.int32), 32, 5, 0.25)
+    assert sel.cu_keep.cpu().tolist() == [0] + [-1] * (len(cu) - 1)
+    assert (sel.kept_idx == -1).all()

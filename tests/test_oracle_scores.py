@@ -273,6 +273,98 @@ def test_rope_equals_complex_multiplication():
     np.testing.assert_allclose(got, want, rtol=0, atol=2.0 ** -7 * np.abs(want).max())   # bf16 output + fp32 tables
 
 
+def _round_fraction(x, mant_bits):
+    """Nearest value with `mant_bits` significant bits, ties to even, in exact rational arithmetic
+    (moderate magnitudes only: no overflow, no subnormals)."""
+    from fractions import Fraction
+    if x == 0:
+        return x
+    a = abs(x)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1                                             # now 2^e <= a < 2^(e+1)
+    unit = Fraction(2) ** (e - (mant_bits - 1))
+    q = a / unit
+    n = q.numerator // q.denominator
+    r = q - n
+    if r > Fraction(1, 2) or (r == Fraction(1, 2) and (n & 1)):
+        n += 1
+    return (n * unit) if x > 0 else -(n * unit)
+
+
+def _f32(x):
+    """Python float -> nearest fp32, as a float (struct does the rounding, not numpy)."""
+    import struct
+    return struct.unpack("<f", struct.pack("<f", x))[0]
+
+
+def test_rope_rounding_steps_against_exact_rational_arithmetic():
+    """The precision ladder of the rotation, step by step, in exact fractions: fp32 cosine and
+    sine (from libm through struct, not numpy), each product rounded to fp32, the difference / sum
+    rounded to fp32, the result rounded to bf16 -- every rounding nearest-even.  Pair t = 0 has
+    frequency 1, so the angle is the integer position itself.  An implementation that fuses the
+    multiply-add, truncates, or rounds halves up fails here (the bit patterns must be equal)."""
+    import math
+    from fractions import Fraction
+    rng = np.random.default_rng(17)
+    d, P = 4, 400
+    pos = rng.integers(1, 1 << 17, size=P)
+    x = _bits(rng.standard_normal((P, 1, d)) * np.exp2(rng.integers(-6, 7, size=(P, 1, 1))))
+    got = orc.rope_rotate_bits(x, pos, 5e5)
+    xv = _vals(x)
+    for p in range(P):
+        c = Fraction(_f32(math.cos(float(pos[p]))))
+        s = Fraction(_f32(math.sin(float(pos[p]))))
+        lo, hi = Fraction(float(xv[p, 0, 0])), Fraction(float(xv[p, 0, 2]))          # pair (0, d/2)
+        out_lo = _round_fraction(_round_fraction(lo * c, 24) - _round_fraction(hi * s, 24), 24)
+        out_hi = _round_fraction(_round_fraction(hi * c, 24) + _round_fraction(lo * s, 24), 24)
+        want = [float(_round_fraction(out_lo, 8)), float(_round_fraction(out_hi, 8))]
+        have = [float(_vals(got[p, 0, 0:1])[0]), float(_vals(got[p, 0, 2:3])[0])]
+        assert have == want, (p, int(pos[p]), have, want)
+
+
+def test_rope_bf16_rounding_is_nearest_even_on_exact_ties():
+    """With the partner element zero the rotated value is ONE fp32 product x * cos(pos), whose
+    24-bit significand follows from integer arithmetic.  Over all positive bf16 inputs in one
+    few binades and 6000 positions, pick the products whose low 16 bits are exactly one half of a
+    bf16 step (a tie: even significand must round down, odd up), and those just above a half
+    (truncation would round them down).  All three kinds occur and all must match bit for bit."""
+    import math
+    mant = np.arange(128, 256, dtype=np.int64)                                   # 8-bit bf16 significands 1.xxxxxxx
+    exps = np.array([121, 127, 130], dtype=np.int64)                             # biased exponents around 1.0
+    xb = ((exps[:, None] << 7) | (mant[None, :] - 128)).astype(np.uint16).ravel()  # positive bf16 patterns
+    x = np.zeros((len(xb), 1, 2), dtype=np.uint16)
+    x[:, 0, 0] = xb                                                              # (lo, hi) = (x, 0), d = 2
+    seen = {"down": 0, "up": 0, "above": 0}
+    for pos in range(1, 6001):
+        cf = _f32(math.cos(float(pos)))
+        cm, ce = math.frexp(abs(cf))                                             # |c| = cm * 2^ce, 0.5 <= cm < 1
+        c_sig = int(cm * (1 << 24))                                              # exact 24-bit significand
+        assert c_sig / (1 << 24) == cm
+        prod = np.tile(mant, len(exps)) * c_sig                                  # exact: 8-bit x 24-bit significands
+        # normalise to 24 bits, nearest-even: prod in [2^30, 2^32)
+        shift = np.where(prod >= (1 << 31), 8, 7)
+        rem = prod & ((1 << shift) - 1)
+        q = prod >> shift
+        halfway = 1 << (shift - 1)
+        q = q + ((rem > halfway) | ((rem == halfway) & ((q & 1) == 1)))
+        q = np.where(q == (1 << 24), 1 << 23, q)                                 # (a carry only renormalises: low bits 0)
+        low = q & 0xFFFF
+        upper_odd = ((q >> 16) & 1) == 1
+        got = orc.rope_rotate_bits(x, np.full(len(xb), pos), 5e5)[:, 0, 0]
+        # what the product rounds to in bf16, from the integer model: keep sign/exponent from an
+        # exact fp64 product rounded twice (fp64 holds 8-bit x 24-bit products exactly)
+        exact = _vals(xb) * cf
+        f32bits = exact.astype(np.float32).view(np.uint32)
+        assert ((f32bits & 0xFFFF) == low).all()                                 # the integer model and the fp32 cast agree
+        for name, sel, bump in (("down", (low == 0x8000) & ~upper_odd, 0), ("up", (low == 0x8000) & upper_odd, 1),
+                                ("above", (low > 0x8000) & (low < 0x8100), 1)):
+            want = ((f32bits[sel] >> 16) + bump).astype(np.uint16)
+            assert (got[sel] == want).all(), (name, pos)
+            seen[name] += int(sel.sum())
+    assert min(seen.values()) > 0, seen
+
+
 def test_rope_makes_logits_depend_on_relative_position_only():
     """<R(p) q, R(p') k> depends on p - p' only: shifting every position by a constant leaves the
     token scores unchanged (up to the bf16 rounding of the rotated vectors)."""
