@@ -26,9 +26,14 @@ COMMON_FLAGS = [
     "-mllvm", "-instcombine-max-copied-from-constant-users=1000000",
     "-Wall", "-Wno-unused-function",
 ]
-# no NaN canonicalisation around fmax in DEVICE code only (NaN inputs are a documented
-# precondition violation there); the host-side argument checks must still see NaNs
-DEVICE_ONLY_FLAGS = ["-Xarch_device", "-fno-honor-nans"]
+# no NaN canonicalisation around fmax in the DEVICE code of the scoring kernels only (NaN inputs
+# are a documented precondition violation there).  Host code must still see NaNs (argument
+# checks), and so must the selection kernels, which report NaN scores in band.
+SCORE_DEVICE_FLAGS = ["-Xarch_device", "-fno-honor-nans"]
+
+
+def _extra_flags(src):
+    return SCORE_DEVICE_FLAGS if os.path.basename(src).startswith("sp_score") else []
 
 
 def sources():
@@ -65,7 +70,7 @@ def build_library(verbose: bool = False, extra_flags=(), lib_path: str = LIB_PAT
         objs.append(obj)
         if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
             continue
-        jobs.append((obj, [hipcc, *COMMON_FLAGS, *DEVICE_ONLY_FLAGS, *extra_flags, *inc, "-c", src, "-o", obj]))
+        jobs.append((obj, [hipcc, *COMMON_FLAGS, *_extra_flags(src), *extra_flags, *inc, "-c", src, "-o", obj]))
     with ThreadPoolExecutor(max_workers=8) as pool:
         list(pool.map(lambda j: _run(j[1], verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden", *objs, "-o", lib_path],

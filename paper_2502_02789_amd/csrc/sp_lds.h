@@ -86,6 +86,26 @@ __device__ __forceinline__ void lds_poke64(uint32_t lds_addr, uint64_t v) {
   asm volatile("ds_write_b64 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
 }
 template <int OFF>
+__device__ __forceinline__ void lds_poke32_at(uint32_t lds_addr, uint32_t v) {
+  asm volatile("ds_write_b32 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
+}
+// four words STRIDE bytes apart, one wait for all of them
+template <int STRIDE>
+__device__ __forceinline__ u32x4 lds_peek4(uint32_t lds_addr) {
+  uint32_t a, b, c, d;
+  asm volatile(
+      "ds_read_b32 %0, %4\n\tds_read_b32 %1, %4 offset:%5\n\tds_read_b32 %2, %4 offset:%6\n\t"
+      "ds_read_b32 %3, %4 offset:%7\n\ts_waitcnt lgkmcnt(0)"
+      : "=&v"(a), "=&v"(b), "=&v"(c), "=&v"(d)
+      : "v"(lds_addr), "n"(STRIDE), "n"(2 * STRIDE), "n"(3 * STRIDE)
+      : "memory");
+  return u32x4{a, b, c, d};
+}
+// 4-byte store with agent-scope coherence
+__device__ __forceinline__ void store32_agent(void* dst, uint32_t v) {
+  asm volatile("global_store_dword %0, %1, off sc1" : : "v"(dst), "v"(v) : "memory");
+}
+template <int OFF>
 __device__ __forceinline__ void lds_fmax(uint32_t lds_addr, float v) {
   asm volatile("ds_max_f32 %0, %1 offset:%2" : : "v"(lds_addr), "v"(v), "n"(OFF) : "memory");
 }

@@ -267,7 +267,11 @@ static int general_max_tiles(const sp_score_args* a) { return (int)(a->T / kTile
 
 // the single-pass kernels are taken only on the caller's promise of an otherwise idle device
 bool single_pass_wanted(const sp_score_args* a) {
-  return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && stream_supported(a);
+  return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && (team_supported(a) || stream_supported(a));
+}
+// where the single-pass kernel that sp_score would pick keeps its "a wait expired" word
+static size_t single_pass_status_offset(const sp_score_args* a) {
+  return team_supported(a) ? team_status_offset(a) : stream_status_offset(a);
 }
 
 size_t general_workspace_bytes(const sp_score_args* a, bool with_tiled) {
@@ -288,7 +292,7 @@ void launch_lse_combine(const ScoreDev& p, hipStream_t stream) {
 
 // these paths have no bounded waits: leave "no wait expired" where sp_score_check looks
 static void clear_stream_status(const sp_score_args* a, hipStream_t stream) {
-  const size_t status_off = single_pass_wanted(a) ? stream_status_offset(a) : 0;
+  const size_t status_off = single_pass_wanted(a) ? single_pass_status_offset(a) : 0;
   if (status_off)
     hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, stream,
                        reinterpret_cast<uint32_t*>(static_cast<char*>(a->d_workspace) + status_off));
@@ -375,7 +379,7 @@ extern "C" size_t sp_score_workspace_bytes(const sp_score_args* a) {
   // (sp_score_general uses the plain kernels), so their kept-logits buffer is not asked for
   const bool single = sp::single_pass_wanted(a);
   const size_t general = sp::general_workspace_bytes(a, /*with_tiled=*/!single);
-  const size_t stream = single ? sp::stream_workspace_bytes(a) : 0;
+  const size_t stream = single ? std::max(sp::stream_workspace_bytes(a), sp::team_workspace_bytes(a)) : 0;
   return general > stream ? general : stream;
 }
 
@@ -408,7 +412,7 @@ extern "C" sp_status sp_score(const sp_score_args* a, void* hip_stream) {
   const sp_status st = check_score_args(a);
   if (st != SP_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (sp::single_pass_wanted(a)) return sp::stream_score(a, stream);
+  if (sp::single_pass_wanted(a)) return sp::team_supported(a) ? sp::team_score(a, stream) : sp::stream_score(a, stream);
   return sp::general_score(a, stream, /*allow_mfma=*/true);
 }
 
@@ -417,7 +421,7 @@ extern "C" sp_status sp_score_check(const sp_score_args* a, void* hip_stream) {
   if (st != SP_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (hipStreamSynchronize(stream) != hipSuccess) return SP_ELAUNCH;
-  const size_t off = sp::single_pass_wanted(a) ? sp::stream_status_offset(a) : 0;
+  const size_t off = sp::single_pass_wanted(a) ? sp::single_pass_status_offset(a) : 0;
   if (off == 0) return SP_OK;
   uint32_t word = 0;
   if (hipMemcpy(&word, static_cast<const char*>(a->d_workspace) + off, sizeof(word), hipMemcpyDeviceToHost) !=

@@ -49,4 +49,11 @@ size_t stream_workspace_bytes(const sp_score_args* a);
 sp_status stream_score(const sp_score_args* a, hipStream_t stream);
 size_t stream_status_offset(const sp_score_args* a);
 
+// single-pass kernel with per-KV-head teams of workgroups (sp_score_team.hip): one prompt of up
+// to 32K keys, SP_LAYER_MAX
+bool team_supported(const sp_score_args* a);
+size_t team_workspace_bytes(const sp_score_args* a);
+sp_status team_score(const sp_score_args* a, hipStream_t stream);
+size_t team_status_offset(const sp_score_args* a);
+
 }  // namespace sp

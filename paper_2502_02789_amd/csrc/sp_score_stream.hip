@@ -51,347 +51,66 @@
 #include <atomic>
 #include <mutex>
 
-#include "sp_score_internal.h"
-#include "sp_lds.h"
+#include "sp_stream_core.h"
 
 namespace sp {
 
-
-constexpr int kWaves = 8;
-constexpr int kThreads = kWaves * kWave;
-constexpr int kMaxWG = 256;
-constexpr uint32_t kEmpty32 = ~0u;
-constexpr uint32_t kPending32 = ~0u - 1;  // in an LDS landing zone: the sample has not arrived yet
 constexpr int kCtlBytes = 128;         // arrival counters and the workgroup's duty words
 constexpr int kStageBytes = kMaxWG * 16;  // landing zone of a reducer's sample: 4 rows x 4 bytes per workgroup
-constexpr int kDefaultSpinBudget = 1 << 16;  // polls per wave over the whole call before giving up (~0.1 s)
 constexpr int kDepSlotBytes = 8 * 32 * 8;  // one slab's deposits: 8 waves x 32 rows x (max, sum)
 
-struct StreamDev {
-  int M, L, N, H, G, lgG, S, lgS, slabs_per_layer, lgSPL, n_slabs, KPW, lgKPW, nwg, wpr, layer_reduce;  // S, slabs_per_layer: powers of two
-  int spin_budget;  // polls a wave may spend waiting for other workgroups over the whole call
-  float c;  // scale * log2(e): logits are handled in the base-2 domain
-  int64_t ts, hs;
-  const uint16_t* q;
+struct StreamDev : StreamShape {
+  int nwg, wpr, layer_reduce;
   const int32_t* n_valid;
   uint32_t* partial;  // [quad of rows][nwg][4]: each workgroup's log-sum-exp (base 2) of the quad's rows
   uint32_t* lse2;     // [rows]
   uint32_t* status;   // [0] != 0: a bounded wait ran out (results invalid)
   float* scores;
   float* lse_out;
-  const int32_t* block_table;  // paged cache: page numbers of the (single) prompt, else null
-  int lg_page;
-  int64_t page_stride;
-  const uint16_t* k[SP_MAX_LAYERS];
 };
-
-__global__ __launch_bounds__(256) void fill_empty_kernel(uint4* __restrict__ dst, size_t n_vec, uint32_t* status) {
-  const size_t stride = (size_t)gridDim.x * 256;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += stride)
-    dst[i] = make_uint4(kEmpty32, kEmpty32, kEmpty32, kEmpty32);
-  if (blockIdx.x == 0 && threadIdx.x == 0) status[0] = 0;
-}
-
-// Register i of a 32x32 accumulator tile holds key (i / 4) * 8 + (i % 4) (+ 4 for the upper
-// half-wave).  In the running-max array that key sits at cell (i / 4) * 8 + (i % 4) * 2 (+ 1 for
-// the upper half-wave) of its tile, and query rows are kSmaxPad cells apart modulo 32: the 16
-// lanes of one atomic (8 queries x 2 half-waves) then fall into 16 different LDS banks.
-constexpr int kSmaxPad = 2;
-__device__ __forceinline__ int smax_cell(int key) {  // key within the workgroup's slice -> cell in a row
-  return (key & ~7) | ((key & 3) << 1) | ((key >> 2) & 1);
-}
-template <int... I>
-__device__ __forceinline__ void lds_fmax_tile(uint32_t lds_addr, const float (&x)[16], std::integer_sequence<int, I...>) {
-  (lds_fmax<((I >> 2) * 8 + (I & 3) * 2) * 4>(lds_addr, x[I]), ...);
-}
 
 __device__ __forceinline__ uint64_t pack_stat(float m, float s) {
   return ((uint64_t)__float_as_uint(s) << 32) | __float_as_uint(m);
 }
 
 template <int D, int TPW, bool PAGED = false>
-struct Streamer {
-  static constexpr int NSETS = 8 / TPW;        // slabs of logits alive in registers
-  static constexpr int TPS = TPW + 1;          // stream tiles per slab: query tile + key tiles
-  static constexpr int KS = D / 16;            // MFMA k-steps per tile
-  static constexpr int ROW_B = D * 2;          // bytes of one row (one key / one query row)
-  static constexpr int TILE_B = 32 * ROW_B;    // 32 rows
-  static constexpr int UNITS = ROW_B / 16;     // 16-byte units per row
-  static constexpr int LOADS = TILE_B / 1024;  // wave-wide 16-byte loads per tile
-  static constexpr int RPI = 64 / UNITS;       // rows covered by one such load
+struct Streamer : StreamCore<D, TPW, PAGED> {
+  using Core = StreamCore<D, TPW, PAGED>;
+  using Core::NSETS; using Core::TILE_B; using Core::RING_BYTES;
+  using Core::wave; using Core::lane; using Core::half; using Core::col; using Core::kvh_local;
+  using Core::budget; using Core::issued; using Core::run_m; using Core::run_s;
+  using Core::may_poll; using Core::note_issued; using Core::fold; using Core::lds_ptr; using Core::layer_of;
   // slab s: published by the last wave to finish it, reduced by its reducers as soon as every
   // workgroup's words are seen, its log-sum-exps requested at the end of slab s + NSETS - 1 and
   // used at the start of slab s + NSETS (just before its register set is reused)
 
   const StreamDev& p;
-  float* smax;           // [N][KPW + kSmaxPad] running max of log2-probabilities (cells: smax_cell)
-  int wave, lane, half, col, wg;
-  int kvh_local, kbg;
-  int keys_wg;           // valid keys owned by this workgroup
-  int budget;            // polls left; a wait that finds it used up gives up and sets `expired`
-  bool expired;
-  int issued;            // vector-memory instructions issued so far by this wave (never over-counted)
-  int seq0, seq1;        // value of `issued` right after the loads of the tile in ring slot 0 / 1
+  int wg;
   int duty_k;            // reducer rotation: this workgroup reduces quad duty_k of the slab if duty_k < quads
-  uint32_t ring_lds;     // LDS byte address of this wave's two-slot ring
   uint32_t dep_lds;      // LDS: [NSETS][8 waves][32 rows] (max, sum) deposits
   uint32_t cnt_lds;      // LDS control block: words 0..7 arrival counters per set; 8 reducer duty (quad or -1);
                          // 9 mask of sets waiting to be published; 10, 11 the two duties' locks; 12 reducer
-                         // sample flag; 16..23 slab number of the set waiting to be published
+                         // sample flag; 13 "a wait of some wave expired"; 16..23 slab number of the set
+                         // waiting to be published
   uint32_t lse_lds;      // LDS: this wave's [2][32] fetched log-sum-exps
   uint32_t stage_lds;    // LDS: landing zone of a reducer sample (one per workgroup)
-  uint32_t rd0;          // LDS byte address of this lane's operand unit for k-step 0 in slot 0
-  uint32_t ld_off[4];    // per-lane global byte offset of key load j (depends on j & 3 only)
-  bf16x8 qf[KS];
-  f32x16 acc[NSETS][TPW];
-  float run_m, run_s;    // running (max of raw logits, sum of 2^((x-max)*c)) of this lane's row
 
-  // LDS layout of a tile: row r at r*ROW_B; inside a row the 16-byte unit holding head-dim
-  // elements [8u, 8u+8) sits at position u ^ key(r), key(r) = r & 15 (D=128) or (r >> 1) & 7
-  // (D=64).  With it the 16 lanes of an operand read hit 16 distinct bank groups, and a
-  // wave-wide direct load still fills 1 KiB of consecutive LDS.
-  __device__ __forceinline__ Streamer(const StreamDev& p_, unsigned char* smem) : p(p_) {
-    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    lane = threadIdx.x & 63;
-    half = lane >> 5;
-    col = lane & 31;
+  static constexpr int kFixedBytes = RING_BYTES + NSETS * kDepSlotBytes + kCtlBytes + kWaves * 256 + kStageBytes;
+
+  __device__ __forceinline__ Streamer(const StreamDev& p_, unsigned char* smem)
+      : Core(p_, (uint32_t)reinterpret_cast<uintptr_t>(smem), reinterpret_cast<float*>(smem + kFixedBytes),
+             (int)blockIdx.x, 0),
+        p(p_) {
     wg = blockIdx.x;
-    kvh_local = wave & (p.S - 1);
-    kbg = wave >> p.lgS;
     const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem);
-    ring_lds = smem_lds + wave * 2 * TILE_B;
-    dep_lds = smem_lds + kWaves * 2 * TILE_B;
+    dep_lds = smem_lds + RING_BYTES;
     cnt_lds = dep_lds + NSETS * kDepSlotBytes;
     lse_lds = cnt_lds + kCtlBytes + wave * 256;
     stage_lds = cnt_lds + kCtlBytes + kWaves * 256;
-    smax = reinterpret_cast<float*>(smem + kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + kCtlBytes + kWaves * 256 + kStageBytes);
-    keys_wg = max(0, min(p.KPW, p.M - wg * p.KPW));
-    budget = p.spin_budget;
-    expired = false;
-    issued = 0;
-    seq0 = seq1 = 0;
     duty_k = wg;
-    // operand read: unit (2t + half) of row col lives at position (2t + half) ^ key(col)
-    //             = 2 * (t ^ (key >> 1)) + (half ^ (key & 1)), so the address is rd0 ^ (t << 5)
-    const int key = (D == 128) ? (col & 15) : ((col >> 1) & 7);
-    rd0 = ring_lds + col * ROW_B + ((half ^ (key & 1)) << 4) + ((key >> 1) << 5);
-    // loads: lane covers row j*RPI + i (i = lane / UNITS) and LDS position lane % UNITS, i.e.
-    // data unit (lane % UNITS) ^ key(row); key(row) = key(i) ^ ((4j) & (UNITS-1)) (disjoint bits)
-    const int i = lane / UNITS;
-    const int key_i = (D == 128) ? i : (i >> 1);
-    const int u0 = (lane % UNITS) ^ key_i;
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj)
-      ld_off[jj] = (uint32_t)((int64_t)i * p.ts * 2) + (uint32_t)((u0 ^ ((4 * jj) & (UNITS - 1))) << 4);
   }
 
-  static size_t smem_bytes(int n_queries, int kpw) {
-    return (size_t)kWaves * 2 * TILE_B + NSETS * kDepSlotBytes + kCtlBytes + kWaves * 256 + kStageBytes +
-           (size_t)n_queries * (kpw + kSmaxPad) * sizeof(float);
-  }
-
-  __device__ __forceinline__ static __attribute__((address_space(3))) void* lds_ptr(uint32_t addr) {
-    return reinterpret_cast<__attribute__((address_space(3))) void*>(addr);
-  }
-  __device__ __forceinline__ static uint32_t lds_addr_of(const void* generic) {
-    return (uint32_t)reinterpret_cast<uintptr_t>(generic);
-  }
-
-  // One more round of a bounded wait?  False (and the wave remembers it) once the budget is gone.
-  __device__ __forceinline__ bool may_poll() {
-    if (budget > 0) { --budget; return true; }
-    expired = true;
-    return false;
-  }
-
-  __device__ __forceinline__ int layer_of(int slab) const { return slab >> p.lgSPL; }
-  __device__ __forceinline__ int kvh_of(int slab) const { return ((slab & (p.slabs_per_layer - 1)) << p.lgS) + kvh_local; }
   __device__ __forceinline__ int row_base(int slab) const { return ((slab << p.lgS) + kvh_local) * 32; }
-
-  // Direct global->LDS load of one key tile into ring slot `slot`.  Always exactly LOADS
-  // wave-wide loads (the vmcnt bookkeeping counts on it): rows beyond the prompt re-read row 0
-  // of the last in-range tile and are masked later.
-  __device__ __forceinline__ void issue_keys(int slab, int kb, int slot) {
-    int key_start = wg * p.KPW + (kbg * TPW + kb) * 32;
-    // keep the address arithmetic at its point of use: hoisted out of the slab loop it would
-    // pin dozens of registers for the whole kernel
-    asm volatile("" : "+s"(key_start));
-    const uint32_t dst = ring_lds + slot * TILE_B;
-    if constexpr (PAGED) {
-      // Paged cache: the RPI (4 or 8) rows of one load lie in one page (pages hold a power of two
-      // >= 8 keys, tiles start at multiples of 32); a scalar table lookup where a load enters a
-      // new page.  Loads and lanes beyond the prompt re-read a valid row (masked later).
-      int rows = min(32, p.M - key_start);
-      asm volatile("" : "+s"(rows));
-      const int first = rows > 0 ? key_start : 0;
-      const unsigned char* layer = reinterpret_cast<const unsigned char*>(p.k[layer_of(slab)]) +
-                                   2 * (int64_t)kvh_of(slab) * p.hs;
-      const int pmask = (1 << p.lg_page) - 1;
-      int ln = lane;
-      asm volatile("" : "+v"(ln));
-      const int i = ln / UNITS;
-      const uint32_t row_part = (uint32_t)((int64_t)i * p.ts * 2);
-      const unsigned char* base = layer;
-#pragma unroll
-      for (int j = 0; j < LOADS; ++j) {
-        const bool inside = j * RPI < rows;
-        const int kk = inside ? first + j * RPI : first;
-        if (j == 0 || !inside || ((j * RPI) & pmask) == 0)
-          base = layer + 2 * ((int64_t)p.block_table[kk >> p.lg_page] * p.page_stride + (int64_t)(kk & pmask) * p.ts);
-        else
-          base += (int64_t)RPI * p.ts * 2;
-        uint32_t lane_off = ld_off[j & 3];
-        asm volatile("" : "+v"(lane_off));
-        if (j * RPI + i >= rows) lane_off -= row_part;  // this lane's row is beyond the prompt: the load's first row instead
-        __builtin_amdgcn_global_load_lds(base + (size_t)lane_off, lds_ptr(dst + j * 1024), 16, 0, 0);
-      }
-      return;
-    }
-    const int start_eff = min(key_start, (p.M - 1) & ~31);
-    const unsigned char* base = reinterpret_cast<const unsigned char*>(p.k[layer_of(slab)]) +
-                                2 * ((int64_t)kvh_of(slab) * p.hs + (int64_t)start_eff * p.ts);
-    if (start_eff + 32 <= p.M) {  // whole tile inside the prompt
-#pragma unroll
-      for (int j = 0; j < LOADS; ++j) {
-        uint32_t lane_off = ld_off[j & 3];
-        asm volatile("" : "+v"(lane_off));  // scalar row base + 32-bit lane offset; nothing 64-bit per lane to keep around
-        const unsigned char* src = base + (int64_t)(j * RPI) * p.ts * 2 + (size_t)lane_off;
-        __builtin_amdgcn_global_load_lds(src, lds_ptr(dst + j * 1024), 16, 0, 0);
-      }
-    } else {
-      const int rows_in = p.M - start_eff;  // 1..31
-      int ln = lane;
-      asm volatile("" : "+v"(ln));
-      const int i = ln / UNITS;
-#pragma unroll
-      for (int j = 0; j < LOADS; ++j) {
-        const bool in = j * RPI + i < rows_in;
-        const int64_t row_off = in ? (int64_t)(j * RPI) * p.ts * 2 + (int64_t)ld_off[j & 3]
-                                   : (int64_t)(ld_off[j & 3] & (uint32_t)(ROW_B - 1));  // same unit of row 0
-        __builtin_amdgcn_global_load_lds(base + row_off, lds_ptr(dst + j * 1024), 16, 0, 0);
-      }
-    }
-  }
-
-  // Direct global->LDS load of the slab's query tile: row r = n*G + g holds Q[layer, n, kvh*G + g, :]
-  // (rows beyond G*N repeat row 0; their columns of the logit tiles are never used).
-  __device__ __forceinline__ void issue_queries(int slab, int slot) {
-    int rows = p.G * p.N;
-    asm volatile("" : "+s"(rows));
-    const uint32_t dst = ring_lds + slot * TILE_B;
-    const unsigned char* base = reinterpret_cast<const unsigned char*>(p.q) +
-                                2 * (((int64_t)layer_of(slab) * p.N * p.H + kvh_of(slab) * p.G) * D);
-    int ln = lane;
-    asm volatile("" : "+v"(ln));  // per-load offsets are cheap to recompute and expensive to keep
-    const int i = ln / UNITS;
-#pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-      const int r = j * RPI + i;
-      const int key = (D == 128) ? (r & 15) : ((r >> 1) & 7);
-      const int unit = (ln % UNITS) ^ key;
-      const int rr = r < rows ? r : 0;
-      const uint32_t off = (uint32_t)((rr >> p.lgG) * p.H * ROW_B + (rr & (p.G - 1)) * ROW_B + unit * 16);
-      __builtin_amdgcn_global_load_lds(base + off, lds_ptr(dst + j * 1024), 16, 0, 0);
-    }
-  }
-
-  // issue stream tile number IDX counted from the start of slab `slab` (0 = its queries,
-  // 1..TPW = its keys, TPW+1 = the next slab's queries, ...); past the end of the call the
-  // last slab is read again (nobody consumes it)
-  template <int IDX>
-  __device__ __forceinline__ void issue_stream(int slab, int slot) {
-    constexpr int ADV = IDX / TPS, I = IDX % TPS;
-    // the slot is about to be overwritten: every LDS read of its previous tile must have been
-    // performed (a freshly issued read could otherwise lose the race against an L2-hit load)
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    const int s = min(slab + ADV, p.n_slabs - 1);
-    if (I == 0) issue_queries(s, slot); else issue_keys(s, I - 1, slot);
-    note_issued(LOADS);
-    if (slot & 1) seq1 = issued; else seq0 = issued;
-  }
-  // the tile in ring slot `slot` has landed once at most the instructions issued after its
-  // loads are still in flight (vector-memory instructions of a wave complete in order)
-  __device__ __forceinline__ void wait_tile(int slot) {
-    wait_vmcnt_upto(__builtin_amdgcn_readfirstlane(issued - ((slot & 1) ? seq1 : seq0)));
-  }
-  // the bookkeeping is wave-uniform; saying so keeps it in scalar registers
-  __device__ __forceinline__ void note_issued(int k) { issued = __builtin_amdgcn_readfirstlane(issued + k); }
-
-  __device__ __forceinline__ bf16x8 read_unit(int t, int slot) const {
-    uint32_t base = rd0;
-    asm volatile("" : "+v"(base));  // one XOR per read beats KS addresses held in registers all along
-    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-        lds_ptr((base ^ (uint32_t)(t << 5)) + slot * TILE_B));
-  }
-
-  __device__ __forceinline__ void read_queries(int slot) {
-#pragma unroll
-    for (int t = 0; t < KS; ++t) qf[t] = read_unit(t, slot);
-  }
-
-  template <int SET>
-  __device__ __forceinline__ void mfma_tile(int kb, int slot) {
-    f32x16 a = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    bf16x8 kf[KS];
-#pragma unroll
-    for (int t = 0; t < KS; ++t) kf[t] = read_unit(t, slot);
-#pragma unroll
-    for (int t = 0; t < KS; ++t) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], a, 0, 0, 0);
-    // operand reads run kAhead steps ahead of the matrix instructions that use them
-    constexpr int kAhead = KS < 4 ? KS : 4;
-    __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
-#pragma unroll
-    for (int t = 0; t < KS - kAhead; ++t) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
-    acc[SET][kb] = a;
-  }
-
-  // key (within the workgroup's slice) held by accumulator register i of tile kb in this lane
-  __device__ __forceinline__ int key_of(int kb, int i) const {
-    return (kbg * TPW + kb) * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
-  }
-
-  template <int SET>
-  __device__ __forceinline__ void stats_tile(int kb) {
-    f32x16& a = acc[SET][kb];
-    const int first = (kbg * TPW + kb) * 32;
-    if (first + 32 > keys_wg) {  // ragged tail: keys beyond the prompt do not count
-      int left = keys_wg - first - half * 4;  // keys of this half-wave's first register still inside
-      asm volatile("" : "+v"(left));           // compare here, when needed: 16 hoisted lane masks would cost 32 SGPRs
-#pragma unroll
-      for (int i = 0; i < 16; ++i)
-        if ((i >> 2) * 8 + (i & 3) >= left) a[i] = -INFINITY;
-    }
-    float tm = a[0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) tm = fmaxf(tm, a[i]);
-    const float m_new = fmaxf(run_m, tm);
-    const float ref = (m_new == -INFINITY) ? 0.f : m_new;
-    const float off = -ref * p.c;
-    // four independent chains: the exponentials are long-latency and a single chain would
-    // serialise on them
-    float s0 = run_s * fast_exp2(fmaf(run_m, p.c, off)), s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; i += 4) {
-      s0 += fast_exp2(fmaf(a[i], p.c, off));
-      s1 += fast_exp2(fmaf(a[i + 1], p.c, off));
-      s2 += fast_exp2(fmaf(a[i + 2], p.c, off));
-      s3 += fast_exp2(fmaf(a[i + 3], p.c, off));
-    }
-    run_m = m_new;
-    run_s = (s0 + s1) + (s2 + s3);
-  }
-
-  // fold two (max, sum) pairs
-  __device__ __forceinline__ void fold(float& m, float& s, float pm, float ps) const {
-    const float mn = fmaxf(m, pm);
-    const float ref = (mn == -INFINITY) ? 0.f : mn;
-    s = s * fast_exp2((m - ref) * p.c) + ps * fast_exp2((pm - ref) * p.c);
-    m = mn;
-  }
 
   // Hop 1, sending side.  Deposit this wave's (max, sum) of each of its 32 rows in LDS and count
   // the arrival; the wave that arrives last publishes the slab (LDS operations of a wave are
@@ -615,46 +334,6 @@ struct Streamer {
     }
     return __uint_as_float(bits);
   }
-
-  // Turn the stored logits of set SET into log2-probabilities and max them into smax: over the
-  // heads of the KV group across lanes, over KV heads / layers in LDS.  LG = log2(group size).
-  template <int SET>
-  __device__ __forceinline__ void finish_set(float lse) {
-    const float neg_lse = -lse;
-    int c = col, h = half;
-    asm volatile("" : "+v"(c), "+v"(h));  // recompute the few lane-dependent values here rather than keep them all along
-    const bool writer = c < p.G * p.N && (c & (p.G - 1)) == 0;
-    // LDS address of this lane's first key of tile 0 in its query's row of smax
-    const uint32_t dst0 = lds_addr_of(smax + (c >> p.lgG) * (p.KPW + kSmaxPad) + kbg * TPW * 32 + h);
-#pragma unroll
-    for (int kb = 0; kb < TPW; ++kb) {
-      float x[16];
-      // step by step over all 16 registers: a DPP read right after the write of its source
-      // register would cost wait states
-#pragma unroll
-      for (int i = 0; i < 16; ++i) x[i] = fmaf(acc[SET][kb][i], p.c, neg_lse);
-      if (p.lgG >= 1) {  // group size is uniform: these are scalar branches around one copy of the code
-#pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = max_quad_xor1(x[i]);
-      }
-      if (p.lgG >= 2) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = max_quad_xor2(x[i]);
-      }
-      if (p.lgG >= 3) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = fmaxf(x[i], __shfl_xor(x[i], 4, kWave));
-      }
-      const int first = (kbg * TPW + kb) * 32;
-      if (first + 32 > keys_wg) {  // ragged tail: keys beyond the prompt never beat the -inf start value
-        const int left = keys_wg - first - h * 4;
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if ((i >> 2) * 8 + (i & 3) >= left) x[i] = -INFINITY;
-      }
-      if (writer) lds_fmax_tile(dst0 + kb * 128, x, std::make_integer_sequence<int, 16>{});
-    }
-  }
 };
 
 template <int D, int TPW, bool MEAN, bool PAGED>
@@ -670,7 +349,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
   for (int j = 0; j < (MEAN ? 8 : 1); ++j) tot[j] = 0.f;
   for (int i = threadIdx.x; i < cells; i += kThreads) *cell_at(i) = -INFINITY;
   if (threadIdx.x < 16)  // arrival counters, duty lock and flag: 0; the duty itself: none
-    *reinterpret_cast<uint32_t*>(smem + kWaves * 2 * St::TILE_B + NSETS * kDepSlotBytes + threadIdx.x * 4) = threadIdx.x == 8 ? ~0u : 0u;
+    *reinterpret_cast<uint32_t*>(smem + St::RING_BYTES + NSETS * kDepSlotBytes + threadIdx.x * 4) = threadIdx.x == 8 ? ~0u : 0u;
   __syncthreads();
 
   // layer-mean mode: slab `done` was just finished by this wave; if it closes a layer (other
@@ -781,8 +460,13 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
   }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
   // A wait of any wave of this workgroup gave up: its tokens' scores may rest on statistics that
-  // never arrived.  They are written as NaN so that no consumer can take them for scores.
-  const bool gave_up = __syncthreads_or(st.expired ? 1 : 0) != 0;
+  // never arrived.  They are written as NaN so that no consumer can take them for scores.  (The
+  // waves tell each other through a word of the control block: a library workgroup reduction
+  // would bring static LDS of its own, which the LDS budget of this kernel has no room for.)
+  if (st.expired && st.lane == 0) lds_or(st.cnt_lds + 52, 1u);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __syncthreads();
+  const bool gave_up = __builtin_amdgcn_readfirstlane(lds_peek(st.cnt_lds + 52)) != 0;
 
   int nv = p.n_valid ? p.n_valid[0] : p.N;
   nv = max(1, min(nv, p.N));
@@ -894,19 +578,24 @@ template <int D, int TPW, bool MEAN, bool PAGED = false>
 static sp_status launch_stream(const StreamDev& dev, const StreamPlan& pl, hipStream_t stream) {
   auto kernel = stream_score_kernel<D, TPW, MEAN, PAGED>;
   // once per kernel and device, under a lock: allow the large dynamic LDS size and make sure a
-  // workgroup of the largest size fits on a compute unit (the grid is one workgroup per unit)
+  // workgroup fits on a compute unit (the grid is one workgroup per unit; the plan has already
+  // bounded the LDS size by what a unit has)
   static std::mutex mu;
   static bool prepared[kMaxDevices] = {};
   {
     std::lock_guard<std::mutex> lock(mu);
     const int slot = current_device();
     if (!prepared[slot]) {
+      hipFuncAttributes fa;
+      if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) != hipSuccess) return SP_ELAUNCH;
+      const int max_dynamic = 160 * 1024 - (int)fa.sharedSizeBytes;  // a unit's LDS less the kernel's static part
+      if ((int)pl.smem_bytes > max_dynamic) return SP_ELAUNCH;
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              160 * 1024) != hipSuccess)
+                              max_dynamic) != hipSuccess)
         return SP_ELAUNCH;
       int per_cu = 0;
       if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kernel), kThreads,
-                                                       160 * 1024) != hipSuccess || per_cu < 1)
+                                                       pl.smem_bytes) != hipSuccess || per_cu < 1)
         return SP_ELAUNCH;
       prepared[slot] = true;
     }

@@ -1,0 +1,521 @@
+// Single-pass scorer for one prompt of up to 32K keys: teams of workgroups, one team per group
+// of KV heads.  SP_LAYER_MAX only (Sec. 3.2.2 of arXiv 2502.02789 as printed: maximum over heads
+// and layers, mean over queries).
+//
+// Same arithmetic and the same per-wave streaming as sp_score_stream.hip (see sp_stream_core.h):
+// every K-cache byte is read from HBM once, the raw logits of the last NSETS slabs wait in
+// registers for their rows' log-sum-exps.  What differs is who shares a softmax row.  There, every
+// workgroup owns 1/256 of the keys for ALL KV heads, so each row's statistics come from 256
+// workgroups and travel in two hops.  Here the grid is cut into TC teams; team t owns the KV heads
+// [t * H_kv/TC, (t+1) * H_kv/TC) and walks over (layer, own KV head) slabs; inside a team workgroup
+// j owns keys [j * KPW, (j+1) * KPW) and all eight of its waves work on the SAME KV head, 32 * TPW
+// keys each.  A softmax row therefore has only P = 256 / TC partners (64 for a 32K prompt), and
+// because the maximum over heads and layers commutes with everything, teams never talk to each
+// other until the very end:
+//
+//   * per slab a workgroup publishes ONE 128-byte line: the base-2 log-sum-exp of its keys for
+//     the slab's 32 rows, written by the wave that completes the slab (the waves' own values are
+//     merged through LDS);
+//   * the lines of a slab's P partners are contiguous, so what a workgroup needs to turn its own
+//     stored logits into probabilities is one dense P * 128-byte read.  Every workgroup does that
+//     read for itself (one hop; nobody reduces on behalf of others): a wave that passes by at the
+//     end of a slab sends the read on its way into an LDS landing zone marked "pending"; a later
+//     passer-by looks at the zone, re-requests the lines that were still empty, or folds the P
+//     values per row into the row's log-sum-exp and leaves the 32 results in LDS for all waves;
+//   * no wave ever waits through vmcnt for any of this; a wave waits (bounded, by polling LDS) only
+//     if the log-sum-exps of slab s - NSETS are not there when it is about to reuse the registers;
+//   * at the end each workgroup writes its [query][key] maxima of log2-probabilities to a per-team
+//     array, and a small second kernel takes the maximum over teams, exponentiates and averages
+//     over the valid queries.
+//
+// Publications per workgroup and slab: one full line instead of 32 scattered 16-byte stores;
+// coherent reads: P lines once (plus re-reads of late lines) instead of a two-hop chain.  Words
+// are "empty" (all ones) until written, written and read with agent-scope coherence; a small
+// kernel refills the exchange area at the start of each call.  As in the other single-pass
+// kernel all workgroups must be resident together (the caller's SP_SCORE_EXCLUSIVE_DEVICE
+// promise), every wait is bounded, and an expired wait turns the call's scores into NaN.
+#include <atomic>
+#include <mutex>
+
+#include "sp_stream_core.h"
+
+namespace sp {
+
+constexpr int kTeamCtlBytes = 128;
+constexpr int kTeamMaxPartners = 64;                       // landing zone: one line per partner
+constexpr int kTeamLandBytes = kTeamMaxPartners * 128;
+constexpr int kTeamDepBytes = 8 * 32 * 4;                  // one slab's deposits: 32 rows x 8 waves
+
+struct TeamDev : StreamShape {
+  int TC, lgTC;       // teams; team = workgroup % TC, index in team = workgroup / TC
+  int P;              // workgroups per team (a multiple of 8, at most kTeamMaxPartners)
+  int M_pad;          // P * KPW
+  uint32_t* partial;  // [team][slab][partner][32]: base-2 log-sum-exp of the partner's keys, per row
+  float* part;        // [team][N][M_pad]: the team's max over its heads and all layers of log2 p
+  uint32_t* status;   // [0] != 0: a bounded wait ran out (results invalid)
+  float* lse_out;
+};
+
+template <int D, int TPW, bool PAGED>
+struct Teamer : StreamCore<D, TPW, PAGED> {
+  using Core = StreamCore<D, TPW, PAGED>;
+  using Core::NSETS; using Core::RING_BYTES;
+  using Core::wave; using Core::lane; using Core::half; using Core::col;
+  using Core::issued; using Core::run_m; using Core::run_s;
+  using Core::may_poll; using Core::note_issued; using Core::fold; using Core::lds_ptr; using Core::layer_of;
+  using Core::kvh_of;
+
+  const TeamDev& p;
+  int team, pidx;
+  uint32_t dep_lds;   // LDS: [NSETS][32 rows][8 waves] each wave's base-2 log-sum-exp of the row over its keys
+  uint32_t ctl_lds;   // LDS control block: words 0..7 arrival counters per set; 8 last slab whose row
+                      // log-sum-exps are in LDS (-1: none); 9 last slab this workgroup has published
+                      // (-1: none); 10 the sampler's lock; 11 "a sample of slab [8]+1 has been requested"
+  uint32_t lse_lds;   // LDS: [NSETS][32] finished row log-sum-exps (slot = slab % NSETS)
+  uint32_t land_lds;  // LDS: landing zone of a sample, [P][32]
+
+  static constexpr int kFixedBytes = RING_BYTES + NSETS * kTeamDepBytes + kTeamCtlBytes + NSETS * 128 + kTeamLandBytes;
+  static size_t smem_bytes(int n_queries, int kpw) {
+    return (size_t)kFixedBytes + (size_t)n_queries * (kpw + kSmaxPad) * sizeof(float);
+  }
+
+  __device__ __forceinline__ Teamer(const TeamDev& p_, unsigned char* smem)
+      : Core(p_, (uint32_t)reinterpret_cast<uintptr_t>(smem), reinterpret_cast<float*>(smem + kFixedBytes),
+             (int)(blockIdx.x >> p_.lgTC), (int)(blockIdx.x & (p_.TC - 1)) * p_.slabs_per_layer),
+        p(p_) {
+    team = blockIdx.x & (p.TC - 1);
+    pidx = blockIdx.x >> p.lgTC;
+    const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+    dep_lds = smem_lds + RING_BYTES;
+    ctl_lds = dep_lds + NSETS * kTeamDepBytes;
+    lse_lds = ctl_lds + kTeamCtlBytes;
+    land_lds = lse_lds + NSETS * 128;
+  }
+
+  // log2(2^a + 2^b + ...) of eight values, -inf if all are
+  __device__ __forceinline__ static float lse2_of8(const u32x4& a, const u32x4& b) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = __uint_as_float(a[i]); v[4 + i] = __uint_as_float(b[i]); }
+    float m = v[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) m = fmaxf(m, v[i]);
+    const float ref = (m == -INFINITY) ? 0.f : m;
+    float z = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z += fast_exp2(v[i] - ref);
+    return (m == -INFINITY) ? -INFINITY : m + __builtin_amdgcn_logf(z);  // v_log_f32 is log2
+  }
+
+  // This wave is done with the slab's keys: leave the base-2 log-sum-exp of each of its 32 rows
+  // over its own keys in LDS and count the arrival; the wave that arrives last merges the eight
+  // waves' values and publishes the workgroup's line (LDS operations of a wave are performed in
+  // order, so whoever sees the count complete also sees every deposit).
+  template <int SET>
+  __device__ __forceinline__ void deposit(int slab) {
+    float m = run_m, s = run_s;
+    fold(m, s, __shfl_xor(run_m, 32, kWave), __shfl_xor(run_s, 32, kWave));
+    const float v = (m == -INFINITY) ? -INFINITY : fmaf(m, p.c, __builtin_amdgcn_logf(s));
+    uint32_t dst = dep_lds + col * 32 + wave * 4;
+    asm volatile("" : "+v"(dst));  // one address plus an immediate per set, not NSETS addresses kept alive
+    if (half == 0) lds_poke32_at<SET * kTeamDepBytes>(dst, __float_as_uint(v));
+    uint32_t old = 0;
+    if (lane == 0) old = lds_add_rtn(ctl_lds + SET * 4, 1);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if ((old & 7) == 7) publish(slab, dep_lds + SET * kTeamDepBytes);
+  }
+
+  __device__ __forceinline__ void publish(int slab, uint32_t dep) {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));  // address arithmetic of this once-per-slab path stays here instead of being hoisted
+    if (ln < 32) {
+      const u32x4 a = lds_peek128(dep + ln * 32), b = lds_peek128(dep + ln * 32 + 16);
+      const float out = lse2_of8(a, b);  // (-inf -- no key of the prompt in this workgroup -- is a value, not "empty")
+      store32_agent(p.partial + ((int64_t)(team * p.n_slabs + slab) * p.P + pidx) * 32 + ln, __float_as_uint(out));
+    }
+    note_issued(1);
+    if (ln == 0) lds_poke32(ctl_lds + 36, (uint32_t)slab);
+  }
+
+  // One step, by whichever wave comes by, towards the row log-sum-exps of the next slab that
+  // lacks them (never beyond slab `limit`, and never before this workgroup itself has published
+  // that slab: its partners are then about as far).  Never waits.
+  __device__ __forceinline__ void service(int limit) {
+    const uint64_t st = lds_peek64(ctl_lds + 32);
+    const int r = (int)__builtin_amdgcn_readfirstlane((uint32_t)st) + 1;
+    const int pub = (int)__builtin_amdgcn_readfirstlane((uint32_t)(st >> 32));
+    if (r > limit || r > pub) return;
+    // one wave at a time: test-and-set
+    uint32_t held = 1;
+    if (lane == 0) held = lds_or_rtn(ctl_lds + 40, 1);
+    if (__builtin_amdgcn_readfirstlane(held) != 0) return;
+    // (another wave may have finished slab r between the two looks)
+    if ((int)__builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 32)) + 1 == r) sample_step(r);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (lane == 0) lds_poke32(ctl_lds + 40, 0);
+  }
+
+  // No sample of slab r out yet: mark the landing zone "pending" and request the P partner lines
+  // (P / 8 wave-wide 16-byte direct-to-LDS loads).  Sample out: look at the zone (LDS reads only);
+  // words still pending -> come back later; pieces still empty -> request those pieces again;
+  // everything there -> fold the P values of each row and leave the 32 log-sum-exps in LDS.
+  __device__ __forceinline__ void sample_step(int r) {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const bool sampled = __builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 44)) != 0;
+    const int groups = p.P >> 3;
+    const unsigned char* src = reinterpret_cast<const unsigned char*>(p.partial + (int64_t)(team * p.n_slabs + r) * p.P * 32) + ln * 16;
+    const u32x4 fill = {kPending32, kPending32, kPending32, kPending32};
+    if (!sampled) {
+#pragma unroll 1  // rare path: keep its register appetite small
+      for (int i = 0; i < groups; ++i) lds_poke128(land_lds + i * 1024 + ln * 16, fill);
+      if (ln == 0) lds_poke32(ctl_lds + 44, 1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the pattern is in place before any answer can land
+#pragma unroll
+      for (int i = 0; i < kTeamMaxPartners / 8; ++i)
+        if (i < groups) __builtin_amdgcn_global_load_lds(src + i * 1024, lds_ptr(land_lds + i * 1024), 16, 0, /*sc1*/ 16);
+      note_issued(groups);
+      return;
+    }
+    bool pending = false;
+    uint32_t miss = 0;  // bit i: this lane's 16 bytes of load i hold an empty word
+#pragma unroll
+    for (int i = 0; i < kTeamMaxPartners / 8; ++i) {
+      if (i < groups) {
+        const u32x4 w = lds_peek128(land_lds + i * 1024 + ln * 16);
+        pending |= w.x == kPending32 || w.y == kPending32 || w.z == kPending32 || w.w == kPending32;
+        if (w.x == kEmpty32 || w.y == kEmpty32 || w.z == kEmpty32 || w.w == kEmpty32) miss |= 1u << i;
+      }
+    }
+    if (__any(pending)) return;
+    if (__any(miss != 0)) {
+#pragma unroll
+      for (int i = 0; i < kTeamMaxPartners / 8; ++i)
+        if (i < groups && ((miss >> i) & 1)) lds_poke128(land_lds + i * 1024 + ln * 16, fill);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int i = 0; i < kTeamMaxPartners / 8; ++i) {
+        if (i < groups && __any((miss >> i) & 1)) {  // wave-uniform: the instruction is issued, for the lanes that miss
+          if ((miss >> i) & 1)
+            __builtin_amdgcn_global_load_lds(src + i * 1024, lds_ptr(land_lds + i * 1024), 16, 0, /*sc1*/ 16);
+          note_issued(1);
+        }
+      }
+      return;
+    }
+    // all P lines are here: lane (row, h) folds partners [h * P/2, (h+1) * P/2) of its row
+    const int row = ln & 31, hf = ln >> 5;
+    const int per_half = p.P >> 1;  // a multiple of four
+    const uint32_t base = land_lds + hf * per_half * 128 + row * 4;
+    float m = -INFINITY;
+#pragma unroll 1
+    for (int j = 0; j < per_half; j += 4) {
+      const u32x4 w = lds_peek4<128>(base + j * 128);
+      m = fmaxf(fmaxf(m, fmaxf(__uint_as_float(w.x), __uint_as_float(w.y))), fmaxf(__uint_as_float(w.z), __uint_as_float(w.w)));
+    }
+    m = fmaxf(m, __shfl_xor(m, 32, kWave));  // finite: the prompt is not empty
+    float z = 0.f;
+#pragma unroll 1
+    for (int j = 0; j < per_half; j += 4) {
+      const u32x4 w = lds_peek4<128>(base + j * 128);
+      z += (fast_exp2(__uint_as_float(w.x) - m) + fast_exp2(__uint_as_float(w.y) - m)) +
+           (fast_exp2(__uint_as_float(w.z) - m) + fast_exp2(__uint_as_float(w.w) - m));
+    }
+    z += __shfl_xor(z, 32, kWave);
+    const float lse = m + __builtin_amdgcn_logf(z);
+    if (hf == 0) lds_poke32(lse_lds + (r & (NSETS - 1)) * 128 + row * 4, __float_as_uint(lse));
+    if (ln == 0) {
+      lds_poke32(ctl_lds + 44, 0);            // no sample out for the next slab
+      lds_poke32(ctl_lds + 32, (uint32_t)r);  // after the values: LDS writes of a wave are performed in order
+    }
+    if (p.lse_out && pidx == 0 && hf == 0 && row < p.G * p.N)  // (not counted in `issued`: counting less only waits more)
+      p.lse_out[((int64_t)layer_of(r) * p.N + (row >> p.lgG)) * p.H + kvh_of(r) * p.G + (row & (p.G - 1))] =
+          lse * 0.6931471805599453f;
+  }
+
+  // This lane's row log-sum-exp of `slab`.  Normally it is there; if not, keep the sampling going
+  // until it is (bounded).
+  __device__ __forceinline__ float take_lse(int slab) {
+    while ((int)__builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 32)) < slab && may_poll()) {
+      service(slab);
+      __builtin_amdgcn_s_sleep(2);
+    }
+    int c = col;
+    asm volatile("" : "+v"(c));
+    return __uint_as_float(lds_peek(lse_lds + (slab & (NSETS - 1)) * 128 + c * 4));
+  }
+};
+
+template <int D, int TPW, bool PAGED>
+__global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
+  extern __shared__ __align__(1024) unsigned char smem[];
+  using Tm = Teamer<D, TPW, PAGED>;
+  constexpr int NSETS = Tm::NSETS, TPS = Tm::TPS;
+  Tm tm(p, smem);
+  const int cells = p.N * p.KPW;  // (query, key) cells of this workgroup
+  auto cell_at = [&](int c) __attribute__((always_inline)) { return tm.smax + c + kSmaxPad * (c >> p.lgKPW); };  // skips the row padding
+  for (int i = threadIdx.x; i < cells; i += kThreads) *cell_at(i) = -INFINITY;
+  if (threadIdx.x < 16)  // arrival counters, lock and flag: 0; "last slab done / published": none
+    *reinterpret_cast<uint32_t*>(smem + Tm::RING_BYTES + NSETS * kTeamDepBytes + threadIdx.x * 4) =
+        (threadIdx.x == 8 || threadIdx.x == 9) ? ~0u : 0u;
+  __syncthreads();
+
+  tm.template issue_stream<0>(0, 0);
+  tm.template issue_stream<1>(0, 1);
+
+  // One slab.  Stream tile x of the slab sits in ring slot (SET*TPS + x) & 1 (NSETS is even, so
+  // the slab's parity is SET's).
+  auto body = [&](auto set_tag, int slab) __attribute__((always_inline)) {
+    constexpr int SET = decltype(set_tag)::value;
+    constexpr int SLOT0 = (SET * TPS) & 1;
+    // The two waves that share a SIMD take turns at being the one the instruction arbiter
+    // prefers; left alone it favours the older wave throughout, and the slab is only published
+    // when the slowest wave is done with it.
+    if ((slab ^ (tm.wave >> 2)) & 1) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(0);
+    tm.wait_tile(SLOT0);
+    tm.read_queries(SLOT0);
+    tm.template issue_stream<2>(slab, SLOT0);
+    if (slab >= NSETS)  // set SET still holds slab - NSETS
+      tm.template finish_set<SET>(tm.take_lse(slab - NSETS));
+    tm.run_m = -INFINITY;
+    tm.run_s = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < TPW; ++kb) {
+      const int slot = (SLOT0 + 1 + kb) & 1;
+      tm.wait_tile(slot);
+      tm.template mfma_tile<SET>(kb, slot);
+      switch (kb) {  // a compile-time constant after unrolling
+        case 0: tm.template issue_stream<3>(slab, slot); break;
+        case 1: tm.template issue_stream<4>(slab, slot); break;
+        case 2: tm.template issue_stream<5>(slab, slot); break;
+        default: tm.template issue_stream<6>(slab, slot); break;
+      }
+      tm.template stats_tile<SET>(kb);
+    }
+    tm.template deposit<SET>(slab);
+    // a step towards the log-sum-exps of an earlier slab, here, where the fewest registers are
+    // live; one slab behind, so that the partners have most likely published it
+    tm.service(slab - 1);
+  };
+
+  for (int s0 = 0; s0 < p.n_slabs; s0 += NSETS) {
+    body(std::integral_constant<int, 0>{}, s0);
+    if (s0 + 1 < p.n_slabs) body(std::integral_constant<int, 1>{}, s0 + 1);
+    if (s0 + 2 < p.n_slabs) body(std::integral_constant<int, 2>{}, s0 + 2);
+    if (s0 + 3 < p.n_slabs) body(std::integral_constant<int, 3>{}, s0 + 3);
+    if (NSETS > 4) {
+      if (s0 + 4 < p.n_slabs) body(std::integral_constant<int, 4 % NSETS>{}, s0 + 4);
+      if (s0 + 5 < p.n_slabs) body(std::integral_constant<int, 5 % NSETS>{}, s0 + 5);
+      if (s0 + 6 < p.n_slabs) body(std::integral_constant<int, 6 % NSETS>{}, s0 + 6);
+      if (s0 + 7 < p.n_slabs) body(std::integral_constant<int, 7 % NSETS>{}, s0 + 7);
+    }
+  }
+
+  // drain: the exchange of the last slabs cannot hide behind further streaming
+  wait_vmcnt<0>();
+  for (int s = max(0, p.n_slabs - NSETS); s < p.n_slabs; ++s) {
+    const float lse = tm.take_lse(s);
+    switch (s % NSETS) {
+      case 0: tm.template finish_set<0>(lse); break;
+      case 1: tm.template finish_set<1>(lse); break;
+      case 2: tm.template finish_set<2>(lse); break;
+      case 3: tm.template finish_set<3>(lse); break;
+      case 4: tm.template finish_set<4 % NSETS>(lse); break;
+      case 5: tm.template finish_set<5 % NSETS>(lse); break;
+      case 6: tm.template finish_set<6 % NSETS>(lse); break;
+      default: tm.template finish_set<7 % NSETS>(lse); break;
+    }
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
+  // A wait of some wave gave up: the call's result is void (the second kernel turns every score
+  // into NaN when it finds the status word set).
+  if (tm.expired && tm.lane == 0) atomicOr(p.status, 1u);
+  __syncthreads();  // every wave's maxima are in LDS
+
+  // the team's maxima for this workgroup's keys: [team][query][key]
+  for (int i = threadIdx.x; i < p.N * tm.keys_wg; i += kThreads) {
+    const int n = i / tm.keys_wg, key = i - n * tm.keys_wg;
+    p.part[((int64_t)tm.team * p.N + n) * p.M_pad + (int64_t)tm.pidx * p.KPW + key] =
+        tm.smax[n * (p.KPW + kSmaxPad) + smax_cell(key)];
+  }
+}
+
+// score[key] = mean over the valid queries of 2^(max over teams of the team's log2-probability
+// maximum): the maximum over all heads and layers, then the mean over queries (Sec. 3.2.2)
+__global__ __launch_bounds__(256) void team_finish_kernel(const float* __restrict__ part, int TC, int N, int M, int M_pad,
+                                                          const int32_t* __restrict__ n_valid,
+                                                          const uint32_t* __restrict__ status, float* __restrict__ scores) {
+  const int key = blockIdx.x * 256 + threadIdx.x;
+  if (key >= M) return;
+  if (status[0] != 0) {  // a bounded wait expired somewhere: nothing of this call can be trusted
+    scores[key] = __uint_as_float(0x7fc00000u);
+    return;
+  }
+  int nv = n_valid ? n_valid[0] : N;
+  nv = max(1, min(nv, N));
+  float sum = 0.f;
+  for (int n = 0; n < nv; ++n) {
+    float m = -INFINITY;
+    for (int t = 0; t < TC; ++t) m = fmaxf(m, part[((int64_t)t * N + n) * M_pad + key]);
+    sum += fast_exp2(m);
+  }
+  scores[key] = sum / (float)nv;
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+struct TeamPlan {
+  bool ok;
+  int TC, P, TPW, KPW, kpt, n_slabs, M_pad;
+  size_t partial_bytes, part_bytes, smem_bytes;
+};
+
+static int team_device_cu_count() {
+  static std::atomic<int> cached[kMaxDevices];
+  const int slot = current_device();
+  const int have = cached[slot].load(std::memory_order_relaxed);
+  if (have > 0) return have;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+    (void)hipGetLastError();
+    return kMaxWG;  // no device visible (sizing queries on a CPU-only host): assume the full chip
+  }
+  cached[slot].store(cus, std::memory_order_relaxed);
+  return cus;
+}
+
+static TeamPlan make_team_plan(const sp_score_args* a, int cus) {
+  TeamPlan pl{};
+  pl.ok = false;
+  const int G = a->H / a->H_kv;
+  if (a->B != 1 || a->T < 1 || a->layer_reduce != SP_LAYER_MAX) return pl;
+  if (a->rope_theta != 0.f) return pl;  // un-rotated caches take the general kernels
+  if (G != 1 && G != 2 && G != 4 && G != 8) return pl;
+  if (G * a->N > 32) return pl;
+  cus = std::min(cus, kMaxWG);
+  // the most teams (fewest partners per softmax row) and the fewest key tiles per wave and slab
+  // that still cover the prompt
+  for (int tc = 8; tc >= 4; tc >>= 1) {
+    if (a->H_kv % tc != 0) continue;
+    const int kpt = a->H_kv / tc;
+    if (kpt & (kpt - 1)) continue;  // slabs per layer: a power of two
+    const int partners = std::min(kTeamMaxPartners, cus / tc) / 8 * 8;
+    if (partners < 8) continue;
+    for (int tpw = 1; tpw <= 2; ++tpw) {
+      const int kpw = kWaves * tpw * 32;
+      if ((int64_t)partners * kpw < a->T) continue;
+      const size_t smem = (size_t)kWaves * 2 * 32 * a->d * 2 + (size_t)(8 / tpw) * (kTeamDepBytes + 128) + kTeamCtlBytes +
+                          kTeamLandBytes + (size_t)a->N * (kpw + kSmaxPad) * sizeof(float);
+      if (smem > 160 * 1024) continue;
+      pl.ok = true;
+      pl.TC = tc; pl.P = partners; pl.TPW = tpw; pl.KPW = kpw; pl.kpt = kpt;
+      pl.n_slabs = a->L * kpt;
+      pl.M_pad = partners * kpw;
+      pl.partial_bytes = align_up((size_t)tc * pl.n_slabs * partners * 128, 256);
+      pl.part_bytes = align_up((size_t)tc * a->N * pl.M_pad * sizeof(float), 256);
+      pl.smem_bytes = smem;
+      return pl;
+    }
+  }
+  return pl;
+}
+
+bool team_supported(const sp_score_args* a) { return make_team_plan(a, team_device_cu_count()).ok; }
+
+size_t team_workspace_bytes(const sp_score_args* a) {
+  const TeamPlan pl = make_team_plan(a, kMaxWG);  // sized for the full chip
+  if (!pl.ok) return 0;
+  return pl.partial_bytes + pl.part_bytes + 256;
+}
+
+// byte offset of the status word inside the workspace, or 0 if the shape does not use this kernel
+size_t team_status_offset(const sp_score_args* a) {
+  const TeamPlan pl = make_team_plan(a, team_device_cu_count());
+  return pl.ok ? pl.partial_bytes + pl.part_bytes : 0;
+}
+
+template <int D, int TPW, bool PAGED>
+static sp_status launch_team(const TeamDev& dev, const TeamPlan& pl, hipStream_t stream) {
+  auto kernel = team_score_kernel<D, TPW, PAGED>;
+  // once per kernel and device, under a lock: allow the large dynamic LDS size and make sure the
+  // whole grid can be resident at once
+  static std::mutex mu;
+  static bool prepared[kMaxDevices] = {};
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    const int slot = current_device();
+    if (!prepared[slot]) {
+      hipFuncAttributes fa;
+      if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) != hipSuccess) return SP_ELAUNCH;
+      const int max_dynamic = 160 * 1024 - (int)fa.sharedSizeBytes;  // a unit's LDS less the kernel's static part
+      if ((int)pl.smem_bytes > max_dynamic) return SP_ELAUNCH;
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              max_dynamic) != hipSuccess)
+        return SP_ELAUNCH;
+      int per_cu = 0;
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kernel), kThreads,
+                                                       pl.smem_bytes) != hipSuccess || per_cu < 1)
+        return SP_ELAUNCH;
+      prepared[slot] = true;
+    }
+  }
+  hipLaunchKernelGGL(kernel, dim3(pl.TC * pl.P), dim3(kThreads), pl.smem_bytes, stream, dev);
+  return launch_status();
+}
+
+sp_status team_score(const sp_score_args* a, hipStream_t stream) {
+  const TeamPlan pl = make_team_plan(a, team_device_cu_count());
+  if (!pl.ok) return SP_EUNSUPPORTED;
+  TeamDev dev;
+  dev.M = (int)a->T; dev.L = a->L; dev.N = a->N; dev.H = a->H; dev.G = a->H / a->H_kv;
+  dev.lgG = dev.G == 1 ? 0 : dev.G == 2 ? 1 : dev.G == 4 ? 2 : 3;
+  dev.S = 1; dev.lgS = 0;
+  dev.slabs_per_layer = pl.kpt;
+  dev.lgSPL = 0;
+  while ((1 << dev.lgSPL) < pl.kpt) ++dev.lgSPL;
+  dev.n_slabs = pl.n_slabs;
+  dev.KPW = pl.KPW;
+  dev.lgKPW = 0;
+  while ((1 << dev.lgKPW) < pl.KPW) ++dev.lgKPW;
+  dev.spin_budget = sp_set_wait_budget(-1);
+  dev.c = a->scale * 1.4426950408889634f;
+  dev.ts = a->k_token_stride; dev.hs = a->k_head_stride;
+  dev.q = static_cast<const uint16_t*>(a->d_q);
+  dev.block_table = a->d_block_table;
+  dev.lg_page = 0;
+  while (a->d_block_table && (1 << dev.lg_page) < a->page_size) ++dev.lg_page;
+  dev.page_stride = a->k_page_stride;
+  for (int l = 0; l < SP_MAX_LAYERS; ++l)
+    dev.k[l] = l < a->L ? static_cast<const uint16_t*>(a->k_layers[l]) : nullptr;
+  dev.TC = pl.TC;
+  dev.lgTC = pl.TC == 8 ? 3 : 2;
+  dev.P = pl.P;
+  dev.M_pad = pl.M_pad;
+  char* ws = static_cast<char*>(a->d_workspace);
+  dev.partial = reinterpret_cast<uint32_t*>(ws);
+  dev.part = reinterpret_cast<float*>(ws + pl.partial_bytes);
+  dev.status = reinterpret_cast<uint32_t*>(ws + pl.partial_bytes + pl.part_bytes);
+  dev.lse_out = a->d_lse;
+
+  const size_t n_vec = pl.partial_bytes / 16;
+  const int fill_blocks = (int)std::min<size_t>((n_vec + 255) / 256, 1024);
+  hipLaunchKernelGGL(fill_empty_kernel, dim3(fill_blocks), dim3(256), 0, stream, reinterpret_cast<uint4*>(ws), n_vec,
+                     dev.status);
+  if (hipGetLastError() != hipSuccess) return SP_ELAUNCH;
+  sp_status st;
+  if (a->d_block_table) {
+    if (a->d == 128) st = pl.TPW == 1 ? launch_team<128, 1, true>(dev, pl, stream) : launch_team<128, 2, true>(dev, pl, stream);
+    else st = pl.TPW == 1 ? launch_team<64, 1, true>(dev, pl, stream) : launch_team<64, 2, true>(dev, pl, stream);
+  } else {
+    if (a->d == 128) st = pl.TPW == 1 ? launch_team<128, 1, false>(dev, pl, stream) : launch_team<128, 2, false>(dev, pl, stream);
+    else st = pl.TPW == 1 ? launch_team<64, 1, false>(dev, pl, stream) : launch_team<64, 2, false>(dev, pl, stream);
+  }
+  if (st != SP_OK) return st;
+  hipLaunchKernelGGL(team_finish_kernel, dim3((unsigned)((a->T + 255) / 256)), dim3(256), 0, stream, dev.part, dev.TC,
+                     dev.N, dev.M, dev.M_pad, a->d_n_valid, dev.status, a->d_scores);
+  return launch_status();
+}
+
+}  // namespace sp

@@ -367,22 +367,27 @@ extern "C" size_t sp_pool_select_workspace_bytes(const sp_pool_select_args* a) {
          sp::align_up(8 * mc, 256) + sp::align_up(4 * mc, 256);
 }
 
-extern "C" sp_status sp_pool_select(const sp_pool_select_args* a, void* hip_stream) {
-  using namespace sp;
+namespace sp {
+
+// argument checks shared by the two entry points (everything but the scratch space)
+static sp_status check_select_args(const sp_pool_select_args* a) {
   if (!a) return SP_ENULL;
   if (!select_shape_ok(a)) return SP_EINVAL;
   if (!a->d_cu_seqlens || !a->d_scores || !a->d_kept_idx || !a->d_cu_keep) return SP_ENULL;
   if (a->kept_capacity < 0) return SP_EINVAL;
-  if (!a->d_workspace || a->workspace_bytes < sp_pool_select_workspace_bytes(a)) return SP_EWORKSPACE;
-  if (reinterpret_cast<uintptr_t>(a->d_workspace) & 255u) return SP_EALIGN;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  return SP_OK;
+}
+
+// enqueue the selection with `scratch` (device memory, 256-byte aligned, at least
+// sp_pool_select_workspace_bytes(a) bytes) as the kernels' scratch space
+static sp_status run_pool_select(const sp_pool_select_args* a, void* scratch, hipStream_t stream) {
   const size_t mc = select_max_chunks(a);
   SelDev p;
   p.B = a->B; p.T = (int)a->T; p.chunk = a->chunk; p.radius = (a->pool_window - 1) / 2;
   p.keep_rate = a->keep_rate; p.capacity = a->kept_capacity;
   p.cu = a->d_cu_seqlens; p.scores = a->d_scores; p.kept_idx = a->d_kept_idx; p.cu_keep = a->d_cu_keep;
   p.chunk_scores_out = a->d_chunk_scores;
-  char* ws = static_cast<char*>(a->d_workspace);
+  char* ws = static_cast<char*>(scratch);
   p.cu_chunks = reinterpret_cast<int32_t*>(ws); ws += align_up(4 * ((size_t)a->B + 1), 256);
   p.seq_keep = reinterpret_cast<int32_t*>(ws);  ws += align_up(4 * (size_t)a->B, 256);
   p.cs = reinterpret_cast<double*>(ws);         ws += align_up(8 * mc, 256);
@@ -404,4 +409,15 @@ extern "C" sp_status sp_pool_select(const sp_pool_select_args* a, void* hip_stre
   if (a->T > 0)
     hipLaunchKernelGGL(emit_kernel, dim3((unsigned)((a->T + 255) / 256)), dim3(256), 0, stream, p);
   return launch_status();
+}
+
+}  // namespace sp
+
+extern "C" sp_status sp_pool_select(const sp_pool_select_args* a, void* hip_stream) {
+  using namespace sp;
+  const sp_status st = check_select_args(a);
+  if (st != SP_OK) return st;
+  if (!a->d_workspace || a->workspace_bytes < sp_pool_select_workspace_bytes(a)) return SP_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(a->d_workspace) & 255u) return SP_EALIGN;
+  return run_pool_select(a, a->d_workspace, static_cast<hipStream_t>(hip_stream));
 }
