@@ -197,6 +197,19 @@ SP_API int64_t sp_keep_upper_bound(int32_t B, const int32_t* h_seqlens, int32_t 
 SP_API size_t sp_pool_select_workspace_bytes(const sp_pool_select_args* args);
 SP_API sp_status sp_pool_select(const sp_pool_select_args* args, void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP-graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same operation and results as sp_pool_select, but
+ * the scratch space is a fixed array inside the library's device image instead of a caller
+ * workspace (d_workspace / workspace_bytes are ignored).  Limits: B <= SP_STATIC_MAX_SEQS and
+ * T / chunk + B <= SP_STATIC_MAX_CHUNKS, else SP_EUNSUPPORTED.  Calls nothing that allocates.
+ * Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU race
+ * (serialise them on one stream).  The array (SP_STATIC_SCRATCH_BYTES per GPU) lives until the
+ * process ends. */
+#define SP_STATIC_MAX_SEQS 4096
+#define SP_STATIC_MAX_CHUNKS 131072
+#define SP_STATIC_SCRATCH_BYTES (2u << 20)
+SP_API sp_status sp_pool_select_static(const sp_pool_select_args* args, void* hip_stream);
+
 /* ---------------------------------------------------------------------------
  * sp_gather: restore_pos_ids (Algorithm 1, Sec. 3.2.4) plus the gathers the base
  * model's prefill needs.  For kept slot s of sequence b:

@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecpref
 
 EXPORTS = (
     "sp_score_workspace_bytes", "sp_score", "sp_score_general", "sp_score_check", "sp_set_wait_budget",
-    "sp_keep_upper_bound", "sp_pool_select_workspace_bytes", "sp_pool_select",
+    "sp_keep_upper_bound", "sp_pool_select_workspace_bytes", "sp_pool_select", "sp_pool_select_static",
     "sp_gather", "sp_strerror", "sp_version",
 )
 
@@ -91,6 +91,8 @@ def load_library() -> C.CDLL:
     lib.sp_pool_select_workspace_bytes.argtypes = [C.POINTER(PoolSelectArgs)]
     lib.sp_pool_select.restype = C.c_int
     lib.sp_pool_select.argtypes = [C.POINTER(PoolSelectArgs), C.c_void_p]
+    lib.sp_pool_select_static.restype = C.c_int
+    lib.sp_pool_select_static.argtypes = [C.POINTER(PoolSelectArgs), C.c_void_p]
     lib.sp_gather.restype = C.c_int
     lib.sp_gather.argtypes = [C.POINTER(GatherArgs), C.c_void_p]
     lib.sp_strerror.restype = C.c_char_p
@@ -223,6 +225,14 @@ def sp_pool_select_workspace_bytes(args: PoolSelectArgs) -> int:
 
 def sp_pool_select(args: PoolSelectArgs, stream=None) -> None:
     _check("sp_pool_select", load_library().sp_pool_select(C.byref(args), _stream_handle(stream)))
+
+
+SP_STATIC_MAX_SEQS, SP_STATIC_MAX_CHUNKS = 4096, 131072
+
+
+def sp_pool_select_static(args: PoolSelectArgs, stream=None) -> None:
+    """sp_pool_select on the library's built-in scratch space (no workspace, nothing allocated)."""
+    _check("sp_pool_select_static", load_library().sp_pool_select_static(C.byref(args), _stream_handle(stream)))
 
 
 # ----------------------------------------------------------------------------

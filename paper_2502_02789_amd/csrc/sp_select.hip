@@ -7,6 +7,8 @@
 // divides only, so the chunk scores (and therefore the kept set) do not depend on how the
 // work is split over lanes.  Top-k is an 8-pass radix select on order-preserving 64-bit
 // keys followed by an ordered scan that resolves equal scores to the lower chunk index.
+#include <mutex>
+
 #include "sp_common.h"
 
 // the k formula below must stay a separate multiply and subtract
@@ -420,4 +422,48 @@ extern "C" sp_status sp_pool_select(const sp_pool_select_args* a, void* hip_stre
   if (!a->d_workspace || a->workspace_bytes < sp_pool_select_workspace_bytes(a)) return SP_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(a->d_workspace) & 255u) return SP_EALIGN;
   return run_pool_select(a, a->d_workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---------------------------------------------------------------------------------------
+// the variant for callers that cannot allocate: scratch space inside the library's image
+// ---------------------------------------------------------------------------------------
+// One copy per GPU (each device that loads the library's code object gets its own), alive until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[SP_STATIC_SCRATCH_BYTES];
+
+namespace sp {
+
+// device address of `scratch` on the current GPU, looked up once per device
+static void* static_scratch_address() {
+  static std::mutex mu;
+  static void* address[kMaxDevices] = {};
+  std::lock_guard<std::mutex> lock(mu);
+  const int slot = current_device();
+  if (!address[slot]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    address[slot] = ptr;
+  }
+  return address[slot];
+}
+
+}  // namespace sp
+
+extern "C" sp_status sp_pool_select_static(const sp_pool_select_args* a, void* hip_stream) {
+  using namespace sp;
+  const sp_status st = check_select_args(a);
+  if (st != SP_OK) return st;
+  if (a->B > SP_STATIC_MAX_SEQS || select_max_chunks(a) > (size_t)SP_STATIC_MAX_CHUNKS) return SP_EUNSUPPORTED;
+  static_assert(256 * ((4 * ((size_t)SP_STATIC_MAX_SEQS + 1) + 255) / 256) + 256 * ((4 * (size_t)SP_STATIC_MAX_SEQS + 255) / 256) +
+                        12 * (size_t)SP_STATIC_MAX_CHUNKS + 512 <= SP_STATIC_SCRATCH_BYTES,
+                "the static scratch must hold the largest workspace the limits allow");
+  if (sp_pool_select_workspace_bytes(a) > SP_STATIC_SCRATCH_BYTES) return SP_EUNSUPPORTED;
+  void* ptr = static_scratch_address();
+  if (!ptr) return SP_ELAUNCH;
+  // nothing in the scratch has to start at zero: every word the kernels read was written earlier
+  // in the same call (chunk table, chunk scores, per-chunk offsets, per-sequence counts)
+  return run_pool_select(a, ptr, static_cast<hipStream_t>(hip_stream));
 }
