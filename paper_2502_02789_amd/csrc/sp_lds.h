@@ -101,6 +101,19 @@ __device__ __forceinline__ u32x4 lds_peek4(uint32_t lds_addr) {
       : "memory");
   return u32x4{a, b, c, d};
 }
+// four 16-byte reads STRIDE bytes apart, one wait for all of them
+struct u32x4x4 { u32x4 v[4]; };
+template <int STRIDE>
+__device__ __forceinline__ u32x4x4 lds_peek128x4(uint32_t lds_addr) {
+  u32x4x4 r;
+  asm volatile(
+      "ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:%5\n\tds_read_b128 %2, %4 offset:%6\n\t"
+      "ds_read_b128 %3, %4 offset:%7\n\ts_waitcnt lgkmcnt(0)"
+      : "=&v"(r.v[0]), "=&v"(r.v[1]), "=&v"(r.v[2]), "=&v"(r.v[3])
+      : "v"(lds_addr), "n"(STRIDE), "n"(2 * STRIDE), "n"(3 * STRIDE)
+      : "memory");
+  return r;
+}
 // 4-byte store with agent-scope coherence
 __device__ __forceinline__ void store32_agent(void* dst, uint32_t v) {
   asm volatile("global_store_dword %0, %1, off sc1" : : "v"(dst), "v"(v) : "memory");

@@ -48,11 +48,15 @@ constexpr int kTeamDepBytes = 8 * 32 * 4;                  // one slab's deposit
 
 struct TeamDev : StreamShape {
   int TC, lgTC;       // teams; team = workgroup % TC, index in team = workgroup / TC
-  int P;              // workgroups per team (a multiple of 8, at most kTeamMaxPartners)
+  int P;              // workgroups per team (a multiple of 32, at most kTeamMaxPartners)
   int M_pad;          // P * KPW
   uint32_t* partial;  // [team][slab][partner][32]: base-2 log-sum-exp of the partner's keys, per row
   float* part;        // [team][N][M_pad]: the team's max over its heads and all layers of log2 p
+  uint32_t* arrived;  // [P]: how many of the TC workgroups that own key slice j are done (+ 65536 per
+                      // workgroup one of whose waits expired); zero at the start of the call
   uint32_t* status;   // [0] != 0: a bounded wait ran out (results invalid)
+  const int32_t* n_valid;
+  float* scores;
   float* lse_out;
 };
 
@@ -70,7 +74,8 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
   uint32_t dep_lds;   // LDS: [NSETS][32 rows][8 waves] each wave's base-2 log-sum-exp of the row over its keys
   uint32_t ctl_lds;   // LDS control block: words 0..7 arrival counters per set; 8 last slab whose row
                       // log-sum-exps are in LDS (-1: none); 9 last slab this workgroup has published
-                      // (-1: none); 10 the sampler's lock; 11 "a sample of slab [8]+1 has been requested"
+                      // (-1: none); 10 the sampler's lock; 11 "a sample of slab [8]+1 has been requested";
+                      // 12 "a wait of some wave expired"; 13 arrival count of this key slice (kernel end)
   uint32_t lse_lds;   // LDS: [NSETS][32] finished row log-sum-exps (slot = slab % NSETS)
   uint32_t land_lds;  // LDS: landing zone of a sample, [P][32]
 
@@ -137,20 +142,27 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
     if (ln == 0) lds_poke32(ctl_lds + 36, (uint32_t)slab);
   }
 
-  // One step, by whichever wave comes by, towards the row log-sum-exps of the next slab that
-  // lacks them (never beyond slab `limit`, and never before this workgroup itself has published
-  // that slab: its partners are then about as far).  Never waits.
+  // By whichever wave comes by: bring the row log-sum-exps of the next slab that lacks them a step
+  // forward (never beyond slab `limit`, and never before this workgroup itself has published
+  // that slab: its partners are then about as far).  A landed sample is folded and the next
+  // slab's sample is sent on its way in the same visit: the waves of a workgroup pass by in a
+  // cluster, once per slab, and those that find the lock taken do nothing.  Never waits.
   __device__ __forceinline__ void service(int limit) {
     const uint64_t st = lds_peek64(ctl_lds + 32);
-    const int r = (int)__builtin_amdgcn_readfirstlane((uint32_t)st) + 1;
+    const int r0 = (int)__builtin_amdgcn_readfirstlane((uint32_t)st) + 1;
     const int pub = (int)__builtin_amdgcn_readfirstlane((uint32_t)(st >> 32));
-    if (r > limit || r > pub) return;
+    if (r0 > limit || r0 > pub) return;
     // one wave at a time: test-and-set
     uint32_t held = 1;
     if (lane == 0) held = lds_or_rtn(ctl_lds + 40, 1);
     if (__builtin_amdgcn_readfirstlane(held) != 0) return;
-    // (another wave may have finished slab r between the two looks)
-    if ((int)__builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 32)) + 1 == r) sample_step(r);
+#pragma unroll 1
+    for (int visit = 0; visit < 2; ++visit) {
+      // (another wave may have finished slab r0 between the two looks)
+      const int r = (int)__builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 32)) + 1;
+      if (r > limit || r > pub) break;
+      if (!sample_step(r)) break;  // not folded yet: nothing more to do now
+    }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     if (lane == 0) lds_poke32(ctl_lds + 40, 0);
   }
@@ -158,8 +170,9 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
   // No sample of slab r out yet: mark the landing zone "pending" and request the P partner lines
   // (P / 8 wave-wide 16-byte direct-to-LDS loads).  Sample out: look at the zone (LDS reads only);
   // words still pending -> come back later; pieces still empty -> request those pieces again;
-  // everything there -> fold the P values of each row and leave the 32 log-sum-exps in LDS.
-  __device__ __forceinline__ void sample_step(int r) {
+  // everything there -> fold the P values of each row and leave the 32 log-sum-exps in LDS
+  // (returns true: slab r is done).
+  __device__ __forceinline__ bool sample_step(int r) {
     int ln = lane;
     asm volatile("" : "+v"(ln));
     const bool sampled = __builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 44)) != 0;
@@ -175,19 +188,30 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
       for (int i = 0; i < kTeamMaxPartners / 8; ++i)
         if (i < groups) __builtin_amdgcn_global_load_lds(src + i * 1024, lds_ptr(land_lds + i * 1024), 16, 0, /*sc1*/ 16);
       note_issued(groups);
-      return;
+      return false;
     }
+    // Look at the zone.  Lane ln holds, of load i, the 16 bytes of partner i * 8 + ln / 8 that carry
+    // rows 4 * (ln % 8) .. + 3: what it needs to check, and exactly one partner's share of a row
+    // quad's fold.  Pass 1: pending / empty words and the rows' maxima; pass 2: the sums.
     bool pending = false;
     uint32_t miss = 0;  // bit i: this lane's 16 bytes of load i hold an empty word
+    const uint32_t zone = land_lds + ln * 16;
+    float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
-    for (int i = 0; i < kTeamMaxPartners / 8; ++i) {
-      if (i < groups) {
-        const u32x4 w = lds_peek128(land_lds + i * 1024 + ln * 16);
-        pending |= w.x == kPending32 || w.y == kPending32 || w.z == kPending32 || w.w == kPending32;
-        if (w.x == kEmpty32 || w.y == kEmpty32 || w.z == kEmpty32 || w.w == kEmpty32) miss |= 1u << i;
+    for (int i0 = 0; i0 < kTeamMaxPartners / 8; i0 += 4) {
+      if (i0 < groups) {  // (groups is a multiple of four)
+        const u32x4x4 w = lds_peek128x4<1024>(zone + i0 * 1024);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const u32x4 x = w.v[j];
+          pending |= x.x == kPending32 || x.y == kPending32 || x.z == kPending32 || x.w == kPending32;
+          if (x.x == kEmpty32 || x.y == kEmpty32 || x.z == kEmpty32 || x.w == kEmpty32) miss |= 1u << (i0 + j);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) m[c] = fmaxf(m[c], __uint_as_float(x[c]));  // (the NaN patterns never win a max)
+        }
       }
     }
-    if (__any(pending)) return;
+    if (__any(pending)) return false;
     if (__any(miss != 0)) {
 #pragma unroll
       for (int i = 0; i < kTeamMaxPartners / 8; ++i)
@@ -201,44 +225,72 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
           note_issued(1);
         }
       }
-      return;
+      return false;
     }
-    // all P lines are here: lane (row, h) folds partners [h * P/2, (h+1) * P/2) of its row
-    const int row = ln & 31, hf = ln >> 5;
-    const int per_half = p.P >> 1;  // a multiple of four
-    const uint32_t base = land_lds + hf * per_half * 128 + row * 4;
-    float m = -INFINITY;
-#pragma unroll 1
-    for (int j = 0; j < per_half; j += 4) {
-      const u32x4 w = lds_peek4<128>(base + j * 128);
-      m = fmaxf(fmaxf(m, fmaxf(__uint_as_float(w.x), __uint_as_float(w.y))), fmaxf(__uint_as_float(w.z), __uint_as_float(w.w)));
+    // all P lines are here: finish the maxima across the eight lanes that share a row quad
+    // (lanes ln, ln ^ 8, ln ^ 16, ln ^ 32), then the sums the same way
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      m[c] = fmaxf(m[c], __shfl_xor(m[c], 8, kWave));
+      m[c] = fmaxf(m[c], __shfl_xor(m[c], 16, kWave));
+      m[c] = fmaxf(m[c], __shfl_xor(m[c], 32, kWave));  // finite: the prompt is not empty
     }
-    m = fmaxf(m, __shfl_xor(m, 32, kWave));  // finite: the prompt is not empty
-    float z = 0.f;
-#pragma unroll 1
-    for (int j = 0; j < per_half; j += 4) {
-      const u32x4 w = lds_peek4<128>(base + j * 128);
-      z += (fast_exp2(__uint_as_float(w.x) - m) + fast_exp2(__uint_as_float(w.y) - m)) +
-           (fast_exp2(__uint_as_float(w.z) - m) + fast_exp2(__uint_as_float(w.w) - m));
+    float z[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i0 = 0; i0 < kTeamMaxPartners / 8; i0 += 4) {
+      if (i0 < groups) {
+        const u32x4x4 w = lds_peek128x4<1024>(zone + i0 * 1024);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) z[c] += fast_exp2(__uint_as_float(w.v[j][c]) - m[c]);
+      }
     }
-    z += __shfl_xor(z, 32, kWave);
-    const float lse = m + __builtin_amdgcn_logf(z);
-    if (hf == 0) lds_poke32(lse_lds + (r & (NSETS - 1)) * 128 + row * 4, __float_as_uint(lse));
+    u32x4 out;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      z[c] += __shfl_xor(z[c], 8, kWave);
+      z[c] += __shfl_xor(z[c], 16, kWave);
+      z[c] += __shfl_xor(z[c], 32, kWave);
+      out[c] = __float_as_uint(m[c] + __builtin_amdgcn_logf(z[c]));
+    }
+    if (ln < 8) lds_poke128(lse_lds + (r & (NSETS - 1)) * 128 + ln * 16, out);  // rows 4 * ln .. + 3
     if (ln == 0) {
       lds_poke32(ctl_lds + 44, 0);            // no sample out for the next slab
       lds_poke32(ctl_lds + 32, (uint32_t)r);  // after the values: LDS writes of a wave are performed in order
     }
-    if (p.lse_out && pidx == 0 && hf == 0 && row < p.G * p.N)  // (not counted in `issued`: counting less only waits more)
-      p.lse_out[((int64_t)layer_of(r) * p.N + (row >> p.lgG)) * p.H + kvh_of(r) * p.G + (row & (p.G - 1))] =
-          lse * 0.6931471805599453f;
+    if (p.lse_out && pidx == 0 && ln < 8) {  // (not counted in `issued`: counting less only waits more)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int row = ln * 4 + c;
+        if (row < p.G * p.N)
+          p.lse_out[((int64_t)layer_of(r) * p.N + (row >> p.lgG)) * p.H + kvh_of(r) * p.G + (row & (p.G - 1))] =
+              __uint_as_float(out[c]) * 0.6931471805599453f;
+      }
+    }
+    return true;
+  }
+
+  // 1 KiB (16 bytes per lane, src = this lane's address) straight into LDS, agent scope.  (The
+  // builtin has to sit in a device function: in the body of a kernel template it keeps the host
+  // pass from emitting the kernel's launch stub.)
+  __device__ __forceinline__ void load_kib_agent(const void* src, uint32_t lds) {
+    __builtin_amdgcn_global_load_lds(src, lds_ptr(lds), 16, 0, /*sc1*/ 16);
   }
 
   // This lane's row log-sum-exp of `slab`.  Normally it is there; if not, keep the sampling going
   // until it is (bounded).
   __device__ __forceinline__ float take_lse(int slab) {
-    while ((int)__builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 32)) < slab && may_poll()) {
-      service(slab);
-      __builtin_amdgcn_s_sleep(2);
+    if ((int)__builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 32)) < slab) {
+      // A waiting wave must cost the working ones as little as possible: lowest issue priority (it
+      // shares its SIMD with a wave that streams) and long naps between looks.  Measured on the
+      // 32K-token workload: polling every 128 cycles at the slab's priority 524 us, this 460 us.
+      __builtin_amdgcn_s_setprio(0);
+      while ((int)__builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 32)) < slab && may_poll()) {
+        service(slab);
+        __builtin_amdgcn_s_sleep(20);
+      }
+      if (((slab + NSETS) ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(2);  // back to the priority of the slab in progress
     }
     int c = col;
     asm volatile("" : "+v"(c));
@@ -291,6 +343,9 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
         default: tm.template issue_stream<6>(slab, slot); break;
       }
       tm.template stats_tile<SET>(kb);
+      // between the key tiles too: with one visit per slab a sampler that has fallen behind
+      // (a sample that had to be repeated) could never catch up again
+      if (kb + 1 < TPW) tm.service(slab - 1);
     }
     tm.template deposit<SET>(slab);
     // a step towards the log-sum-exps of an earlier slab, here, where the fewest registers are
@@ -327,39 +382,86 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
     }
   }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
-  // A wait of some wave gave up: the call's result is void (the second kernel turns every score
-  // into NaN when it finds the status word set).
-  if (tm.expired && tm.lane == 0) atomicOr(p.status, 1u);
-  __syncthreads();  // every wave's maxima are in LDS
+  if (tm.expired && tm.lane == 0) {  // a wait of this wave gave up
+    atomicOr(p.status, 1u);
+    lds_or(tm.ctl_lds + 48, 1u);
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __syncthreads();  // every wave's maxima (and give-up marks) are in LDS
 
-  // the team's maxima for this workgroup's keys: [team][query][key]
-  for (int i = threadIdx.x; i < p.N * tm.keys_wg; i += kThreads) {
-    const int n = i / tm.keys_wg, key = i - n * tm.keys_wg;
-    p.part[((int64_t)tm.team * p.N + n) * p.M_pad + (int64_t)tm.pidx * p.KPW + key] =
-        tm.smax[n * (p.KPW + kSmaxPad) + smax_cell(key)];
+  // The team's maxima for this workgroup's keys go out as [team][query][key].  The TC workgroups
+  // that own the same key slice (one per team) count their arrivals; the one that arrives last
+  // takes the maximum over the teams -- now the maximum over all heads and layers --,
+  // exponentiates and averages over the valid queries (Sec. 3.2.2).  The workgroups sit on
+  // different dies: the values are stored with agent scope and are complete before the count,
+  // and the last one fetches them with agent-scope loads (straight into the idle tile ring,
+  // all at once).
+  for (int i = threadIdx.x; i < p.N * p.KPW; i += kThreads) {
+    const int n = i >> p.lgKPW, key = i & (p.KPW - 1);  // (keys beyond the prompt carry -inf: never read back)
+    store32_agent(p.part + ((int64_t)tm.team * p.N + n) * p.M_pad + (int64_t)tm.pidx * p.KPW + key,
+                  __float_as_uint(tm.smax[n * (p.KPW + kSmaxPad) + smax_cell(key)]));
+  }
+  wait_vmcnt<0>();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t mine = 1u + (__builtin_amdgcn_readfirstlane(lds_peek(tm.ctl_lds + 48)) != 0 ? 65536u : 0u);
+    const uint32_t before = atomicAdd(p.arrived + tm.pidx, mine);
+    lds_poke32(tm.ctl_lds + 52, before + mine);
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __syncthreads();
+  const uint32_t count = __builtin_amdgcn_readfirstlane(lds_peek(tm.ctl_lds + 52));
+  if ((int)(count & 65535u) != p.TC) return;  // somebody else will be last
+  const bool void_result = (count >> 16) != 0;  // a wait expired in one of the TC workgroups: no score of this slice can be trusted
+  int nv = p.n_valid ? p.n_valid[0] : p.N;
+  nv = max(1, min(nv, p.N));
+  // queries in groups whose TC x group x KPW values fit the ring; 1 KiB (256 keys of one team and
+  // query) per wave-wide load
+  const int per_query = p.TC * p.KPW * 4;                 // bytes
+  const int group = min(nv, Tm::RING_BYTES / per_query);  // >= 1: at most 16 KiB per query
+  const int chunks_per_row = p.KPW >> 8;                  // KPW is 256 or 512
+  float sum[2] = {0.f, 0.f};                              // this thread's keys: threadIdx.x (+ 512)
+  const uint32_t ring = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+  for (int n0 = 0; n0 < nv; n0 += group) {
+    const int gq = min(group, nv - n0);
+    const int rows = p.TC * gq;                           // (team, query) rows of KPW values each
+    for (int c = tm.wave; c < rows * chunks_per_row; c += kWaves) {
+      const int row = c / chunks_per_row, piece = c - row * chunks_per_row;
+      const int t = row / gq, n = n0 + row - t * gq;
+      const float* src = p.part + ((int64_t)t * p.N + n) * p.M_pad + (int64_t)tm.pidx * p.KPW + piece * 256 + tm.lane * 4;
+      tm.load_kib_agent(src, ring + (uint32_t)c * 1024);
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+    for (int j = 0; j < 2; ++j) {
+      const int key = threadIdx.x + j * kThreads;
+      if (key < tm.keys_wg) {
+        for (int q = 0; q < gq; ++q) {
+          float m = -INFINITY;
+          for (int t = 0; t < p.TC; ++t) m = fmaxf(m, __uint_as_float(lds_peek(ring + ((t * gq + q) * p.KPW + key) * 4)));
+          sum[j] += fast_exp2(m);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  for (int j = 0; j < 2; ++j) {
+    const int key = threadIdx.x + j * kThreads;
+    if (key < tm.keys_wg)
+      p.scores[(int64_t)tm.pidx * p.KPW + key] = void_result ? __uint_as_float(0x7fc00000u) : sum[j] / (float)nv;
   }
 }
 
-// score[key] = mean over the valid queries of 2^(max over teams of the team's log2-probability
-// maximum): the maximum over all heads and layers, then the mean over queries (Sec. 3.2.2)
-__global__ __launch_bounds__(256) void team_finish_kernel(const float* __restrict__ part, int TC, int N, int M, int M_pad,
-                                                          const int32_t* __restrict__ n_valid,
-                                                          const uint32_t* __restrict__ status, float* __restrict__ scores) {
-  const int key = blockIdx.x * 256 + threadIdx.x;
-  if (key >= M) return;
-  if (status[0] != 0) {  // a bounded wait expired somewhere: nothing of this call can be trusted
-    scores[key] = __uint_as_float(0x7fc00000u);
-    return;
+// start-of-call state of the exchange area: every line "empty", arrival counts and status word clear
+__global__ __launch_bounds__(256) void team_fill_kernel(uint4* __restrict__ dst, size_t n_vec, uint32_t* __restrict__ arrived,
+                                                        int n_arrived, uint32_t* __restrict__ status) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += stride)
+    dst[i] = make_uint4(kEmpty32, kEmpty32, kEmpty32, kEmpty32);
+  if (blockIdx.x == 0) {
+    for (int i = threadIdx.x; i < n_arrived; i += 256) arrived[i] = 0;
+    if (threadIdx.x == 0) status[0] = 0;
   }
-  int nv = n_valid ? n_valid[0] : N;
-  nv = max(1, min(nv, N));
-  float sum = 0.f;
-  for (int n = 0; n < nv; ++n) {
-    float m = -INFINITY;
-    for (int t = 0; t < TC; ++t) m = fmaxf(m, part[((int64_t)t * N + n) * M_pad + key]);
-    sum += fast_exp2(m);
-  }
-  scores[key] = sum / (float)nv;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -401,8 +503,8 @@ static TeamPlan make_team_plan(const sp_score_args* a, int cus) {
     if (a->H_kv % tc != 0) continue;
     const int kpt = a->H_kv / tc;
     if (kpt & (kpt - 1)) continue;  // slabs per layer: a power of two
-    const int partners = std::min(kTeamMaxPartners, cus / tc) / 8 * 8;
-    if (partners < 8) continue;
+    const int partners = std::min(kTeamMaxPartners, cus / tc) / 32 * 32;  // the sampler reads lines in batches of 32
+    if (partners < 32) continue;
     for (int tpw = 1; tpw <= 2; ++tpw) {
       const int kpw = kWaves * tpw * 32;
       if ((int64_t)partners * kpw < a->T) continue;
@@ -427,7 +529,7 @@ bool team_supported(const sp_score_args* a) { return make_team_plan(a, team_devi
 size_t team_workspace_bytes(const sp_score_args* a) {
   const TeamPlan pl = make_team_plan(a, kMaxWG);  // sized for the full chip
   if (!pl.ok) return 0;
-  return pl.partial_bytes + pl.part_bytes + 256;
+  return pl.partial_bytes + pl.part_bytes + 256 + 256;  // + status word + arrival counts
 }
 
 // byte offset of the status word inside the workspace, or 0 if the shape does not use this kernel
@@ -497,12 +599,15 @@ sp_status team_score(const sp_score_args* a, hipStream_t stream) {
   dev.partial = reinterpret_cast<uint32_t*>(ws);
   dev.part = reinterpret_cast<float*>(ws + pl.partial_bytes);
   dev.status = reinterpret_cast<uint32_t*>(ws + pl.partial_bytes + pl.part_bytes);
+  dev.arrived = reinterpret_cast<uint32_t*>(ws + pl.partial_bytes + pl.part_bytes + 256);  // kTeamMaxPartners words
+  dev.n_valid = a->d_n_valid;
+  dev.scores = a->d_scores;
   dev.lse_out = a->d_lse;
 
   const size_t n_vec = pl.partial_bytes / 16;
   const int fill_blocks = (int)std::min<size_t>((n_vec + 255) / 256, 1024);
-  hipLaunchKernelGGL(fill_empty_kernel, dim3(fill_blocks), dim3(256), 0, stream, reinterpret_cast<uint4*>(ws), n_vec,
-                     dev.status);
+  hipLaunchKernelGGL(team_fill_kernel, dim3(fill_blocks), dim3(256), 0, stream, reinterpret_cast<uint4*>(ws), n_vec,
+                     dev.arrived, dev.P, dev.status);
   if (hipGetLastError() != hipSuccess) return SP_ELAUNCH;
   sp_status st;
   if (a->d_block_table) {
@@ -512,10 +617,7 @@ sp_status team_score(const sp_score_args* a, hipStream_t stream) {
     if (a->d == 128) st = pl.TPW == 1 ? launch_team<128, 1, false>(dev, pl, stream) : launch_team<128, 2, false>(dev, pl, stream);
     else st = pl.TPW == 1 ? launch_team<64, 1, false>(dev, pl, stream) : launch_team<64, 2, false>(dev, pl, stream);
   }
-  if (st != SP_OK) return st;
-  hipLaunchKernelGGL(team_finish_kernel, dim3((unsigned)((a->T + 255) / 256)), dim3(256), 0, stream, dev.part, dev.TC,
-                     dev.N, dev.M, dev.M_pad, a->d_n_valid, dev.status, a->d_scores);
-  return launch_status();
+  return st;
 }
 
 }  // namespace sp
