@@ -493,6 +493,10 @@ static TeamPlan make_team_plan(const sp_score_args* a, int cus) {
   pl.ok = false;
   const int G = a->H / a->H_kv;
   if (a->B != 1 || a->T < 1 || a->layer_reduce != SP_LAYER_MAX) return pl;
+  // Where both single-pass kernels fit, this one is taken where it was measured to be the faster
+  // (16 layers, 8 look-ahead rows; team / all-workgroup kernel, us): head dim 128: 8K keys 90 / 83,
+  // 12K 109 / 113, 16K 126 / 135, 32K 218 / 230; head dim 64: 8K 75 / 64, 16K 86 / 84, 32K 163 / 158.
+  if (a->d != 128 || a->T <= 8192) return pl;
   if (a->rope_theta != 0.f) return pl;  // un-rotated caches take the general kernels
   if (G != 1 && G != 2 && G != 4 && G != 8) return pl;
   if (G * a->N > 32) return pl;

@@ -67,7 +67,7 @@ def test_valid_query_count_on_one_long_prompt(n_valid, mode, paged):
     """One prompt, eight KV heads, eight look-ahead rows of which only the first n_valid count
     (Sec. 3.3: look-ahead tokens after an end-of-sequence are not valid): the shape the single-pass
     kernels take, contiguous and behind a block table, against the oracle."""
-    w = synth.scaled(synth.workload(3), seqlens=(6000 + 13,), L=3)
+    w = synth.scaled(synth.workload(3), seqlens=(9000 + 13,), L=3)   # (long enough for either single-pass kernel)
     inp = synth.make_qk(w)
     scale = 1.0 / math.sqrt(w.d)
     nv = np.array([n_valid], dtype=np.int32)
@@ -201,14 +201,15 @@ def test_one_long_prompt_without_the_exclusive_device_promise(mode):
     np.testing.assert_allclose(lse, want_lse, rtol=0, atol=2e-4)
 
 
-def test_expired_wait_is_impossible_to_miss():
-    """The single-pass kernel's waits for other workgroups are bounded.  With the bound set to
+@pytest.mark.parametrize("tokens", [4096 + 40, 9000])     # the all-workgroup kernel / the team kernel
+def test_expired_wait_is_impossible_to_miss(tokens):
+    """The single-pass kernels' waits for other workgroups are bounded.  With the bound set to
     zero from the host every wait gives up at once (all kernels still run to their end): the scores
     must then be NaN, sp_score_check must report SP_ETIMEOUT, and selection and gather must hand on
     no keep set.  With the bound restored the same objects give the oracle's result again."""
     import torch
     from paper_2502_02789_amd import binding as sp, device as dev
-    w = synth.scaled(synth.workload(3), seqlens=(4096 + 40,), L=3)
+    w = synth.scaled(synth.workload(3), seqlens=(tokens,), L=3)
     inp = synth.make_qk(w)
     scale = 1.0 / math.sqrt(w.d)
     q = dev.bf16_from_bits(inp["q"])
@@ -242,6 +243,27 @@ def test_expired_wait_is_impossible_to_miss():
     want, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, orc.LAYER_MAX)
     hp.assert_scores_close(s.scores.cpu().numpy(), want, "after the bound was restored")
     assert int(sel.cu_keep[1]) > 0 and (gat.kept_pos[:int(sel.cu_keep[1])] >= 0).all()
+
+
+@pytest.mark.parametrize("shape", [
+    dict(tokens=9001, H=32, H_kv=8, N=8),      # eight teams, two key tiles per wave and slab, ragged tail
+    dict(tokens=16384, H=8, H_kv=8, N=8),      # one query head per KV head, exactly full
+    dict(tokens=20011, H=16, H_kv=8, N=3),     # four teams of 64 workgroups, two heads per KV head
+    dict(tokens=11000, H=64, H_kv=8, N=4),     # eight heads per KV head
+    dict(tokens=10007, H=16, H_kv=4, N=8),     # four KV heads: four teams, one KV head each
+    dict(tokens=9500, H=32, H_kv=16, N=2),     # sixteen KV heads: two per team
+])
+def test_team_kernel_shapes(shape):
+    """One prompt of 8K..32K keys, head dim 128, SP_LAYER_MAX: the kernel whose workgroups form teams
+    per group of KV heads, in each of its team / tile configurations, against the oracle; twice on
+    one workspace, bitwise equal."""
+    tokens = shape.pop("tokens")
+    w = synth.scaled(synth.workload(3), seqlens=(tokens,), L=3, **shape)
+    inp = synth.make_qk(w)
+    a = _check(w, inp, orc.LAYER_MAX, general=False)
+    got1, lse1 = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, 1.0 / math.sqrt(w.d), orc.LAYER_MAX)
+    got2, lse2 = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, 1.0 / math.sqrt(w.d), orc.LAYER_MAX)
+    assert np.array_equal(got1, got2) and np.array_equal(lse1, lse2)
 
 
 def _raw_inputs(seed, seqlens, L, H, H_kv, d, N):
