@@ -15,6 +15,8 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libspecprefill.so")
+PROBE_SRC = os.path.join(PKG_DIR, "csrc_probe", "sp_probe.hip")
+PROBE_LIB_PATH = os.path.join(PKG_DIR, "libspprobe.so")     # the benchmark's read-only probes, a library of its own
 
 COMMON_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -78,6 +80,13 @@ def build_library(verbose: bool = False, extra_flags=(), lib_path: str = LIB_PAT
     return lib_path
 
 
+def build_probe(verbose: bool = False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _run([hipcc, *COMMON_FLAGS, "-shared", "-I", os.path.join(ROOT, "include"), PROBE_SRC, "-o", PROBE_LIB_PATH], verbose)
+    return PROBE_LIB_PATH
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True, incremental="--incremental" in sys.argv[1:]))
+    print(build_probe(verbose=True))
     sys.exit(0)

@@ -478,14 +478,16 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
     }
     __syncthreads();
   }
-  for (int key = threadIdx.x; key < st.keys_wg; key += kThreads) {
+  for (int key = threadIdx.x; key < p.KPW; key += kThreads) {
+    const int token = st.key_of_local(key);
+    if (token >= p.M) continue;
     float sum = 0.f;
     for (int n = 0; n < nv; ++n) {
       const float v = st.smax[n * (p.KPW + kSmaxPad) + smax_cell(key)];
       sum += MEAN ? v : fast_exp2(v);
     }
     const float denom = MEAN ? (float)nv * (float)p.L : (float)nv;
-    p.scores[(int64_t)blockIdx.x * p.KPW + key] = gave_up ? __uint_as_float(0x7fc00000u) : sum / denom;
+    p.scores[token] = gave_up ? __uint_as_float(0x7fc00000u) : sum / denom;
   }
   if (gave_up && threadIdx.x == 0) atomicOr(p.status, 1u);
 }
@@ -615,6 +617,7 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   dev.slabs_per_layer = pl.slabs_per_layer; dev.n_slabs = pl.n_slabs; dev.KPW = pl.KPW; dev.nwg = pl.nwg;
   dev.lgKPW = 0;
   while ((1 << dev.lgKPW) < pl.KPW) ++dev.lgKPW;
+  dev.own_step = pl.KPW; dev.tile_step = 32;  // every workgroup one run of KPW keys (and all KV heads of them)
   dev.wpr = pl.wpr; dev.layer_reduce = a->layer_reduce;
   dev.spin_budget = g_spin_budget.load(std::memory_order_relaxed);
   dev.c = a->scale * 1.4426950408889634f;

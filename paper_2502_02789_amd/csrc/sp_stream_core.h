@@ -36,6 +36,9 @@ struct StreamShape {
   int slabs_per_layer, lgSPL;    // slabs per layer (of this workgroup's sequence of slabs)
   int n_slabs;
   int KPW, lgKPW;                // keys owned by a workgroup
+  int own_step, tile_step;       // key tile x of owner o starts at key o * own_step + x * tile_step: (KPW, 32) gives
+                                 // every workgroup one run of KPW keys, (32, owners * 32) deals the 32-key
+                                 // tiles out to the workgroups in turn
   int spin_budget;               // polls a wave may spend waiting for other workgroups over the whole call
   float c;                       // scale * log2(e): logits are handled in the base-2 domain
   int64_t ts, hs;                // token / head stride of the K cache, elements
@@ -82,10 +85,9 @@ struct StreamCore {
   const StreamShape& p;
   float* smax;           // [N][KPW + kSmaxPad] running max of log2-probabilities (cells: smax_cell)
   int wave, lane, half, col;
-  int owner;             // which KPW-slice of the prompt this workgroup owns
+  int owner;             // which share of the prompt's key tiles this workgroup owns (see own_step, tile_step)
   int kvh_base;          // first KV head of this workgroup's sequence of slabs
   int kvh_local, kbg;    // this wave's KV head inside a slab, and its group of key tiles
-  int keys_wg;           // valid keys owned by this workgroup
   int budget;            // polls left; a wait that finds it used up gives up and sets `expired`
   bool expired;
   int issued;            // vector-memory instructions issued so far by this wave (never over-counted)
@@ -111,7 +113,6 @@ struct StreamCore {
     kvh_local = wave & (p.S - 1);
     kbg = wave >> p.lgS;
     ring_lds = ring_base + wave * 2 * TILE_B;
-    keys_wg = max(0, min(p.KPW, p.M - owner * p.KPW));
     budget = p.spin_budget;
     expired = false;
     issued = 0;
@@ -144,6 +145,12 @@ struct StreamCore {
     return false;
   }
 
+  // first key (in the prompt) of this workgroup's key tile x; of this wave's tile kb
+  __device__ __forceinline__ int tile_key(int x) const { return owner * p.own_step + x * p.tile_step; }
+  __device__ __forceinline__ int wave_tile_key(int kb) const { return tile_key(kbg * TPW + kb); }
+  // prompt key of the workgroup's local key number `local` (tile local / 32, position local % 32)
+  __device__ __forceinline__ int key_of_local(int local) const { return tile_key(local >> 5) + (local & 31); }
+
   __device__ __forceinline__ int layer_of(int slab) const { return slab >> p.lgSPL; }
   __device__ __forceinline__ int kvh_of(int slab) const {
     return kvh_base + ((slab & (p.slabs_per_layer - 1)) << p.lgS) + kvh_local;
@@ -153,7 +160,7 @@ struct StreamCore {
   // wave-wide loads (the vmcnt bookkeeping counts on it): rows beyond the prompt re-read row 0
   // of the last in-range tile and are masked later.
   __device__ __forceinline__ void issue_keys(int slab, int kb, int slot) {
-    int key_start = owner * p.KPW + (kbg * TPW + kb) * 32;
+    int key_start = wave_tile_key(kb);
     // keep the address arithmetic at its point of use: hoisted out of the slab loop it would
     // pin dozens of registers for the whole kernel
     asm volatile("" : "+s"(key_start));
@@ -293,9 +300,9 @@ struct StreamCore {
   template <int SET>
   __device__ __forceinline__ void stats_tile(int kb) {
     f32x16& a = acc[SET][kb];
-    const int first = (kbg * TPW + kb) * 32;
-    if (first + 32 > keys_wg) {  // ragged tail: keys beyond the prompt do not count
-      int left = keys_wg - first - half * 4;  // keys of this half-wave's first register still inside
+    const int inside = p.M - wave_tile_key(kb);  // keys of this tile that belong to the prompt (may be <= 0 or >= 32)
+    if (inside < 32) {  // ragged tail: keys beyond the prompt do not count
+      int left = inside - half * 4;  // keys of this half-wave's first register still inside
       asm volatile("" : "+v"(left));           // compare here, when needed: 16 hoisted lane masks would cost 32 SGPRs
 #pragma unroll
       for (int i = 0; i < 16; ++i)
@@ -358,9 +365,9 @@ struct StreamCore {
 #pragma unroll
         for (int i = 0; i < 16; ++i) x[i] = fmaxf(x[i], __shfl_xor(x[i], 4, kWave));
       }
-      const int first = (kbg * TPW + kb) * 32;
-      if (first + 32 > keys_wg) {  // ragged tail: keys beyond the prompt never beat the -inf start value
-        const int left = keys_wg - first - h * 4;
+      const int inside = p.M - wave_tile_key(kb);
+      if (inside < 32) {  // ragged tail: keys beyond the prompt never beat the -inf start value
+        const int left = inside - h * 4;
 #pragma unroll
         for (int i = 0; i < 16; ++i)
           if ((i >> 2) * 8 + (i & 3) >= left) x[i] = -INFINITY;

@@ -22,6 +22,19 @@ def test_every_declared_symbol_is_exported():
         assert hasattr(lib, n), n
 
 
+def test_probe_library_exports_what_its_header_declares():
+    from paper_2502_02789_amd import probe
+    text = open(os.path.join(ROOT, "include", "sp_probe.h")).read()
+    names = re.findall(r"^SP_PROBE_API\s+[\w\s\*]+?\b(sp_\w+)\s*\(", text, flags=re.M)
+    assert set(names) == set(probe.EXPORTS) and len(names) == len(probe.EXPORTS)
+    lib = C.CDLL(probe.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    lib = probe.load_library()
+    assert lib.sp_probe_read(None, 1, 16, 1, None, None) == -1          # argument checks need no GPU
+    assert lib.sp_probe_tiled(None, 1, 32768, 8, 128, 1024, 128, None, None) == -1
+
+
 def test_struct_layouts_match_the_header_field_order():
     text = open(os.path.join(ROOT, "include", "specprefill.h")).read()
     for cname, cls in (("sp_score_args", sp.ScoreArgs), ("sp_pool_select_args", sp.PoolSelectArgs),
