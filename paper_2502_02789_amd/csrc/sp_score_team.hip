@@ -284,11 +284,12 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
     if ((int)__builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 32)) < slab) {
       // A waiting wave must cost the working ones as little as possible: lowest issue priority (it
       // shares its SIMD with a wave that streams) and long naps between looks.  Measured on the
-      // 32K-token workload: polling every 128 cycles at the slab's priority 524 us, this 460 us.
+      // 32K-token workload (whole call, steady state): naps of 8 x 64 cycles 409 us, 20: 400, 40: 397,
+      // 80: 394, 127: 394.
       __builtin_amdgcn_s_setprio(0);
       while ((int)__builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 32)) < slab && may_poll()) {
         service(slab);
-        __builtin_amdgcn_s_sleep(20);
+        __builtin_amdgcn_s_sleep(80);
       }
       if (((slab + NSETS) ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(2);  // back to the priority of the slab in progress
     }
@@ -345,12 +346,14 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
       tm.template stats_tile<SET>(kb);
       // between the key tiles too: with one visit per slab a sampler that has fallen behind
       // (a sample that had to be repeated) could never catch up again
-      if (kb + 1 < TPW) tm.service(slab - 1);
+      if (kb + 1 < TPW) tm.service(slab - 2);
     }
     tm.template deposit<SET>(slab);
-    // a step towards the log-sum-exps of an earlier slab, here, where the fewest registers are
-    // live; one slab behind, so that the partners have most likely published it
-    tm.service(slab - 1);
+    // A step towards the log-sum-exps of an earlier slab, here, where the fewest registers are
+    // live.  Two slabs behind: a sample that comes back with lines still empty has to be repeated
+    // and costs more than it gains (whole call with the limit at slab: 430 us, slab - 1: 397 us,
+    // slab - 2: 389 us; three behind is too late: 418 us).
+    tm.service(slab - 2);
   };
 
   for (int s0 = 0; s0 < p.n_slabs; s0 += NSETS) {
