@@ -224,6 +224,46 @@ def side_measurement(number, layer_reduce, steps, warmup):
     return out
 
 
+def short_prompt_measurement(steps, warmup):
+    """Workload 1 (one 1024-token prompt, no look-ahead): the separate calls against the single
+    fused launch (sp_score_pool_select), GPU time per step from HIP events."""
+    import numpy as np
+    import torch
+    from paper_2502_02789_amd import device as dev
+    pr = Problem(1, "max")
+    stream = pr.stream
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for a, b in ev:
+            a.record(stream)
+            fn()
+            b.record(stream)
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        return ms[len(ms) // 2] * 1e3
+
+    def separate():
+        pr.scorer.run(stream)
+        pr.sel.run(stream)
+
+    t_sep = timed(separate)
+    kept_sep = pr.sel.kept_idx.clone()
+    scores_sep = pr.scorer.scores.clone()
+    t_fused = timed(lambda: dev.score_pool_select(pr.scorer, pr.sel, stream))
+    same_keep = bool((kept_sep == pr.sel.kept_idx).all())
+    rel = float(((scores_sep - pr.scorer.scores).abs() / scores_sep.abs()).max())
+    w = pr.w
+    return {
+        "workload": f"{w.name}: B={w.B} T={w.T} L={w.L} H={w.H} H_kv={w.H_kv} d={w.d} N={w.N}",
+        "sp_score_plus_sp_pool_select_us": t_sep, "sp_score_pool_select_us": t_fused,
+        "same_keep_set": same_keep, "max_rel_diff_of_scores": rel, "ok": bool(same_keep and rel <= 2 * SCORE_RTOL),
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -342,6 +382,8 @@ def main():
         for number, mode in ((3, "mean" if args.layer_reduce == "max" else "max"), (2, "max"), (5, "max"), (4, "max")):
             also.append(side_measurement(number, mode, steps=20, warmup=40 if number != 4 else 10))
             ok = ok and also[-1]["ok"]
+        also.append(short_prompt_measurement(steps=50, warmup=20))
+        ok = ok and also[-1]["ok"]
         out["also"] = also
     print(json.dumps(out), flush=True)
     if not ok:

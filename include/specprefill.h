@@ -211,6 +211,21 @@ SP_API sp_status sp_pool_select(const sp_pool_select_args* args, void* hip_strea
 SP_API sp_status sp_pool_select_static(const sp_pool_select_args* args, void* hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * sp_score_pool_select: sp_score followed by sp_pool_select for ONE SHORT prompt, in a single
+ * kernel launch by a single workgroup (Sec. 3.2 equation, Sec. 3.2.2 and Sec. 3.2.3 in one go;
+ * the case of the paper's variants without look-ahead on short contexts, Sec. 4.3, where the
+ * separate calls are bound by their launches).  `score` and `select` are filled exactly as for
+ * the separate calls and must describe the same prompt (select->B == score->B, select->T ==
+ * score->T, select->d_scores == score->d_scores, select->d_cu_seqlens == score->d_cu_seqlens);
+ * the workspace fields of both are ignored.  Outputs: everything the two calls write (scores,
+ * optional lse, kept_idx, cu_keep, optional chunk_scores); scores agree with sp_score's to the
+ * tolerance of fp32 summation order, the selection is sp_pool_select's on these scores.
+ * Supported: B == 1, 1 <= T <= 2048, H/H_kv * N <= 8, rope_theta == 0, no block table, at most 2048
+ * chunks; anything else returns SP_EUNSUPPORTED and launches nothing (use the separate calls).
+ * --------------------------------------------------------------------------- */
+SP_API sp_status sp_score_pool_select(const sp_score_args* score, const sp_pool_select_args* select, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
  * sp_gather: restore_pos_ids (Algorithm 1, Sec. 3.2.4) plus the gathers the base
  * model's prefill needs.  For kept slot s of sequence b:
  *     kept_pos[s]  = kept_idx[s] - cu_seqlens[b]      (position in the ORIGINAL prompt)

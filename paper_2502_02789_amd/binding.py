@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecpref
 
 EXPORTS = (
     "sp_score_workspace_bytes", "sp_score", "sp_score_general", "sp_score_check", "sp_set_wait_budget",
-    "sp_keep_upper_bound", "sp_pool_select_workspace_bytes", "sp_pool_select", "sp_pool_select_static",
+    "sp_keep_upper_bound", "sp_pool_select_workspace_bytes", "sp_pool_select", "sp_pool_select_static", "sp_score_pool_select",
     "sp_gather", "sp_strerror", "sp_version",
 )
 
@@ -93,6 +93,8 @@ def load_library() -> C.CDLL:
     lib.sp_pool_select.argtypes = [C.POINTER(PoolSelectArgs), C.c_void_p]
     lib.sp_pool_select_static.restype = C.c_int
     lib.sp_pool_select_static.argtypes = [C.POINTER(PoolSelectArgs), C.c_void_p]
+    lib.sp_score_pool_select.restype = C.c_int
+    lib.sp_score_pool_select.argtypes = [C.POINTER(ScoreArgs), C.POINTER(PoolSelectArgs), C.c_void_p]
     lib.sp_gather.restype = C.c_int
     lib.sp_gather.argtypes = [C.POINTER(GatherArgs), C.c_void_p]
     lib.sp_strerror.restype = C.c_char_p
@@ -225,6 +227,12 @@ def sp_pool_select_workspace_bytes(args: PoolSelectArgs) -> int:
 
 def sp_pool_select(args: PoolSelectArgs, stream=None) -> None:
     _check("sp_pool_select", load_library().sp_pool_select(C.byref(args), _stream_handle(stream)))
+
+
+def sp_score_pool_select(score: ScoreArgs, select: PoolSelectArgs, stream=None) -> None:
+    """One short prompt scored and selected in a single launch (raises SpError(SP_EUNSUPPORTED) if it does not fit)."""
+    _check("sp_score_pool_select",
+           load_library().sp_score_pool_select(C.byref(score), C.byref(select), _stream_handle(stream)))
 
 
 SP_STATIC_MAX_SEQS, SP_STATIC_MAX_CHUNKS = 4096, 131072

@@ -99,6 +99,13 @@ class Selector:
         return self.kept_idx, self.cu_keep
 
 
+def score_pool_select(scorer: Scorer, selector: Selector, stream=None):
+    """One short prompt scored and selected in a single launch (sp_score_pool_select); the selector
+    must have been built on scorer.scores and the same cu_seqlens."""
+    sp.sp_score_pool_select(scorer.args, selector.args, stream)
+    return scorer.scores, selector.kept_idx, selector.cu_keep
+
+
 class Gatherer:
     def __init__(self, sel: Selector, *, token_ids: Optional[torch.Tensor] = None,
                  embed: Optional[torch.Tensor] = None):
