@@ -220,8 +220,11 @@ SP_API sp_status sp_pool_select_static(const sp_pool_select_args* args, void* hi
  * the workspace fields of both are ignored.  Outputs: everything the two calls write (scores,
  * optional lse, kept_idx, cu_keep, optional chunk_scores); scores agree with sp_score's to the
  * tolerance of fp32 summation order, the selection is sp_pool_select's on these scores.
- * Supported: B == 1, 1 <= T <= 2048, H/H_kv * N <= 8, rope_theta == 0, no block table, at most 2048
- * chunks; anything else returns SP_EUNSUPPORTED and launches nothing (use the separate calls).
+ * Supported: B == 1, 1 <= T <= 2048, H/H_kv a power of two with H/H_kv * N <= 16, rope_theta == 0,
+ * no block table, at most 2048 chunks; anything else returns SP_EUNSUPPORTED and launches nothing
+ * (use the separate calls).  One compute unit does all the work: the call pays while
+ * L * H_kv * T stays small (a few thousand keys of a few layers); the separate calls, which use
+ * the whole device, overtake it beyond that.
  * --------------------------------------------------------------------------- */
 SP_API sp_status sp_score_pool_select(const sp_score_args* score, const sp_pool_select_args* select, void* hip_stream);
 

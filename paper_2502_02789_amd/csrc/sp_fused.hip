@@ -7,22 +7,32 @@
 // average pooling, chunk means, top-k chunks and compaction of Sec. 3.2.3 -- the paper's
 // variants without look-ahead (Sec. 4.3) on short contexts are exactly this case.
 //
-// One thread owns up to kKeysPerThread keys.  Per (layer, KV head): the thread's logits against
-// the KV head's R = (H / H_kv) * N query rows stay in registers, the rows' (max, sum exp) are
-// reduced over the workgroup, and the thread turns its logits into log-probabilities and folds
-// them into its own running [key][query] maxima (registers again).  Nothing but the final scores
-// ever leaves the workgroup.  Plain fp32 FMAs: at these sizes the matrix cores would change
-// nothing.  The selection then runs on the scores in LDS with the same arithmetic, in the same
-// order, as sp_pool_select (fp64, index order), so both paths keep the same tokens.
+// One compute unit has to do all the arithmetic, so the logits go through the matrix cores even
+// though at most 16 of the operand's columns are in use: v_mfma_f32_16x16x32_bf16 with 16 keys
+// as rows and the KV head's (H / H_kv) * N query rows as columns.  Both operands come straight
+// from global memory in the instruction's own layout (lane = row or column, 16 contiguous bytes
+// of the head dim per lane), with no staging.  A lane therefore holds logits of ONE query row
+// (lane % 16) against four keys per tile, which makes everything after the product cheap:
+//   * (max, sum exp) of a softmax row: in-lane over the wave's tiles, two lane exchanges inside
+//     the wave, one value per wave through LDS, 16 lanes per row for the second level -- two
+//     barriers per batch of PB (layer, KV head) pairs;
+//   * max over the heads of a KV group: DPP moves between neighbouring lanes;
+//   * max / mean over layers: in-lane; mean over the valid queries: one DPP sum at the end.
+// Nothing but the final scores ever leaves the workgroup.  The selection then runs on the scores
+// in LDS with the same arithmetic, in the same order, as sp_pool_select (fp64, index order), so
+// both paths keep the same tokens.
+#include "sp_lds.h"
 #include "sp_score_internal.h"
 #include "sp_select_core.h"
 
 namespace sp {
 
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
 constexpr int kFusedThreads = 1024;
+constexpr int kFusedWaves = kFusedThreads / 64;
 constexpr int kFusedMaxKeys = 2048;
-constexpr int kKeysPerThread = kFusedMaxKeys / kFusedThreads;  // 2
-constexpr int kFusedMaxRows = 8;                               // query rows per KV head: (H / H_kv) * N
+constexpr int kFusedMaxRows = 16;  // query rows per KV head: (H / H_kv) * N, the columns of one MFMA
 
 struct FusedDev {
   int M, L, N, H, H_kv, G, d, layer_reduce;
@@ -36,170 +46,201 @@ struct FusedDev {
   const uint16_t* k[SP_MAX_LAYERS];
 };
 
-// sum and max over the workgroup of R per-thread values each; results land in out_m[r], out_z[r]
-// (LDS) for every thread to read after the call
-template <int R>
-__device__ __forceinline__ void block_row_stats(const float (&m)[R], const float (&z)[R], float* red_m, float* red_z,
-                                                float* out_m, float* out_z) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const float wm = wave_max(m[r]);
-    const float wz = wave_sum(m[r] == -INFINITY ? 0.f : z[r] * expf(m[r] - wm));
-    if (lane == 0) { red_m[r * 16 + wave] = wm; red_z[r * 16 + wave] = wz; }
-  }
-  __syncthreads();
-  if (threadIdx.x < R * 16) {  // 16 lanes per row
-    const int r = threadIdx.x >> 4;
-    float wm = red_m[threadIdx.x], wz = red_z[threadIdx.x];
-    float bm = wm;
-#pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) bm = fmaxf(bm, __shfl_xor(bm, off, 16));
-    float bz = (wm == -INFINITY) ? 0.f : wz * expf(wm - bm);
-#pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) bz += __shfl_xor(bz, off, 16);
-    if ((threadIdx.x & 15) == 0) { out_m[r] = bm; out_z[r] = bz; }
-  }
-  __syncthreads();
+// the value of another lane of the same row of 16 lanes (DPP control word CTRL)
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+struct OpMax { static __device__ __forceinline__ float f(float a, float b) { return fmaxf(a, b); } };
+struct OpAdd { static __device__ __forceinline__ float f(float a, float b) { return a + b; } };
+// Reduction over aligned groups of `lanes` (1, 2, 4, 8 or 16) lanes; every lane of the group gets
+// the result.  Lane ^ 1, lane ^ 2 inside the quad, then the mirrored half row and the mirrored row.
+template <class Op>
+__device__ __forceinline__ float group_reduce(float v, int lanes) {
+  if (lanes >= 2) v = Op::f(v, dpp_f32<0xB1>(v));
+  if (lanes >= 4) v = Op::f(v, dpp_f32<0x4E>(v));
+  if (lanes >= 8) v = Op::f(v, dpp_f32<0x141>(v));
+  if (lanes >= 16) v = Op::f(v, dpp_f32<0x140>(v));
+  return v;
 }
 
-template <int D, int R>
+template <int D, int KK>  // KK: 64-key blocks per wave (1: up to 1024 keys, 2: up to 2048)
 __global__ __launch_bounds__(kFusedThreads) void fused_short_kernel(const FusedDev p) {
-  __shared__ float q_lds[R * D];          // the KV head's query rows, fp32
-  __shared__ float red_m[R * 16], red_z[R * 16], row_m[R], row_z[R];
+  constexpr int TPW = 4 * KK;  // 16-key tiles per wave
+  constexpr int PB = 2 / KK;   // (layer, KV head) pairs per batch: PB * TPW * 4 logits per lane
+  constexpr int KS = D / 32;   // MFMA steps along the head dim
+  static_assert(PB * 16 * 16 <= kFusedThreads, "16 lanes per softmax row in the second level");
+  __shared__ double wide[kFusedMaxKeys];  // first the pooled scores, then (as 64-bit keys) the selection's keys
+  static_assert(kFusedMaxKeys >= kSingleMaxChunks, "the selection's keys reuse the pooled scores' room");
+  __shared__ float red_m[PB * 16 * kFusedWaves], red_z[PB * 16 * kFusedWaves], row_m[PB * 16], row_z[PB * 16];
   __shared__ float score_lds[kFusedMaxKeys];
   __shared__ double cs_lds[kSingleMaxChunks];
-  const int tid = threadIdx.x;
-  const int rows = p.G * p.N;             // <= R
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 15, kg = lane >> 4;  // operand row / column; 8-element group of the head dim
+  const int rows = p.G * p.N;               // <= 16; query row r = (query) * G + (head of the group)
+  const int pairs = p.L * p.H_kv;
+  const float scale2 = p.scale * 1.44269504088896341f;  // logits in units of ln 2
+  const int tile0 = wave * TPW;             // the wave's keys: tiles tile0 .. tile0 + TPW - 1
+  // logit c[t][j] of this lane: query row n, key (tile0 + t) * 16 + 4 * kg + j
+  auto key_of = [&](int t, int j) { return (tile0 + t) * 16 + 4 * kg + j; };
 
-  float tot[kKeysPerThread][kFusedMaxRows];  // per own key and query: running max (or per-layer sums)
+  float tot[TPW][4], lmax[TPW][4];  // over the layers / this layer's max over heads
 #pragma unroll
-  for (int kk = 0; kk < kKeysPerThread; ++kk)
+  for (int t = 0; t < TPW; ++t)
 #pragma unroll
-    for (int n = 0; n < kFusedMaxRows; ++n) tot[kk][n] = (p.layer_reduce == SP_LAYER_MAX) ? -INFINITY : 0.f;
-
-  for (int l = 0; l < p.L; ++l) {
-    float lmax[kKeysPerThread][kFusedMaxRows];  // this layer's max over heads
-#pragma unroll
-    for (int kk = 0; kk < kKeysPerThread; ++kk)
-#pragma unroll
-      for (int n = 0; n < kFusedMaxRows; ++n) lmax[kk][n] = -INFINITY;
-    for (int g = 0; g < p.H_kv; ++g) {
-      // query rows r = n * G + j of this KV head -> LDS as fp32
-      for (int i = tid; i < rows * D; i += kFusedThreads) {
-        const int r = i / D, t = i - r * D;
-        const int n = r / p.G, j = r - n * p.G;
-        q_lds[i] = __uint_as_float((uint32_t)p.q[(((int64_t)l * p.N + n) * p.H + g * p.G + j) * D + t] << 16);
-      }
-      __syncthreads();
-      float s[kKeysPerThread][R];
-      float m[R], z[R];
-#pragma unroll
-      for (int r = 0; r < R; ++r) { m[r] = -INFINITY; z[r] = 0.f; }
-#pragma unroll
-      for (int kk = 0; kk < kKeysPerThread; ++kk) {
-        const int key = tid + kk * kFusedThreads;
-        const bool valid = key < p.M;
-        float acc[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) acc[r] = 0.f;
-        const uint4* kp = reinterpret_cast<const uint4*>(p.k[l] + (int64_t)(valid ? key : 0) * p.ts + (int64_t)g * p.hs);
-#pragma unroll 4
-        for (int c = 0; c < D / 8; ++c) {
-          const uint4 v = kp[c];
-          const float k0 = bf16_lo(v.x), k1 = bf16_hi(v.x), k2 = bf16_lo(v.y), k3 = bf16_hi(v.y);
-          const float k4 = bf16_lo(v.z), k5 = bf16_hi(v.z), k6 = bf16_lo(v.w), k7 = bf16_hi(v.w);
-#pragma unroll
-          for (int r = 0; r < R; ++r) {
-            const float* qr = q_lds + r * D + 8 * c;
-            float a = acc[r];
-            a = fmaf(qr[0], k0, a); a = fmaf(qr[1], k1, a); a = fmaf(qr[2], k2, a); a = fmaf(qr[3], k3, a);
-            a = fmaf(qr[4], k4, a); a = fmaf(qr[5], k5, a); a = fmaf(qr[6], k6, a); a = fmaf(qr[7], k7, a);
-            acc[r] = a;
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-          const float x = (valid && r < rows) ? p.scale * acc[r] : -INFINITY;
-          s[kk][r] = x;
-          const float mn = fmaxf(m[r], x);
-          z[r] = (mn == -INFINITY) ? 0.f : z[r] * expf(m[r] - mn) + expf(x - mn);
-          m[r] = mn;
-        }
-      }
-      block_row_stats<R>(m, z, red_m, red_z, row_m, row_z);  // (its barriers also fence q_lds for the next KV head)
-      float lse[R];
-#pragma unroll
-      for (int r = 0; r < R; ++r) lse[r] = row_m[r] + logf(row_z[r]);
-      if (p.lse_out && tid < rows) {
-        const int n = tid / p.G, j = tid - n * p.G;
-        p.lse_out[((int64_t)l * p.N + n) * p.H + g * p.G + j] = row_m[tid] + logf(row_z[tid]);
-      }
-#pragma unroll
-      for (int kk = 0; kk < kKeysPerThread; ++kk)
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-          if (r < rows) {
-            const int n = r / p.G;
-            // (n < kFusedMaxRows because rows <= R <= kFusedMaxRows; written so that the index is a constant after unrolling)
-#pragma unroll
-            for (int nn = 0; nn < kFusedMaxRows; ++nn)
-              if (nn == n) lmax[kk][nn] = fmaxf(lmax[kk][nn], s[kk][r] - lse[r]);
-          }
+    for (int j = 0; j < 4; ++j) {
+      tot[t][j] = (p.layer_reduce == SP_LAYER_MAX) ? -INFINITY : 0.f;
+      lmax[t][j] = -INFINITY;
     }
+
+  for (int b0 = 0; b0 < pairs; b0 += PB) {
+    f32x4 c[PB][TPW];
 #pragma unroll
-    for (int kk = 0; kk < kKeysPerThread; ++kk)
+    for (int pb = 0; pb < PB; ++pb) {
+      const int pair = b0 + pb;
 #pragma unroll
-      for (int n = 0; n < kFusedMaxRows; ++n) {
-        if (p.layer_reduce == SP_LAYER_MAX) tot[kk][n] = fmaxf(tot[kk][n], lmax[kk][n]);
-        else tot[kk][n] += expf(lmax[kk][n]);
+      for (int t = 0; t < TPW; ++t) c[pb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (pair >= pairs) continue;
+      const int l = pair / p.H_kv, g = pair - l * p.H_kv;
+      bf16x8 qv[KS];  // column n of the query operand (zero beyond the last query row)
+      {
+        const int nn = n < rows ? n : 0;
+        const int nq = nn / p.G, j = nn - nq * p.G;
+        const uint16_t* qp = p.q + (((int64_t)l * p.N + nq) * p.H + g * p.G + j) * D + 8 * kg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          uint4 v = *reinterpret_cast<const uint4*>(qp + 32 * ks);
+          if (n >= rows) v = make_uint4(0, 0, 0, 0);
+          qv[ks] = __builtin_bit_cast(bf16x8, v);
+        }
       }
+      // Four tiles at a time: all their loads first (rows past the end of the prompt read the
+      // last key again and are masked below), so that one round trip covers the group.
+      const uint16_t* kbase = p.k[l] + (int64_t)g * p.hs + 8 * kg;
+#pragma unroll
+      for (int t0 = 0; t0 < TPW; t0 += 4) {
+        uint4 kv[4][KS];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int row = min((tile0 + t0 + t) * 16 + n, p.M - 1);
+          const uint16_t* kp = kbase + (int64_t)row * p.ts;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) kv[t][ks] = *reinterpret_cast<const uint4*>(kp + 32 * ks);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            c[pb][t0 + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kv[t][ks]), qv[ks], c[pb][t0 + t], 0, 0, 0);
+      }
+      // base-2 logits from here on: exp2 is one instruction
+#pragma unroll
+      for (int t = 0; t < TPW; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[pb][t][j] = key_of(t, j) < p.M ? scale2 * c[pb][t][j] : -INFINITY;
+    }
+
+    // (max, sum exp) of the batch's PB * 16 softmax rows over the workgroup
+#pragma unroll
+    for (int pb = 0; pb < PB; ++pb) {
+      float wm = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < TPW; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wm = fmaxf(wm, c[pb][t][j]);
+      wm = fmaxf(wm, __shfl_xor(wm, 16));
+      wm = fmaxf(wm, __shfl_xor(wm, 32));
+      float wz = 0.f;
+#pragma unroll
+      for (int t = 0; t < TPW; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wz += (wm == -INFINITY) ? 0.f : exp2f(c[pb][t][j] - wm);
+      wz += __shfl_xor(wz, 16);
+      wz += __shfl_xor(wz, 32);
+      if (lane < 16) { red_m[(pb * 16 + lane) * kFusedWaves + wave] = wm; red_z[(pb * 16 + lane) * kFusedWaves + wave] = wz; }
+    }
+    __syncthreads();
+    if (tid < PB * 16 * kFusedWaves) {  // 16 lanes per row, one per wave's pair of values
+      const float wm = red_m[tid], wz = red_z[tid];
+      const float bm = group_reduce<OpMax>(wm, 16);
+      const float bz = group_reduce<OpAdd>((wm == -INFINITY) ? 0.f : wz * exp2f(wm - bm), 16);
+      if ((tid & 15) == 0) { row_m[tid >> 4] = bm; row_z[tid >> 4] = bz; }
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int pb = 0; pb < PB; ++pb) {
+      const int pair = b0 + pb;
+      if (pair >= pairs) continue;
+      const int l = pair / p.H_kv, g = pair - l * p.H_kv;
+      const float lse = row_m[pb * 16 + n] + log2f(row_z[pb * 16 + n]);  // base 2
+      if (p.lse_out && tid < rows) {
+        const int nq = tid / p.G, j = tid - nq * p.G;
+        p.lse_out[((int64_t)l * p.N + nq) * p.H + g * p.G + j] = 0.69314718055994531f * lse;
+      }
+#pragma unroll
+      for (int t = 0; t < TPW; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          lmax[t][j] = fmaxf(lmax[t][j], group_reduce<OpMax>(c[pb][t][j] - lse, p.G));  // over the group's heads
+      if (g == p.H_kv - 1) {  // the layer is complete
+#pragma unroll
+        for (int t = 0; t < TPW; ++t)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (p.layer_reduce == SP_LAYER_MAX) tot[t][j] = fmaxf(tot[t][j], lmax[t][j]);
+            else tot[t][j] += exp2f(lmax[t][j]);
+            lmax[t][j] = -INFINITY;
+          }
+      }
+    }
   }
 
+  // mean over the valid queries: the lanes of a query's first head carry its value
   int nv = p.n_valid ? p.n_valid[0] : p.N;
   nv = max(1, min(nv, p.N));
+  const bool counts = n < rows && n % p.G == 0 && n / p.G < nv;
+  const float inv_denom = 1.f / ((p.layer_reduce == SP_LAYER_MAX) ? (float)nv : (float)nv * (float)p.L);
 #pragma unroll
-  for (int kk = 0; kk < kKeysPerThread; ++kk) {
-    const int key = tid + kk * kFusedThreads;
-    if (key < p.M) {
-      float acc = 0.f;
+  for (int t = 0; t < TPW; ++t)
 #pragma unroll
-      for (int n = 0; n < kFusedMaxRows; ++n)
-        if (n < nv) acc += (p.layer_reduce == SP_LAYER_MAX) ? expf(tot[kk][n]) : tot[kk][n];
-      const float denom = (p.layer_reduce == SP_LAYER_MAX) ? (float)nv : (float)nv * (float)p.L;
-      const float sc = acc / denom;
-      score_lds[key] = sc;
-      p.scores[key] = sc;
+    for (int j = 0; j < 4; ++j) {
+      const float mine = (p.layer_reduce == SP_LAYER_MAX) ? exp2f(tot[t][j]) : tot[t][j];
+      const float sc = group_reduce<OpAdd>(counts ? mine : 0.f, 16) * inv_denom;
+      const int key = key_of(t, j);
+      if (n == 0 && key < p.M) {
+        score_lds[key] = sc;
+        p.scores[key] = sc;
+      }
     }
-  }
   __syncthreads();
 
   // Sec. 3.2.3 on the scores in LDS; the same fp64 arithmetic in the same order as sp_pool_select
   const SelDev& sp_ = p.sel;
+  for (int i = tid; i < p.M; i += kFusedThreads) {
+    const int a = max(0, i - sp_.radius), e = min(p.M - 1, i + sp_.radius);
+    double sum = 0.0;
+    for (int x = a; x <= e; ++x) sum += (double)score_lds[x];
+    wide[i] = sum / (double)(e - a + 1);
+  }
+  __syncthreads();
   const int n_chunks = (p.M + sp_.chunk - 1) / sp_.chunk;
   for (int j = tid; j < n_chunks; j += kFusedThreads) {
     const int s0 = j * sp_.chunk, s1 = min(s0 + sp_.chunk, p.M);
     double t = 0.0;
-    for (int i = s0; i < s1; ++i) {  // pooled value of token i, then straight into its chunk's sum
-      const int a = max(0, i - sp_.radius), e = min(p.M - 1, i + sp_.radius);
-      double sum = 0.0;
-      for (int x = a; x <= e; ++x) sum += (double)score_lds[x];
-      t += sum / (double)(e - a + 1);
-    }
+    for (int x = s0; x < s1; ++x) t += wide[x];
     const double mean = t / (double)(s1 - s0);
     cs_lds[j] = mean;
     if (sp_.chunk_scores_out) sp_.chunk_scores_out[j] = (float)mean;
   }
   __syncthreads();
-  select_emit_single(sp_, cs_lds);
+  select_emit_single(sp_, cs_lds, reinterpret_cast<uint64_t*>(wide));
 }
 
 template <int D>
-static sp_status launch_fused(const FusedDev& dev, int rows, hipStream_t stream) {
-  if (rows <= 1) hipLaunchKernelGGL((fused_short_kernel<D, 1>), dim3(1), dim3(kFusedThreads), 0, stream, dev);
-  else if (rows <= 2) hipLaunchKernelGGL((fused_short_kernel<D, 2>), dim3(1), dim3(kFusedThreads), 0, stream, dev);
-  else if (rows <= 4) hipLaunchKernelGGL((fused_short_kernel<D, 4>), dim3(1), dim3(kFusedThreads), 0, stream, dev);
-  else hipLaunchKernelGGL((fused_short_kernel<D, 8>), dim3(1), dim3(kFusedThreads), 0, stream, dev);
+static sp_status launch_fused(const FusedDev& dev, hipStream_t stream) {
+  if (dev.M <= kFusedThreads) hipLaunchKernelGGL((fused_short_kernel<D, 1>), dim3(1), dim3(kFusedThreads), 0, stream, dev);
+  else hipLaunchKernelGGL((fused_short_kernel<D, 2>), dim3(1), dim3(kFusedThreads), 0, stream, dev);
   return launch_status();
 }
 
@@ -210,7 +251,7 @@ extern "C" sp_status sp_score_pool_select(const sp_score_args* a, const sp_pool_
   if (!a || !s) return SP_ENULL;
   // each half is checked as the separate calls check it (workspaces are not needed here)
   if (a->B < 1 || a->N < 1 || a->N > SP_MAX_QUERIES || a->L < 1 || a->L > SP_MAX_LAYERS) return SP_EINVAL;
-  if (a->H < 1 || a->H_kv < 1 || a->H % a->H_kv != 0 || a->H / a->H_kv > 8) return SP_EINVAL;
+  if (a->H < 1 || a->H_kv < 1 || a->H % a->H_kv != 0) return SP_EINVAL;
   if (a->d != 64 && a->d != 128) return SP_EINVAL;
   if (a->T < 0 || a->T >= (int64_t)INT32_MAX) return SP_EINVAL;
   if (a->layer_reduce != SP_LAYER_MAX && a->layer_reduce != SP_LAYER_MEAN) return SP_EINVAL;
@@ -228,7 +269,8 @@ extern "C" sp_status sp_score_pool_select(const sp_score_args* a, const sp_pool_
   if (!finite_f64(s->keep_rate) || s->keep_rate <= 0.0 || s->keep_rate > 1.0 || s->kept_capacity < 0) return SP_EINVAL;
   if (!s->d_kept_idx || !s->d_cu_keep) return SP_ENULL;
   // what one workgroup can hold
-  const int rows = a->H / a->H_kv * a->N;
+  const int G = a->H / a->H_kv, rows = G * a->N;
+  if ((G & (G - 1)) != 0) return SP_EUNSUPPORTED;  // the heads of a KV group sit in an aligned run of lanes
   if (a->B != 1 || a->T < 1 || a->T > kFusedMaxKeys || rows > kFusedMaxRows || a->rope_theta != 0.f || a->d_block_table ||
       (a->T + s->chunk - 1) / s->chunk > kSingleMaxChunks)
     return SP_EUNSUPPORTED;
@@ -250,5 +292,5 @@ extern "C" sp_status sp_score_pool_select(const sp_score_args* a, const sp_pool_
   p.chunk_scores_out = s->d_chunk_scores;
   p.cu_chunks = nullptr; p.seq_keep = nullptr; p.cs = nullptr; p.chunk_off = nullptr;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  return a->d == 64 ? launch_fused<64>(dev, rows, stream) : launch_fused<128>(dev, rows, stream);
+  return a->d == 64 ? launch_fused<64>(dev, stream) : launch_fused<128>(dev, stream);
 }

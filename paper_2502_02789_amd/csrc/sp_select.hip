@@ -159,7 +159,10 @@ __global__ __launch_bounds__(1024) void select_kernel(const SelDev p) {
   if (t == 0) p.seq_keep[b] = total_tokens;
 }
 
-__global__ __launch_bounds__(1024) void select_emit_single_kernel(const SelDev p) { select_emit_single(p, p.cs); }
+__global__ __launch_bounds__(1024) void select_emit_single_kernel(const SelDev p) {
+  __shared__ uint64_t keys[kSingleMaxChunks];
+  select_emit_single(p, p.cs, keys);
+}
 
 __global__ __launch_bounds__(1024) void cu_keep_kernel(const SelDev p) {
   int bad = 0;

@@ -84,13 +84,14 @@ __device__ __forceinline__ void find_bucket(const int* hist, int need, int t, in
 }
 
 // Single sequence with at most kSingleMaxChunks chunks: top-k, compaction and the kept-index
-// list in one workgroup and one launch.  The k-th largest key is found by the same 8-pass radix
-// select as in select_kernel, on keys held in LDS; ties at the threshold go to the lower chunk
-// indices by an ordered scan; kept tokens are written straight away.
+// list in one workgroup and one launch.  Above kCountMaxChunks chunks the k-th largest key is
+// found by the same 8-pass radix select as in select_kernel, on keys held in LDS; ties at the
+// threshold go to the lower chunk indices by an ordered scan; kept tokens are written straight away.
 constexpr int kSingleMaxChunks = 2048;
-// `cs`: the chunk scores (global or LDS memory).  Call with all 1024 threads of the workgroup.
-__device__ __forceinline__ void select_emit_single(const SelDev& p, const double* cs) {
-  __shared__ uint64_t keys[kSingleMaxChunks];
+constexpr int kCountMaxChunks = 256;  // up to here the chunks are ranked by counting instead
+// `cs`: the chunk scores (global or LDS memory); `keys`: LDS room for kSingleMaxChunks 64-bit keys.
+// Call with all 1024 threads of the workgroup.
+__device__ __forceinline__ void select_emit_single(const SelDev& p, const double* cs, uint64_t* keys) {
   __shared__ int hist[256];
   __shared__ int sh[1024];
   __shared__ int s_bucket, s_need;
@@ -113,6 +114,43 @@ __device__ __forceinline__ void select_emit_single(const SelDev& p, const double
   }
   if (__syncthreads_or(bad)) {  // invalid scores: reported in band, nothing kept
     if (t == 0) p.cu_keep[1] = -1;
+    return;
+  }
+
+  if (n <= kCountMaxChunks) {
+    // Few chunks: thread t ranks chunk t by counting the chunks that come before it in the order
+    // (larger score, or equal score and lower index); the k first are kept.  All chunks but the
+    // last have the same length, so a kept token's place follows from the number of kept chunks
+    // before its own: no scan, two barriers.
+    __shared__ uint64_t kept_mask[kCountMaxChunks / 64];
+    bool keep = false;
+    if (t < n) {
+      const uint64_t mine = keys[t];
+      int rank = 0;
+      for (int j = 0; j < n; ++j) {
+        const uint64_t other = keys[j];
+        rank += (other > mine || (other == mine && j < t)) ? 1 : 0;
+      }
+      keep = rank < k;
+    }
+    const uint64_t ballot = __ballot(keep);
+    if (t < kCountMaxChunks && (t & 63) == 0) kept_mask[t >> 6] = ballot;
+    __syncthreads();
+    for (int i = t; i < M; i += 1024) {
+      const int c = i / p.chunk, w = c >> 6;
+      const uint64_t word = kept_mask[w];
+      if (!((word >> (c & 63)) & 1ull)) continue;
+      int before = __popcll(word & ((1ull << (c & 63)) - 1ull));
+      for (int x = 0; x < w; ++x) before += __popcll(kept_mask[x]);
+      const int64_t pos = (int64_t)before * p.chunk + (i - c * p.chunk);
+      if (pos < p.capacity) p.kept_idx[pos] = i;
+    }
+    if (t == 0) {
+      int kept_chunks = 0;
+      for (int x = 0; x < kCountMaxChunks / 64; ++x) kept_chunks += __popcll(kept_mask[x]);
+      const bool last_kept = (kept_mask[(n - 1) >> 6] >> ((n - 1) & 63)) & 1ull;
+      p.cu_keep[1] = (int32_t)((int64_t)kept_chunks * p.chunk - (last_kept ? (int64_t)n * p.chunk - M : 0));
+    }
     return;
   }
 
