@@ -212,19 +212,23 @@ SP_API sp_status sp_pool_select_static(const sp_pool_select_args* args, void* hi
 
 /* ---------------------------------------------------------------------------
  * sp_score_pool_select: sp_score followed by sp_pool_select for ONE SHORT prompt, in a single
- * kernel launch by a single workgroup (Sec. 3.2 equation, Sec. 3.2.2 and Sec. 3.2.3 in one go;
- * the case of the paper's variants without look-ahead on short contexts, Sec. 4.3, where the
- * separate calls are bound by their launches).  `score` and `select` are filled exactly as for
- * the separate calls and must describe the same prompt (select->B == score->B, select->T ==
- * score->T, select->d_scores == score->d_scores, select->d_cu_seqlens == score->d_cu_seqlens);
- * the workspace fields of both are ignored.  Outputs: everything the two calls write (scores,
- * optional lse, kept_idx, cu_keep, optional chunk_scores); scores agree with sp_score's to the
- * tolerance of fp32 summation order, the selection is sp_pool_select's on these scores.
- * Supported: B == 1, 1 <= T <= 2048, H/H_kv a power of two with H/H_kv * N <= 16, rope_theta == 0,
- * no block table, at most 2048 chunks; anything else returns SP_EUNSUPPORTED and launches nothing
- * (use the separate calls).  One compute unit does all the work: the call pays while
- * L * H_kv * T stays small (a few thousand keys of a few layers); the separate calls, which use
- * the whole device, overtake it beyond that.
+ * kernel launch (Sec. 3.2 equation, Sec. 3.2.2 and Sec. 3.2.3 in one go; the case of the paper's
+ * variants without look-ahead on short contexts, Sec. 4.3, where the separate calls are bound by
+ * their launches).  `score` and `select` are filled exactly as for the separate calls and must
+ * describe the same prompt (select->B == score->B, select->T == score->T, select->d_scores ==
+ * score->d_scores, select->d_cu_seqlens == score->d_cu_seqlens).  score->d_workspace must hold
+ * sp_score_workspace_bytes(score) bytes as for sp_score (the logits pass through it; SP_EWORKSPACE
+ * otherwise); select's workspace fields are ignored.  Outputs: everything the two calls write
+ * (scores, optional lse, kept_idx, cu_keep, optional chunk_scores); scores agree with sp_score's
+ * to the tolerance of fp32 summation order, the selection is sp_pool_select's on these scores.
+ * The workgroups of the launch never wait for one another (the last one to finish its share
+ * completes the call), so nothing depends on what else runs on the device; they do count their
+ * arrivals in one word per device, so two of these calls must not overlap on one GPU.
+ * Supported: B == 1, 1 <= T <= 2048, H/H_kv * N <= 16, L * H * N <= 4096, rope_theta == 0, no block
+ * table, at most 2048 chunks; anything else returns SP_EUNSUPPORTED and launches nothing (use the
+ * separate calls).  The part after the logits is done by one workgroup: the call pays while
+ * L * H * N * T stays small (a few layers of a few thousand keys); the separate calls, which use
+ * the whole device throughout, overtake it beyond that.
  * --------------------------------------------------------------------------- */
 SP_API sp_status sp_score_pool_select(const sp_score_args* score, const sp_pool_select_args* select, void* hip_stream);
 

@@ -1,26 +1,27 @@
 // sp_score_pool_select: scoring and chunk selection of ONE SHORT prompt in a single launch.
 //
 // For a prompt of a few thousand tokens the separate calls are bound by their launches (about
-// eight kernels for half a megabyte of keys), not by any throughput.  Here one workgroup does
+// eight kernels for half a megabyte of keys), not by any throughput.  Here one launch does
 // everything the two calls do: logits, row softmax over the prompt, max over heads (and layers),
 // mean over the valid queries (Sec. 3.2 equation and Sec. 3.2.2 of arXiv 2502.02789), then the
 // average pooling, chunk means, top-k chunks and compaction of Sec. 3.2.3 -- the paper's
 // variants without look-ahead (Sec. 4.3) on short contexts are exactly this case.
 //
-// One compute unit has to do all the arithmetic, so the logits go through the matrix cores even
-// though at most 16 of the operand's columns are in use: v_mfma_f32_16x16x32_bf16 with 16 keys
-// as rows and the KV head's (H / H_kv) * N query rows as columns.  Both operands come straight
-// from global memory in the instruction's own layout (lane = row or column, 16 contiguous bytes
-// of the head dim per lane), with no staging.  A lane therefore holds logits of ONE query row
-// (lane % 16) against four keys per tile, which makes everything after the product cheap:
-//   * (max, sum exp) of a softmax row: in-lane over the wave's tiles, two lane exchanges inside
-//     the wave, one value per wave through LDS, 16 lanes per row for the second level -- two
-//     barriers per batch of PB (layer, KV head) pairs;
-//   * max over the heads of a KV group: DPP moves between neighbouring lanes;
-//   * max / mean over layers: in-lane; mean over the valid queries: one DPP sum at the end.
-// Nothing but the final scores ever leaves the workgroup.  The selection then runs on the scores
-// in LDS with the same arithmetic, in the same order, as sp_pool_select (fp64, index order), so
-// both paths keep the same tokens.
+// Two phases, joined without any waiting:
+//   1. One workgroup per 64 keys; wave w takes the 16-key tile w % 4 of it and every fourth
+//      (layer, KV head) pair.  v_mfma_f32_16x16x32_bf16 with the 16 keys as rows and the KV
+//      head's (H / H_kv) * N query rows as columns, both operands straight from global memory in
+//      the instruction's own layout.  The wave writes its base-2 logits and, per softmax row,
+//      the (max, sum exp2) of its 16 keys to the workspace.
+//   2. Every workgroup then counts itself in; the one that arrives LAST (whichever it is: nobody
+//      waits for anybody, so nothing depends on which workgroups run together) finds all of phase 1
+//      in the workspace and finishes alone: row log-sum-exps from the tile partials, per key the
+//      max over heads / max or mean over layers / mean over the valid queries, and then the
+//      selection on the scores in LDS with the same arithmetic, in the same order, as
+//      sp_pool_select (fp64, index order), so both paths keep the same tokens.
+// One workgroup alone is several times slower at phase 1 (one compute unit's load path and ALUs
+// against sixteen or more), and phase 2 on compact rows wastes no lanes on the operand's unused
+// columns.
 #include "sp_lds.h"
 #include "sp_score_internal.h"
 #include "sp_select_core.h"
@@ -30,18 +31,25 @@ namespace sp {
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kFusedThreads = 1024;
-constexpr int kFusedWaves = kFusedThreads / 64;
 constexpr int kFusedMaxKeys = 2048;
-constexpr int kFusedMaxRows = 16;  // query rows per KV head: (H / H_kv) * N, the columns of one MFMA
+constexpr int kFusedMaxRows = 16;         // query rows per KV head: (H / H_kv) * N, the columns of one MFMA
+constexpr int kFusedMaxSoftmaxRows = 4096;  // L * H * N: their log-sum-exps are held in LDS in phase 2
+
+// arrivals of the call in flight; the finishing workgroup puts it back to zero
+static __device__ unsigned int fused_arrivals;
 
 struct FusedDev {
   int M, L, N, H, H_kv, G, d, layer_reduce;
+  int M_pad;       // keys rounded up to whole workgroups (64)
   float scale;
   int64_t ts, hs;  // token / head stride of the K cache, elements
   const uint16_t* q;
   const int32_t* n_valid;
   float* scores;
   float* lse_out;
+  float* logit2;   // workspace [L * H_kv][rows][M_pad]: base-2 logits
+  float* part_m;   // workspace [L * H_kv][rows][M_pad / 16]: max of a tile's logits
+  float* part_z;   //           ... and the sum of exp2(logit - that max)
   SelDev sel;
   const uint16_t* k[SP_MAX_LAYERS];
 };
@@ -53,173 +61,200 @@ __device__ __forceinline__ float dpp_f32(float v) {
 }
 struct OpMax { static __device__ __forceinline__ float f(float a, float b) { return fmaxf(a, b); } };
 struct OpAdd { static __device__ __forceinline__ float f(float a, float b) { return a + b; } };
-// Reduction over aligned groups of `lanes` (1, 2, 4, 8 or 16) lanes; every lane of the group gets
-// the result.  Lane ^ 1, lane ^ 2 inside the quad, then the mirrored half row and the mirrored row.
+// Reduction over aligned groups of 16 lanes; every lane of the group gets the result.
+// Lane ^ 1, lane ^ 2 inside the quad, then the mirrored half row and the mirrored row.
 template <class Op>
-__device__ __forceinline__ float group_reduce(float v, int lanes) {
-  if (lanes >= 2) v = Op::f(v, dpp_f32<0xB1>(v));
-  if (lanes >= 4) v = Op::f(v, dpp_f32<0x4E>(v));
-  if (lanes >= 8) v = Op::f(v, dpp_f32<0x141>(v));
-  if (lanes >= 16) v = Op::f(v, dpp_f32<0x140>(v));
+__device__ __forceinline__ float reduce16(float v) {
+  v = Op::f(v, dpp_f32<0xB1>(v));
+  v = Op::f(v, dpp_f32<0x4E>(v));
+  v = Op::f(v, dpp_f32<0x141>(v));
+  v = Op::f(v, dpp_f32<0x140>(v));
   return v;
 }
 
-template <int D, int KK>  // KK: 64-key blocks per wave (1: up to 1024 keys, 2: up to 2048)
+__device__ __forceinline__ void store_f32_agent(float* dst, float v) { store32_agent(dst, __float_as_uint(v)); }
+
+template <int D>
 __global__ __launch_bounds__(kFusedThreads) void fused_short_kernel(const FusedDev p) {
-  constexpr int TPW = 4 * KK;  // 16-key tiles per wave
-  constexpr int PB = 2 / KK;   // (layer, KV head) pairs per batch: PB * TPW * 4 logits per lane
-  constexpr int KS = D / 32;   // MFMA steps along the head dim
-  static_assert(PB * 16 * 16 <= kFusedThreads, "16 lanes per softmax row in the second level");
+  constexpr int KS = D / 32;  // MFMA steps along the head dim
   __shared__ double wide[kFusedMaxKeys];  // first the pooled scores, then (as 64-bit keys) the selection's keys
   static_assert(kFusedMaxKeys >= kSingleMaxChunks, "the selection's keys reuse the pooled scores' room");
-  __shared__ float red_m[PB * 16 * kFusedWaves], red_z[PB * 16 * kFusedWaves], row_m[PB * 16], row_z[PB * 16];
   __shared__ float score_lds[kFusedMaxKeys];
-  __shared__ double cs_lds[kSingleMaxChunks];
+  // the softmax rows' log-sum-exps, later the chunk scores
+  __shared__ __align__(16) unsigned char lse_or_cs[kSingleMaxChunks * sizeof(double)];
+  static_assert(kFusedMaxSoftmaxRows * sizeof(float) <= sizeof(lse_or_cs), "the log-sum-exps must fit");
+  __shared__ unsigned int ticket;
+  __shared__ unsigned short item_tab[kFusedMaxSoftmaxRows];  // phase 2b's order of softmax rows, with marks
+  constexpr int kRowMask = 0x0fff, kLayerEnds = 0x4000, kQueryEnds = 0x8000;
+  static_assert(kFusedMaxSoftmaxRows <= kRowMask + 1, "a row number must fit under the marks");
+  float* lse_lds = reinterpret_cast<float*>(lse_or_cs);
+  double* cs_lds = reinterpret_cast<double*>(lse_or_cs);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = lane & 15, kg = lane >> 4;  // operand row / column; 8-element group of the head dim
-  const int rows = p.G * p.N;               // <= 16; query row r = (query) * G + (head of the group)
+  const int rows = p.G * p.N;  // <= 16; query row r = (query) * G + (head of the group)
   const int pairs = p.L * p.H_kv;
-  const float scale2 = p.scale * 1.44269504088896341f;  // logits in units of ln 2
-  const int tile0 = wave * TPW;             // the wave's keys: tiles tile0 .. tile0 + TPW - 1
-  // logit c[t][j] of this lane: query row n, key (tile0 + t) * 16 + 4 * kg + j
-  auto key_of = [&](int t, int j) { return (tile0 + t) * 16 + 4 * kg + j; };
+  const int tiles = p.M_pad >> 4;
+  const float scale2 = p.scale * 1.44269504088896341f;  // logits in units of ln 2: exp2 is one instruction
 
-  float tot[TPW][4], lmax[TPW][4];  // over the layers / this layer's max over heads
-#pragma unroll
-  for (int t = 0; t < TPW; ++t)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      tot[t][j] = (p.layer_reduce == SP_LAYER_MAX) ? -INFINITY : 0.f;
-      lmax[t][j] = -INFINITY;
-    }
-
-  for (int b0 = 0; b0 < pairs; b0 += PB) {
-    f32x4 c[PB][TPW];
-#pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-      const int pair = b0 + pb;
-#pragma unroll
-      for (int t = 0; t < TPW; ++t) c[pb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (pair >= pairs) continue;
+  // ---- phase 1: logits and tile partials of 64 keys ----
+  {
+    const int n = lane & 15, kg = lane >> 4;  // operand row / column; 8-element group of the head dim
+    const int tile = blockIdx.x * 4 + (wave & 3);
+    const int key0 = tile * 16 + 4 * kg;      // the lane's logits: query row n, keys key0 .. key0 + 3
+    const int krow = min(tile * 16 + n, p.M - 1);  // rows past the end read the last key again; masked below
+    for (int pair = wave >> 2; pair < pairs; pair += 4) {
       const int l = pair / p.H_kv, g = pair - l * p.H_kv;
-      bf16x8 qv[KS];  // column n of the query operand (zero beyond the last query row)
-      {
-        const int nn = n < rows ? n : 0;
-        const int nq = nn / p.G, j = nn - nq * p.G;
-        const uint16_t* qp = p.q + (((int64_t)l * p.N + nq) * p.H + g * p.G + j) * D + 8 * kg;
+      const int nn = n < rows ? n : 0;
+      const int nq = nn / p.G, j = nn - nq * p.G;
+      const uint16_t* qp = p.q + (((int64_t)l * p.N + nq) * p.H + g * p.G + j) * D + 8 * kg;
+      const uint16_t* kp = p.k[l] + (int64_t)g * p.hs + (int64_t)krow * p.ts + 8 * kg;
+      uint4 qv[KS], kv[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          uint4 v = *reinterpret_cast<const uint4*>(qp + 32 * ks);
-          if (n >= rows) v = make_uint4(0, 0, 0, 0);
-          qv[ks] = __builtin_bit_cast(bf16x8, v);
+      for (int ks = 0; ks < KS; ++ks) {
+        qv[ks] = *reinterpret_cast<const uint4*>(qp + 32 * ks);
+        kv[ks] = *reinterpret_cast<const uint4*>(kp + 32 * ks);
+      }
+      f32x4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        if (n >= rows) qv[ks] = make_uint4(0, 0, 0, 0);  // columns beyond the last query row
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kv[ks]), __builtin_bit_cast(bf16x8, qv[ks]), c, 0, 0, 0);
+      }
+      float m = -INFINITY;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        c[jj] = key0 + jj < p.M ? scale2 * c[jj] : -INFINITY;
+        m = fmaxf(m, c[jj]);
+      }
+      m = fmaxf(m, __shfl_xor(m, 16));
+      m = fmaxf(m, __shfl_xor(m, 32));  // -inf for a tile wholly past the end of the prompt
+      float z = 0.f;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) z += (m == -INFINITY) ? 0.f : exp2f(c[jj] - m);
+      z += __shfl_xor(z, 16);
+      z += __shfl_xor(z, 32);
+      if (n < rows) {
+        const int64_t row = (int64_t)pair * rows + n;
+        store128_agent(p.logit2 + row * p.M_pad + key0, u32x4{__float_as_uint(c[0]), __float_as_uint(c[1]), __float_as_uint(c[2]), __float_as_uint(c[3])});
+        if (kg == 0) {
+          store_f32_agent(p.part_m + row * tiles + tile, m);
+          store_f32_agent(p.part_z + row * tiles + tile, z);
         }
-      }
-      // Four tiles at a time: all their loads first (rows past the end of the prompt read the
-      // last key again and are masked below), so that one round trip covers the group.
-      const uint16_t* kbase = p.k[l] + (int64_t)g * p.hs + 8 * kg;
-#pragma unroll
-      for (int t0 = 0; t0 < TPW; t0 += 4) {
-        uint4 kv[4][KS];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int row = min((tile0 + t0 + t) * 16 + n, p.M - 1);
-          const uint16_t* kp = kbase + (int64_t)row * p.ts;
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) kv[t][ks] = *reinterpret_cast<const uint4*>(kp + 32 * ks);
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks)
-            c[pb][t0 + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kv[t][ks]), qv[ks], c[pb][t0 + t], 0, 0, 0);
-      }
-      // base-2 logits from here on: exp2 is one instruction
-#pragma unroll
-      for (int t = 0; t < TPW; ++t)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) c[pb][t][j] = key_of(t, j) < p.M ? scale2 * c[pb][t][j] : -INFINITY;
-    }
-
-    // (max, sum exp) of the batch's PB * 16 softmax rows over the workgroup
-#pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-      float wm = -INFINITY;
-#pragma unroll
-      for (int t = 0; t < TPW; ++t)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) wm = fmaxf(wm, c[pb][t][j]);
-      wm = fmaxf(wm, __shfl_xor(wm, 16));
-      wm = fmaxf(wm, __shfl_xor(wm, 32));
-      float wz = 0.f;
-#pragma unroll
-      for (int t = 0; t < TPW; ++t)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) wz += (wm == -INFINITY) ? 0.f : exp2f(c[pb][t][j] - wm);
-      wz += __shfl_xor(wz, 16);
-      wz += __shfl_xor(wz, 32);
-      if (lane < 16) { red_m[(pb * 16 + lane) * kFusedWaves + wave] = wm; red_z[(pb * 16 + lane) * kFusedWaves + wave] = wz; }
-    }
-    __syncthreads();
-    if (tid < PB * 16 * kFusedWaves) {  // 16 lanes per row, one per wave's pair of values
-      const float wm = red_m[tid], wz = red_z[tid];
-      const float bm = group_reduce<OpMax>(wm, 16);
-      const float bz = group_reduce<OpAdd>((wm == -INFINITY) ? 0.f : wz * exp2f(wm - bm), 16);
-      if ((tid & 15) == 0) { row_m[tid >> 4] = bm; row_z[tid >> 4] = bz; }
-    }
-    __syncthreads();
-
-#pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-      const int pair = b0 + pb;
-      if (pair >= pairs) continue;
-      const int l = pair / p.H_kv, g = pair - l * p.H_kv;
-      const float lse = row_m[pb * 16 + n] + log2f(row_z[pb * 16 + n]);  // base 2
-      if (p.lse_out && tid < rows) {
-        const int nq = tid / p.G, j = tid - nq * p.G;
-        p.lse_out[((int64_t)l * p.N + nq) * p.H + g * p.G + j] = 0.69314718055994531f * lse;
-      }
-#pragma unroll
-      for (int t = 0; t < TPW; ++t)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          lmax[t][j] = fmaxf(lmax[t][j], group_reduce<OpMax>(c[pb][t][j] - lse, p.G));  // over the group's heads
-      if (g == p.H_kv - 1) {  // the layer is complete
-#pragma unroll
-        for (int t = 0; t < TPW; ++t)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (p.layer_reduce == SP_LAYER_MAX) tot[t][j] = fmaxf(tot[t][j], lmax[t][j]);
-            else tot[t][j] += exp2f(lmax[t][j]);
-            lmax[t][j] = -INFINITY;
-          }
       }
     }
   }
 
-  // mean over the valid queries: the lanes of a query's first head carry its value
+  // ---- count in; all but the last to arrive are done ----
+  wait_vmcnt<0>();  // this thread's workspace stores have been performed
+  __syncthreads();
+  if (tid == 0) ticket = atomicAdd(&fused_arrivals, 1u);
+  __syncthreads();
+  if (ticket != gridDim.x - 1) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // nothing read below may come from before the count
+  if (tid == 0) __hip_atomic_store(&fused_arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+  // Reads of what other workgroups wrote cost a trip to memory each (microseconds): the first
+  // logits phase 2b needs are requested now, so that they travel together with 2a's partials.
   int nv = p.n_valid ? p.n_valid[0] : p.N;
   nv = max(1, min(nv, p.N));
-  const bool counts = n < rows && n % p.G == 0 && n / p.G < nv;
-  const float inv_denom = 1.f / ((p.layer_reduce == SP_LAYER_MAX) ? (float)nv : (float)nv * (float)p.L);
+  const int heads_total = p.L * p.H;   // head f of all layers: softmax row (f / G) * rows + nq * G + f % G
+  const int items = nv * heads_total;  // per key, item i: query i / heads_total, head i % heads_total
+  // (divisions are dear: each item's row and its end-of-layer / end-of-query marks are tabulated once)
+  for (int i = tid; i < items; i += kFusedThreads) {
+    const int nq = i / heads_total, f = i - nq * heads_total;
+    const int row = (f / p.G) * rows + nq * p.G + f % p.G;
+    item_tab[i] = (unsigned short)(row | ((f + 1) % p.H == 0 ? kLayerEnds : 0) | (f + 1 == heads_total ? kQueryEnds : 0));
+  }
+  __syncthreads();
+  constexpr int kAhead = 16;
+  float ahead[kAhead];
 #pragma unroll
-  for (int t = 0; t < TPW; ++t)
+  for (int u = 0; u < kAhead; ++u)
+    ahead[u] = p.logit2[(int64_t)(item_tab[min(u, items - 1)] & kRowMask) * p.M_pad + min(tid, p.M - 1)];
+
+  // ---- phase 2a: row log-sum-exps (base 2) from the tile partials, 16 lanes per row ----
+  const int softmax_rows = pairs * rows;
+  constexpr int kPartsPerLane = kFusedMaxKeys / 16 / 16;  // a row's tiles, dealt to 16 lanes
+  for (int r0 = 0; r0 < softmax_rows; r0 += kFusedThreads / 16) {
+    const int row = r0 + (tid >> 4), sub = tid & 15;
+    const bool live = row < softmax_rows;
+    float pm[kPartsPerLane], pz[kPartsPerLane];  // all loads first: one round trip
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float mine = (p.layer_reduce == SP_LAYER_MAX) ? exp2f(tot[t][j]) : tot[t][j];
-      const float sc = group_reduce<OpAdd>(counts ? mine : 0.f, 16) * inv_denom;
-      const int key = key_of(t, j);
-      if (n == 0 && key < p.M) {
-        score_lds[key] = sc;
-        p.scores[key] = sc;
+    for (int u = 0; u < kPartsPerLane; ++u) {
+      const int x = sub + 16 * u;
+      const bool has = live && x < tiles;
+      const int64_t at = has ? (int64_t)row * tiles + x : 0;
+      pm[u] = p.part_m[at];
+      pz[u] = p.part_z[at];
+      if (!has) { pm[u] = -INFINITY; pz[u] = 0.f; }
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < kPartsPerLane; ++u) m = fmaxf(m, pm[u]);
+    m = reduce16<OpMax>(m);  // finite for a live row: its first tile has a key
+    float z = 0.f;
+#pragma unroll
+    for (int u = 0; u < kPartsPerLane; ++u) z += (pm[u] == -INFINITY) ? 0.f : pz[u] * exp2f(pm[u] - m);
+    z = reduce16<OpAdd>(z);
+    if (live && sub == 0) {
+      const float lse2 = m + log2f(z);
+      lse_lds[row] = lse2;
+      if (p.lse_out) {
+        const int pair = row / rows, r = row - pair * rows;
+        const int l = pair / p.H_kv, g = pair - l * p.H_kv, nq = r / p.G, j = r - nq * p.G;
+        p.lse_out[((int64_t)l * p.N + nq) * p.H + g * p.G + j] = 0.69314718055994531f * lse2;
       }
     }
+  }
   __syncthreads();
 
-  // Sec. 3.2.3 on the scores in LDS; the same fp64 arithmetic in the same order as sp_pool_select
+  // ---- phase 2b: the scores, one key per thread at a time ----
+  const float denom = (p.layer_reduce == SP_LAYER_MAX) ? (float)nv : (float)nv * (float)p.L;
+  for (int key = tid; key < p.M; key += kFusedThreads) {
+    float acc = 0.f;
+    float over_layers = (p.layer_reduce == SP_LAYER_MAX) ? -INFINITY : 0.f;
+    float lm = -INFINITY;  // max over the layer's heads of log2 p
+    for (int i0 = 0; i0 < items; i0 += kAhead) {
+      float v[kAhead];
+      if (i0 == 0 && key == tid) {
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) v[u] = ahead[u];
+      } else {
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) v[u] = p.logit2[(int64_t)(item_tab[min(i0 + u, items - 1)] & kRowMask) * p.M_pad + key];
+      }
+      int entry[kAhead];
+      float lse[kAhead];  // (no branches here: the table and log-sum-exp reads go out together)
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) entry[u] = item_tab[min(i0 + u, items - 1)];
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) lse[u] = lse_lds[entry[u] & kRowMask];
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) {
+        if (i0 + u >= items) entry[u] = 0, v[u] = -INFINITY;
+        lm = fmaxf(lm, v[u] - lse[u]);
+        if (entry[u] & kLayerEnds) {
+          if (p.layer_reduce == SP_LAYER_MAX) over_layers = fmaxf(over_layers, lm);
+          else over_layers += exp2f(lm);
+          lm = -INFINITY;
+        }
+        if (entry[u] & kQueryEnds) {
+          acc += (p.layer_reduce == SP_LAYER_MAX) ? exp2f(over_layers) : over_layers;
+          over_layers = (p.layer_reduce == SP_LAYER_MAX) ? -INFINITY : 0.f;
+        }
+      }
+    }
+    const float sc = acc / denom;
+    score_lds[key] = sc;
+    p.scores[key] = sc;
+  }
+  __syncthreads();
+
+  // ---- phase 2c: Sec. 3.2.3 on the scores in LDS; the same fp64 arithmetic in the same order as sp_pool_select ----
   const SelDev& sp_ = p.sel;
   for (int i = tid; i < p.M; i += kFusedThreads) {
     const int a = max(0, i - sp_.radius), e = min(p.M - 1, i + sp_.radius);
     double sum = 0.0;
+#pragma unroll 8
     for (int x = a; x <= e; ++x) sum += (double)score_lds[x];
     wide[i] = sum / (double)(e - a + 1);
   }
@@ -228,6 +263,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_short_kernel(const FusedD
   for (int j = tid; j < n_chunks; j += kFusedThreads) {
     const int s0 = j * sp_.chunk, s1 = min(s0 + sp_.chunk, p.M);
     double t = 0.0;
+#pragma unroll 8
     for (int x = s0; x < s1; ++x) t += wide[x];
     const double mean = t / (double)(s1 - s0);
     cs_lds[j] = mean;
@@ -237,11 +273,19 @@ __global__ __launch_bounds__(kFusedThreads) void fused_short_kernel(const FusedD
   select_emit_single(sp_, cs_lds, reinterpret_cast<uint64_t*>(wide));
 }
 
-template <int D>
-static sp_status launch_fused(const FusedDev& dev, hipStream_t stream) {
-  if (dev.M <= kFusedThreads) hipLaunchKernelGGL((fused_short_kernel<D, 1>), dim3(1), dim3(kFusedThreads), 0, stream, dev);
-  else hipLaunchKernelGGL((fused_short_kernel<D, 2>), dim3(1), dim3(kFusedThreads), 0, stream, dev);
-  return launch_status();
+static bool fused_shape_ok(const sp_score_args* a) {
+  if (a->B != 1 || a->T < 1 || a->T > kFusedMaxKeys || a->rope_theta != 0.f || a->d_block_table) return false;
+  if (a->H_kv < 1 || a->H % a->H_kv != 0 || (a->d != 64 && a->d != 128)) return false;
+  const int G = a->H / a->H_kv;
+  if (G * a->N > kFusedMaxRows || (int64_t)a->L * a->H * a->N > kFusedMaxSoftmaxRows) return false;
+  return true;
+}
+
+size_t fused_workspace_bytes(const sp_score_args* a) {
+  if (!fused_shape_ok(a)) return 0;
+  const size_t m_pad = ((size_t)a->T + 63) / 64 * 64;
+  const size_t softmax_rows = (size_t)a->L * a->H * a->N;
+  return align_up(softmax_rows * m_pad * sizeof(float), 256) + 2 * align_up(softmax_rows * (m_pad / 16) * sizeof(float), 256);
 }
 
 }  // namespace sp
@@ -249,7 +293,7 @@ static sp_status launch_fused(const FusedDev& dev, hipStream_t stream) {
 extern "C" sp_status sp_score_pool_select(const sp_score_args* a, const sp_pool_select_args* s, void* hip_stream) {
   using namespace sp;
   if (!a || !s) return SP_ENULL;
-  // each half is checked as the separate calls check it (workspaces are not needed here)
+  // each half is checked as the separate calls check it (the selection's workspace is not needed here)
   if (a->B < 1 || a->N < 1 || a->N > SP_MAX_QUERIES || a->L < 1 || a->L > SP_MAX_LAYERS) return SP_EINVAL;
   if (a->H < 1 || a->H_kv < 1 || a->H % a->H_kv != 0) return SP_EINVAL;
   if (a->d != 64 && a->d != 128) return SP_EINVAL;
@@ -268,12 +312,11 @@ extern "C" sp_status sp_score_pool_select(const sp_score_args* a, const sp_pool_
   if (s->chunk < 1 || s->pool_window < 1 || (s->pool_window & 1) == 0) return SP_EINVAL;
   if (!finite_f64(s->keep_rate) || s->keep_rate <= 0.0 || s->keep_rate > 1.0 || s->kept_capacity < 0) return SP_EINVAL;
   if (!s->d_kept_idx || !s->d_cu_keep) return SP_ENULL;
-  // what one workgroup can hold
-  const int G = a->H / a->H_kv, rows = G * a->N;
-  if ((G & (G - 1)) != 0) return SP_EUNSUPPORTED;  // the heads of a KV group sit in an aligned run of lanes
-  if (a->B != 1 || a->T < 1 || a->T > kFusedMaxKeys || rows > kFusedMaxRows || a->rope_theta != 0.f || a->d_block_table ||
-      (a->T + s->chunk - 1) / s->chunk > kSingleMaxChunks)
-    return SP_EUNSUPPORTED;
+  // what the single launch covers
+  if (!fused_shape_ok(a) || (a->T + s->chunk - 1) / s->chunk > kSingleMaxChunks) return SP_EUNSUPPORTED;
+  const size_t need = fused_workspace_bytes(a);
+  if (!a->d_workspace || a->workspace_bytes < need) return SP_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(a->d_workspace) & 255u) return SP_EALIGN;
 
   FusedDev dev;
   dev.M = (int)a->T; dev.L = a->L; dev.N = a->N; dev.H = a->H; dev.H_kv = a->H_kv; dev.G = a->H / a->H_kv; dev.d = a->d;
@@ -284,6 +327,16 @@ extern "C" sp_status sp_score_pool_select(const sp_score_args* a, const sp_pool_
   dev.n_valid = a->d_n_valid;
   dev.scores = a->d_scores;
   dev.lse_out = a->d_lse;
+  dev.M_pad = (dev.M + 63) / 64 * 64;
+  {
+    const size_t softmax_rows = (size_t)a->L * a->H * a->N;
+    char* ws = static_cast<char*>(a->d_workspace);
+    dev.logit2 = reinterpret_cast<float*>(ws);
+    ws += align_up(softmax_rows * dev.M_pad * sizeof(float), 256);
+    dev.part_m = reinterpret_cast<float*>(ws);
+    ws += align_up(softmax_rows * (dev.M_pad / 16) * sizeof(float), 256);
+    dev.part_z = reinterpret_cast<float*>(ws);
+  }
   for (int l = 0; l < SP_MAX_LAYERS; ++l) dev.k[l] = l < a->L ? static_cast<const uint16_t*>(a->k_layers[l]) : nullptr;
   SelDev& p = dev.sel;
   p.B = 1; p.T = (int)a->T; p.chunk = s->chunk; p.radius = (s->pool_window - 1) / 2;
@@ -292,5 +345,8 @@ extern "C" sp_status sp_score_pool_select(const sp_score_args* a, const sp_pool_
   p.chunk_scores_out = s->d_chunk_scores;
   p.cu_chunks = nullptr; p.seq_keep = nullptr; p.cs = nullptr; p.chunk_off = nullptr;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  return a->d == 64 ? launch_fused<64>(dev, stream) : launch_fused<128>(dev, stream);
+  const dim3 grid(dev.M_pad / 64), block(kFusedThreads);
+  if (a->d == 64) hipLaunchKernelGGL((fused_short_kernel<64>), grid, block, 0, stream, dev);
+  else hipLaunchKernelGGL((fused_short_kernel<128>), grid, block, 0, stream, dev);
+  return launch_status();
 }

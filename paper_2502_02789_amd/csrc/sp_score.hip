@@ -380,7 +380,8 @@ extern "C" size_t sp_score_workspace_bytes(const sp_score_args* a) {
   const bool single = sp::single_pass_wanted(a);
   const size_t general = sp::general_workspace_bytes(a, /*with_tiled=*/!single);
   const size_t stream = single ? std::max(sp::stream_workspace_bytes(a), sp::team_workspace_bytes(a)) : 0;
-  return general > stream ? general : stream;
+  // (sp_score_pool_select takes its logits' room from the same workspace)
+  return std::max(std::max(general, stream), sp::fused_workspace_bytes(a));
 }
 
 static sp_status check_score_args(const sp_score_args* a) {

@@ -56,4 +56,7 @@ size_t team_workspace_bytes(const sp_score_args* a);
 sp_status team_score(const sp_score_args* a, hipStream_t stream);
 size_t team_status_offset(const sp_score_args* a);
 
+// single-launch scoring + selection of one short prompt (sp_fused.hip); 0 if the shape is not covered
+size_t fused_workspace_bytes(const sp_score_args* a);
+
 }  // namespace sp

@@ -127,6 +127,7 @@ __device__ __forceinline__ void select_emit_single(const SelDev& p, const double
     if (t < n) {
       const uint64_t mine = keys[t];
       int rank = 0;
+#pragma unroll 8
       for (int j = 0; j < n; ++j) {
         const uint64_t other = keys[j];
         rank += (other > mine || (other == mine && j < t)) ? 1 : 0;

@@ -39,7 +39,8 @@ def _run_fused(w, inp, mode, chunk, window, rate, n_valid=None, head_major=False
     dict(number=1, seqlens=(1333,), H=8, H_kv=2, N=2, n_valid=1),      # eight rows per KV head, one valid query
     dict(number=3, seqlens=(777,), L=2, H=8, H_kv=8, N=8, n_valid=5),  # head dim 128, one head per KV head
     dict(number=1, seqlens=(1100,), H=8, H_kv=1, N=2, n_valid=2),      # sixteen rows: every column of the operand
-    dict(number=3, seqlens=(2000,), L=2, H=4, H_kv=2, N=3, n_valid=2), # head dim 128, two key blocks per wave, six rows
+    dict(number=3, seqlens=(2000,), L=2, H=4, H_kv=2, N=3, n_valid=2), # head dim 128, six rows
+    dict(number=1, seqlens=(333,), L=5, H=6, H_kv=2, N=4, n_valid=3),  # three heads per KV head, more pairs than waves take at once
     dict(number=1, seqlens=(600,), H=4, H_kv=1, N=1, chunk=1, window=1, rate=0.1),   # the raw variant
     dict(number=1, seqlens=(1500,), chunk=48, window=7, rate=0.33, head_major=True),
 ])
@@ -90,7 +91,7 @@ def test_fused_refuses_what_one_workgroup_cannot_hold():
     from paper_2502_02789_amd import binding as sp, device as dev
     lib = sp.load_library()
     for changes in (dict(seqlens=(2049,)), dict(seqlens=(300, 200)), dict(seqlens=(500,), H=8, H_kv=1, N=3),
-                    dict(seqlens=(500,), N=9), dict(seqlens=(500,), H=6, H_kv=2)):
+                    dict(seqlens=(500,), N=9)):
         w = synth.scaled(synth.workload(1), **changes)
         inp = synth.make_qk(w)
         q = dev.bf16_from_bits(inp["q"])
