@@ -148,9 +148,11 @@ class Problem:
         if w.embed_dim:
             embed = dev.bf16_from_bits(synth.make_embedding(w.vocab, w.embed_dim, w.seed, threads=threads))
         self.t_gen = time.perf_counter() - t0
-        # the benchmark box runs nothing else on its GPU: the single-pass kernels may be used
+        # the benchmark box runs nothing else on its GPU: the single-pass kernels may be used; the
+        # workspace is this object's alone, as a serving loop's would be, so from the second call on
+        # sp_score is told that it still holds what the call before left (SP_SCORE_WORKSPACE_KEPT)
         self.scorer = dev.Scorer(q, ks, cu, H_kv=w.H_kv, scale=1.0 / math.sqrt(w.d), layer_reduce=mode,
-                                 exclusive_device=True)
+                                 exclusive_device=True, keep_workspace=True)
         cap = sp.sp_keep_upper_bound(list(w.seqlens), w.chunk, w.keep_rate)
         self.sel = dev.Selector(self.scorer.scores, cu, chunk=w.chunk, pool_window=w.pool_window,
                                 keep_rate=w.keep_rate, capacity=cap)
@@ -202,7 +204,7 @@ def side_measurement(number, layer_reduce, steps, warmup):
     pr = Problem(number, layer_reduce)
     w = pr.w
     _, score_ms, sel_ms, gat_ms = pr.timed(steps, warmup)
-    sp.sp_score_check(pr.scorer.args)
+    pr.scorer.check()
     fast = pr.scorer.scores.cpu().numpy().astype(np.float64)
     pr.scorer.run(pr.stream, general=True)
     torch.cuda.synchronize()
@@ -314,12 +316,17 @@ def main():
     # what was timed is what gets checked: the outputs of the last timed step
     timeout_status = "ok"
     try:
-        sp.sp_score_check(pr.scorer.args)
+        pr.scorer.check()
     except sp.SpError as e:
         timeout_status = str(e)
     gpu_scores = pr.scorer.scores.cpu().numpy()
     gpu_kept = pr.sel.kept_idx.cpu().numpy()
     gpu_cu_keep = pr.sel.cu_keep.cpu().numpy()
+    # the same steps on a workspace that is taken as new by every call (the flag never set)
+    pr.scorer._keep = False
+    fresh_score_ms = pr.timed(max(10, args.steps // 2), 5, general=args.general)[1]
+    pr.scorer._keep = True
+    fresh_matches = bool((pr.scorer.scores.cpu().numpy() == gpu_scores).all() or args.general)
 
     k_bytes = w.k_bytes()
     algo_bytes = k_bytes + 4 * w.T                  # K cache read once + fp32 score per token written
@@ -337,7 +344,8 @@ def main():
             "workload": f"{w.name}: B={w.B} T={w.T} L={w.L} H={w.H} H_kv={w.H_kv} d={w.d} N={w.N} "
                         f"chunk={w.chunk} keep_rate={w.keep_rate} pool_window={w.pool_window}",
             "layer_reduce": args.layer_reduce, "k_cache_bytes": k_bytes, "kept_tokens": n_keep,
-            "score_kernels": "general" if args.general else "auto", "flags": "SP_SCORE_EXCLUSIVE_DEVICE",
+            "score_kernels": "general" if args.general else "auto",
+            "flags": "SP_SCORE_EXCLUSIVE_DEVICE | SP_SCORE_WORKSPACE_KEPT (from the second call on)",
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -345,6 +353,8 @@ def main():
             "traffic": measured_traffic(args.workload, args.general, args.layer_reduce),
             "kernel": "sp_score (all its launches)", "avg_ms": score_avg_ms, "median_ms": score_ms[len(score_ms) // 2],
             "algorithmic_bytes": algo_bytes,
+            "avg_ms_without_workspace_kept": sum(fresh_score_ms) / len(fresh_score_ms),
+            "same_scores_without_workspace_kept": fresh_matches,
         },
         "select_gather_ms": sel_avg_ms + gat_avg_ms,
         "sp_pool_select_us": sel_avg_ms * 1e3, "sp_gather_us": gat_avg_ms * 1e3,
@@ -357,7 +367,7 @@ def main():
     out["roofline"].update(probe.stream_ceiling(pr.scorer.k_layers))
     out["roofline"]["frac_of_stream_ceiling"] = achieved / out["roofline"]["stream_ceiling_gbps"]
 
-    ok = timeout_status == "ok"
+    ok = timeout_status == "ok" and fresh_matches
     oracle_scores = None
     if not args.skip_cpu:
         out["cpu_baseline"], oracle_scores = cpu_baseline(w, pr.inp, 0 if args.layer_reduce == "max" else 1,

@@ -69,6 +69,17 @@ typedef enum { SP_LAYER_MAX = 0, SP_LAYER_MEAN = 1 } sp_layer_reduce;
                                         If the promise is broken a bounded wait can expire; the
                                         affected scores are then NaN (see sp_score_check and
                                         sp_pool_select), never silently wrong. */
+#define SP_SCORE_WORKSPACE_KEPT 2u   /* The caller promises that args->d_workspace was last written by
+                                        an sp_score call with the same shape fields (B, T, N, L, H,
+                                        H_kv, d, layer_reduce, paging) that completed without
+                                        SP_ETIMEOUT, and has not been touched since.  A single-pass
+                                        call leaves its exchange area ready for the next call, so
+                                        the kernel that re-initialises it can then be skipped (a
+                                        few microseconds per call in a serving loop that keeps its
+                                        workspace).  The first call on a workspace, and the call
+                                        after a time-out, must not set it.  Other kernels ignore
+                                        it.  With a broken promise waits expire or scores are
+                                        wrong. */
 
 /* ---------------------------------------------------------------------------
  * sp_score: compute_attention_score + aggregate_attention_score (Algorithm 1),

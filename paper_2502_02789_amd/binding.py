@@ -16,6 +16,7 @@ SP_EINVAL, SP_ENULL, SP_EALIGN, SP_EWORKSPACE, SP_EUNSUPPORTED, SP_ELAUNCH, SP_E
 SP_LAYER_MAX, SP_LAYER_MEAN = 0, 1
 SP_MAX_LAYERS, SP_MAX_QUERIES = 128, 16
 SP_SCORE_EXCLUSIVE_DEVICE = 1
+SP_SCORE_WORKSPACE_KEPT = 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecprefill.so")
 

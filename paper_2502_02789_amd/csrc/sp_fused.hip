@@ -300,7 +300,7 @@ extern "C" sp_status sp_score_pool_select(const sp_score_args* a, const sp_pool_
   if (a->T < 0 || a->T >= (int64_t)INT32_MAX) return SP_EINVAL;
   if (a->layer_reduce != SP_LAYER_MAX && a->layer_reduce != SP_LAYER_MEAN) return SP_EINVAL;
   if (!finite_f32(a->scale) || a->scale <= 0.f || !finite_f32(a->rope_theta) || a->rope_theta < 0.f) return SP_EINVAL;
-  if (a->flags & ~(uint32_t)SP_SCORE_EXCLUSIVE_DEVICE) return SP_EINVAL;
+  if (a->flags & ~(uint32_t)(SP_SCORE_EXCLUSIVE_DEVICE | SP_SCORE_WORKSPACE_KEPT)) return SP_EINVAL;
   if (!a->d_q || !a->k_layers || !a->d_cu_seqlens || !a->d_scores) return SP_ENULL;
   for (int l = 0; l < a->L; ++l)
     if (!a->k_layers[l]) return SP_ENULL;

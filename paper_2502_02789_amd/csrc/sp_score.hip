@@ -248,7 +248,8 @@ __global__ __launch_bounds__(256) void score_accum_kernel(const ScoreDev p) {
   }
 }
 
-__global__ void clear_word_kernel(uint32_t* word) { *word = 0; }
+// the status words (and, for the team kernel's layout, its epoch: sp_score_check then looks at word 1)
+__global__ void clear_word_kernel(uint32_t* word) { word[0] = word[1] = word[2] = word[3] = 0; }
 
 // ---------------------------------------------------------------------------------------
 // host side
@@ -394,7 +395,7 @@ static sp_status check_score_args(const sp_score_args* a) {
   if (a->rope_theta == 0.f && a->d_q_pos != nullptr) return SP_EINVAL;
   if (a->rope_theta > 0.f && a->d_q_pos == nullptr) return SP_ENULL;
   if (!sp::finite_f32(a->scale) || a->scale <= 0.f) return SP_EINVAL;
-  if (a->flags & ~(uint32_t)SP_SCORE_EXCLUSIVE_DEVICE) return SP_EINVAL;
+  if (a->flags & ~(uint32_t)(SP_SCORE_EXCLUSIVE_DEVICE | SP_SCORE_WORKSPACE_KEPT)) return SP_EINVAL;
   if (a->k_token_stride < 0 || a->k_head_stride < 0) return SP_EINVAL;
   if (a->d_block_table) {
     if (a->page_size < 8 || (a->page_size & (a->page_size - 1)) != 0 || a->blocks_per_seq < 1) return SP_EINVAL;
@@ -424,10 +425,12 @@ extern "C" sp_status sp_score_check(const sp_score_args* a, void* hip_stream) {
   if (hipStreamSynchronize(stream) != hipSuccess) return SP_ELAUNCH;
   const size_t off = sp::single_pass_wanted(a) ? sp::single_pass_status_offset(a) : 0;
   if (off == 0) return SP_OK;
-  uint32_t word = 0;
-  if (hipMemcpy(&word, static_cast<const char*>(a->d_workspace) + off, sizeof(word), hipMemcpyDeviceToHost) !=
+  uint32_t words[4] = {0, 0, 0, 0};  // (every single-pass workspace has 256 bytes at `off`)
+  if (hipMemcpy(words, static_cast<const char*>(a->d_workspace) + off, sizeof(words), hipMemcpyDeviceToHost) !=
       hipSuccess)
     return SP_ELAUNCH;
+  // the team kernel keeps one status word per epoch parity and has moved on to the next epoch
+  const uint32_t word = sp::team_supported(a) ? words[(words[2] + 1u) & 1u] : words[0];
   return word == 0 ? SP_OK : SP_ETIMEOUT;
 }
 

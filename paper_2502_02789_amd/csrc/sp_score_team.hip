@@ -50,11 +50,16 @@ struct TeamDev : StreamShape {
   int TC, lgTC;       // teams; team = workgroup % TC, index in team = workgroup / TC
   int P;              // workgroups per team (a multiple of 32, at most kTeamMaxPartners)
   int M_pad;          // P * KPW
-  uint32_t* partial;  // [team][slab][partner][32]: base-2 log-sum-exp of the partner's keys, per row
+  uint32_t* partial;  // two copies of [team][slab][partner][32]: base-2 log-sum-exp of the partner's
+                      // keys, per row.  A call works in copy (epoch & 1) and leaves the other one
+                      // "empty" for the call after it.
+  size_t partial_words;  // 32-bit words of one copy
   float* part;        // [team][N][M_pad]: the team's max over its heads and all layers of log2 p
   uint32_t* arrived;  // [P]: how many of the TC workgroups that own key slice j are done (+ 65536 per
                       // workgroup one of whose waits expired); zero at the start of the call
-  uint32_t* status;   // [0] != 0: a bounded wait ran out (results invalid)
+  uint32_t* status;   // [epoch & 1] != 0: a bounded wait of this call ran out (results invalid); [2]: epoch,
+                      // the number of calls this workspace has served since it was last filled; [3]: key
+                      // slices finished (zero at the start of the call)
   const int32_t* n_valid;
   float* scores;
   float* lse_out;
@@ -71,6 +76,9 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
 
   const TeamDev& p;
   int team, pidx;
+  uint32_t epoch;          // of this call
+  uint32_t* partial_cur;   // the exchange lines of this call
+  uint32_t* partial_nxt;   // ... and of the next one
   uint32_t dep_lds;   // LDS: [NSETS][32 rows][8 waves] each wave's base-2 log-sum-exp of the row over its keys
   uint32_t ctl_lds;   // LDS control block: words 0..7 arrival counters per set; 8 last slab whose row
                       // log-sum-exps are in LDS (-1: none); 9 last slab this workgroup has published
@@ -90,6 +98,9 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
         p(p_) {
     team = blockIdx.x & (p.TC - 1);
     pidx = blockIdx.x >> p.lgTC;
+    epoch = __builtin_amdgcn_readfirstlane(p.status[2]);  // (changed only after every workgroup is past this point)
+    partial_cur = p.partial + (size_t)(epoch & 1u) * p.partial_words;
+    partial_nxt = p.partial + (size_t)(~epoch & 1u) * p.partial_words;
     const uint32_t smem_lds = (uint32_t)reinterpret_cast<uintptr_t>(smem);
     dep_lds = smem_lds + RING_BYTES;
     ctl_lds = dep_lds + NSETS * kTeamDepBytes;
@@ -136,9 +147,13 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
     if (ln < 32) {
       const u32x4 a = lds_peek128(dep + ln * 32), b = lds_peek128(dep + ln * 32 + 16);
       const float out = lse2_of8(a, b);  // (-inf -- no key of the prompt in this workgroup -- is a value, not "empty")
-      store32_agent(p.partial + ((int64_t)(team * p.n_slabs + slab) * p.P + pidx) * 32 + ln, __float_as_uint(out));
+      const int64_t at = ((int64_t)(team * p.n_slabs + slab) * p.P + pidx) * 32 + ln;
+      store32_agent(partial_cur + at, __float_as_uint(out));
+      // the same line of the other copy: "empty" again for the call after this one (nobody reads
+      // that copy during this call, and the end of the kernel makes the store visible)
+      asm volatile("global_store_dword %0, %1, off" : : "v"(partial_nxt + at), "v"(kEmpty32) : "memory");
     }
-    note_issued(1);
+    note_issued(2);
     if (ln == 0) lds_poke32(ctl_lds + 36, (uint32_t)slab);
   }
 
@@ -177,7 +192,7 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
     asm volatile("" : "+v"(ln));
     const bool sampled = __builtin_amdgcn_readfirstlane(lds_peek(ctl_lds + 44)) != 0;
     const int groups = p.P >> 3;
-    const unsigned char* src = reinterpret_cast<const unsigned char*>(p.partial + (int64_t)(team * p.n_slabs + r) * p.P * 32) + ln * 16;
+    const unsigned char* src = reinterpret_cast<const unsigned char*>(partial_cur + (int64_t)(team * p.n_slabs + r) * p.P * 32) + ln * 16;
     const u32x4 fill = {kPending32, kPending32, kPending32, kPending32};
     if (!sampled) {
 #pragma unroll 1  // rare path: keep its register appetite small
@@ -311,6 +326,7 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
   if (threadIdx.x < 16)  // arrival counters, lock and flag: 0; "last slab done / published": none
     *reinterpret_cast<uint32_t*>(smem + Tm::RING_BYTES + NSETS * kTeamDepBytes + threadIdx.x * 4) =
         (threadIdx.x == 8 || threadIdx.x == 9) ? ~0u : 0u;
+  if (blockIdx.x == 0 && threadIdx.x == 0) p.status[~tm.epoch & 1u] = 0;  // the next call's status word
   __syncthreads();
 
   tm.template issue_stream<0>(0, 0);
@@ -386,7 +402,7 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
   }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
   if (tm.expired && tm.lane == 0) {  // a wait of this wave gave up
-    atomicOr(p.status, 1u);
+    atomicOr(p.status + (tm.epoch & 1u), 1u);
     lds_or(tm.ctl_lds + 48, 1u);
   }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -415,6 +431,13 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
   __syncthreads();
   const uint32_t count = __builtin_amdgcn_readfirstlane(lds_peek(tm.ctl_lds + 52));
   if ((int)(count & 65535u) != p.TC) return;  // somebody else will be last
+  if (threadIdx.x == 0) {  // leave the workspace as the next call expects it; the last slice of all turns the epoch
+    p.arrived[tm.pidx] = 0;
+    if (atomicAdd(p.status + 3, 1u) == (uint32_t)p.P - 1u) {
+      p.status[3] = 0;
+      p.status[2] = tm.epoch + 1u;
+    }
+  }
   const bool void_result = (count >> 16) != 0;  // a wait expired in one of the TC workgroups: no score of this slice can be trusted
   int nv = p.n_valid ? p.n_valid[0] : p.N;
   nv = max(1, min(nv, p.N));
@@ -463,7 +486,7 @@ __global__ __launch_bounds__(256) void team_fill_kernel(uint4* __restrict__ dst,
     dst[i] = make_uint4(kEmpty32, kEmpty32, kEmpty32, kEmpty32);
   if (blockIdx.x == 0) {
     for (int i = threadIdx.x; i < n_arrived; i += 256) arrived[i] = 0;
-    if (threadIdx.x == 0) status[0] = 0;
+    if (threadIdx.x < 4) status[threadIdx.x] = 0;  // both status words, the epoch, the slice count
   }
 }
 
@@ -536,13 +559,13 @@ bool team_supported(const sp_score_args* a) { return make_team_plan(a, team_devi
 size_t team_workspace_bytes(const sp_score_args* a) {
   const TeamPlan pl = make_team_plan(a, kMaxWG);  // sized for the full chip
   if (!pl.ok) return 0;
-  return pl.partial_bytes + pl.part_bytes + 256 + 256;  // + status word + arrival counts
+  return 2 * pl.partial_bytes + pl.part_bytes + 256 + 256;  // + status words and epoch + arrival counts
 }
 
 // byte offset of the status word inside the workspace, or 0 if the shape does not use this kernel
 size_t team_status_offset(const sp_score_args* a) {
   const TeamPlan pl = make_team_plan(a, team_device_cu_count());
-  return pl.ok ? pl.partial_bytes + pl.part_bytes : 0;
+  return pl.ok ? 2 * pl.partial_bytes + pl.part_bytes : 0;
 }
 
 template <int D, int TPW, bool PAGED>
@@ -610,18 +633,23 @@ sp_status team_score(const sp_score_args* a, hipStream_t stream) {
   dev.M_pad = pl.M_pad;
   char* ws = static_cast<char*>(a->d_workspace);
   dev.partial = reinterpret_cast<uint32_t*>(ws);
-  dev.part = reinterpret_cast<float*>(ws + pl.partial_bytes);
-  dev.status = reinterpret_cast<uint32_t*>(ws + pl.partial_bytes + pl.part_bytes);
-  dev.arrived = reinterpret_cast<uint32_t*>(ws + pl.partial_bytes + pl.part_bytes + 256);  // kTeamMaxPartners words
+  dev.partial_words = pl.partial_bytes / 4;
+  dev.part = reinterpret_cast<float*>(ws + 2 * pl.partial_bytes);
+  dev.status = reinterpret_cast<uint32_t*>(ws + 2 * pl.partial_bytes + pl.part_bytes);
+  dev.arrived = reinterpret_cast<uint32_t*>(ws + 2 * pl.partial_bytes + pl.part_bytes + 256);  // kTeamMaxPartners words
   dev.n_valid = a->d_n_valid;
   dev.scores = a->d_scores;
   dev.lse_out = a->d_lse;
 
-  const size_t n_vec = pl.partial_bytes / 16;
-  const int fill_blocks = (int)std::min<size_t>((n_vec + 255) / 256, 1024);
-  hipLaunchKernelGGL(team_fill_kernel, dim3(fill_blocks), dim3(256), 0, stream, reinterpret_cast<uint4*>(ws), n_vec,
-                     dev.arrived, dev.P, dev.status);
-  if (hipGetLastError() != hipSuccess) return SP_ELAUNCH;
+  if (!(a->flags & SP_SCORE_WORKSPACE_KEPT)) {
+    // epoch 0: the first copy of the exchange lines "empty", counts and status clear.  (A call
+    // leaves all of that behind in the state the next call needs, one epoch on.)
+    const size_t n_vec = pl.partial_bytes / 16;
+    const int fill_blocks = (int)std::min<size_t>((n_vec + 255) / 256, 1024);
+    hipLaunchKernelGGL(team_fill_kernel, dim3(fill_blocks), dim3(256), 0, stream, reinterpret_cast<uint4*>(ws), n_vec,
+                       dev.arrived, dev.P, dev.status);
+    if (hipGetLastError() != hipSuccess) return SP_ELAUNCH;
+  }
   sp_status st;
   if (a->d_block_table) {
     if (a->d == 128) st = pl.TPW == 1 ? launch_team<128, 1, true>(dev, pl, stream) : launch_team<128, 2, true>(dev, pl, stream);

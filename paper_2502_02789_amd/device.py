@@ -39,9 +39,13 @@ class Scorer:
                  n_valid: Optional[torch.Tensor] = None, want_lse: bool = False,
                  rope_theta: float = 0.0, q_pos: Optional[torch.Tensor] = None,
                  block_table: Optional[torch.Tensor] = None, page_size: int = 0, total_tokens: Optional[int] = None,
-                 exclusive_device: bool = True):
+                 exclusive_device: bool = True, keep_workspace: bool = False):
         """exclusive_device: promise that nothing else runs on the GPU during the call
-        (SP_SCORE_EXCLUSIVE_DEVICE), which lets sp_score take its single-pass kernels."""
+        (SP_SCORE_EXCLUSIVE_DEVICE), which lets sp_score take its single-pass kernels.
+        keep_workspace: from the second run() on, pass SP_SCORE_WORKSPACE_KEPT (this object owns
+        its workspace, so the promise holds as long as run() is the only thing that writes it;
+        anything else that does -- run(general=True), score_pool_select, a failed check() --
+        makes the next run() start from a fresh workspace again)."""
         L, B, N, H, d = q.shape
         T = int(k_layers[0].shape[0]) if block_table is None else int(total_tokens)
         self.block_table = block_table
@@ -63,9 +67,29 @@ class Scorer:
                                        workspace=self.workspace, rope_theta=rope_theta, q_pos=q_pos, T=T,
                                        block_table=block_table, page_size=page_size, flags=flags)
 
+        self._base_flags, self._keep, self._kept = flags, keep_workspace, False
+
+    def forget_workspace(self):
+        """The workspace has been written by something other than sp_score."""
+        self._kept = False
+
     def run(self, stream=None, general: bool = False) -> torch.Tensor:
-        (sp.sp_score_general if general else sp.sp_score)(self.args, stream)
+        if general:
+            self._kept = False
+            sp.sp_score_general(self.args, stream)
+            return self.scores
+        self.args.flags = self._base_flags | (sp.SP_SCORE_WORKSPACE_KEPT if self._keep and self._kept else 0)
+        sp.sp_score(self.args, stream)
+        self._kept = True
         return self.scores
+
+    def check(self, stream=None):
+        """sp_score_check; raises SpError(SP_ETIMEOUT) if a bounded wait of the last run expired."""
+        try:
+            sp.sp_score_check(self.args, stream)
+        except sp.SpError:
+            self._kept = False
+            raise
 
 
 class Selector:
@@ -102,6 +126,7 @@ class Selector:
 def score_pool_select(scorer: Scorer, selector: Selector, stream=None):
     """One short prompt scored and selected in a single launch (sp_score_pool_select); the selector
     must have been built on scorer.scores and the same cu_seqlens."""
+    scorer.forget_workspace()  # the logits pass through it
     sp.sp_score_pool_select(scorer.args, selector.args, stream)
     return scorer.scores, selector.kept_idx, selector.cu_keep
 

@@ -139,7 +139,7 @@ def test_argument_errors_launch_nothing():
     assert status(N=17) == sp.SP_EINVAL
     assert status(H_kv=3) == sp.SP_EINVAL
     assert status(layer_reduce=2) == sp.SP_EINVAL
-    assert status(flags=2) == sp.SP_EINVAL                        # an unknown flag bit
+    assert status(flags=4) == sp.SP_EINVAL                        # an unknown flag bit
     assert status(scale=float("nan")) == sp.SP_EINVAL
     assert status(d_q=None) == sp.SP_ENULL
     assert status(d_scores=None) == sp.SP_ENULL
@@ -243,6 +243,58 @@ def test_expired_wait_is_impossible_to_miss(tokens):
     want, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, orc.LAYER_MAX)
     hp.assert_scores_close(s.scores.cpu().numpy(), want, "after the bound was restored")
     assert int(sel.cu_keep[1]) > 0 and (gat.kept_pos[:int(sel.cu_keep[1])] >= 0).all()
+
+
+@pytest.mark.parametrize("shape", [dict(tokens=9001, L=3), dict(tokens=16500, L=2, H=8, H_kv=8)])
+def test_kept_workspace_over_consecutive_calls(shape):
+    """SP_SCORE_WORKSPACE_KEPT: a single-pass call leaves its exchange area ready for the next
+    one, so from the second call on the kernel that re-initialises it is skipped.  Five calls in a
+    row on one workspace (epochs of both parities), a time-out in between (after which the
+    workspace starts afresh), the other entry points that write the workspace: every result is
+    checked against the oracle, and a kept call's scores equal a fresh call's bit for bit."""
+    import torch
+    from paper_2502_02789_amd import binding as sp, device as dev
+    shape = dict(shape)
+    w = synth.scaled(synth.workload(3), seqlens=(shape.pop("tokens"),), **shape)
+    inp = synth.make_qk(w)
+    scale = 1.0 / math.sqrt(w.d)
+    want, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, orc.LAYER_MAX)
+    q = dev.bf16_from_bits(inp["q"])
+    ks = [dev.bf16_from_bits(k) for k in inp["k"]]
+    cu = torch.from_numpy(inp["cu_seqlens"]).cuda()
+    s = dev.Scorer(q, ks, cu, H_kv=w.H_kv, scale=scale, keep_workspace=True)
+    first = None
+    for call in range(5):
+        s.scores.fill_(float("nan"))
+        s.run()
+        assert bool(s.args.flags & sp.SP_SCORE_WORKSPACE_KEPT) == (call > 0)
+        s.check()
+        got = s.scores.cpu().numpy()
+        hp.assert_scores_close(got, want, f"call {call}")
+        first = got if first is None else first
+        assert np.array_equal(got, first), call
+    # a call whose waits give up leaves the workspace in no particular state: the next one starts afresh
+    before = sp.sp_set_wait_budget(0)
+    try:
+        s.run()
+        with pytest.raises(sp.SpError):
+            s.check()
+    finally:
+        sp.sp_set_wait_budget(before)
+    for call in range(3):
+        s.scores.fill_(float("nan"))
+        s.run()
+        assert bool(s.args.flags & sp.SP_SCORE_WORKSPACE_KEPT) == (call > 0)
+        s.check()
+        assert np.array_equal(s.scores.cpu().numpy(), first), call
+    # the two-pass kernels write the same workspace
+    s.run(general=True)
+    s.check()
+    s.scores.fill_(float("nan"))
+    s.run()
+    assert not (s.args.flags & sp.SP_SCORE_WORKSPACE_KEPT)
+    s.check()
+    assert np.array_equal(s.scores.cpu().numpy(), first)
 
 
 @pytest.mark.parametrize("shape", [
