@@ -25,13 +25,17 @@
 //   * no wave ever waits through vmcnt for any of this; a wave waits (bounded, by polling LDS) only
 //     if the log-sum-exps of slab s - NSETS are not there when it is about to reuse the registers;
 //   * at the end each workgroup writes its [query][key] maxima of log2-probabilities to a per-team
-//     array, and a small second kernel takes the maximum over teams, exponentiates and averages
-//     over the valid queries.
+//     array and counts itself in; of the TC workgroups that own the same keys the one that arrives
+//     last takes the maximum over teams, exponentiates and averages over the valid queries.
 //
 // Publications per workgroup and slab: one full line instead of 32 scattered 16-byte stores;
 // coherent reads: P lines once (plus re-reads of late lines) instead of a two-hop chain.  Words
-// are "empty" (all ones) until written, written and read with agent-scope coherence; a small
-// kernel refills the exchange area at the start of each call.  As in the other single-pass
+// are "empty" (all ones) until written, written and read with agent-scope coherence.  The
+// exchange lines exist twice: a call works in one copy and, line by line as it publishes, puts
+// "empty" back into the other, so the next call finds its copy clean (the epoch word in the
+// workspace says which is which; counters and status words are handed on the same way).  A small
+// kernel sets all of that up in front of a call that cannot rely on the previous one
+// (no SP_SCORE_WORKSPACE_KEPT).  As in the other single-pass
 // kernel all workgroups must be resident together (the caller's SP_SCORE_EXCLUSIVE_DEVICE
 // promise), every wait is bounded, and an expired wait turns the call's scores into NaN.
 #include <atomic>
