@@ -195,9 +195,11 @@ class Problem:
         return n_keep * (row + 4 * 4)
 
 
-def side_measurement(number, layer_reduce, steps, warmup):
+def side_measurement(number, layer_reduce, steps, warmup, raw_cache_too=False):
     """GPU-only timing of another workload / layer reduction (no oracle leg), cross-checked
-    against the library's plain two-pass kernels on the same inputs."""
+    against the library's plain two-pass kernels on the same inputs.  raw_cache_too: the same
+    buffers once more taken as an UN-rotated cache that sp_score rotates itself (rope_theta > 0),
+    cross-checked the same way."""
     import numpy as np
     import torch
     from paper_2502_02789_amd import binding as sp
@@ -221,6 +223,38 @@ def side_measurement(number, layer_reduce, steps, warmup):
         "sp_gather_gbps": pr.gather_bytes() / (g_avg * 1e-3) / 1e9,
         "max_rel_diff_vs_plain_kernels": rel, "ok": bool(rel <= 2 * SCORE_RTOL),
     }
+    if raw_cache_too:
+        from paper_2502_02789_amd import device as dev
+        old = pr.scorer
+        q_pos = torch.tensor([[m + n for n in range(w.N)] for m in w.seqlens], dtype=torch.int32, device="cuda")
+        mode = sp.SP_LAYER_MAX if layer_reduce == "max" else sp.SP_LAYER_MEAN
+        pr.scorer = None
+        del old.workspace
+        raw = dev.Scorer(old.q, old.k_layers, old.cu, H_kv=w.H_kv, scale=1.0 / math.sqrt(w.d), layer_reduce=mode,
+                         rope_theta=5e5, q_pos=q_pos, exclusive_device=True)
+        ms = []
+        for i in range(warmup + steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(pr.stream)
+            raw.run(pr.stream)
+            b.record(pr.stream)
+            if i >= warmup:
+                ms.append((a, b))
+        torch.cuda.synchronize()
+        ms = [a.elapsed_time(b) for a, b in ms]
+        fast = raw.scores.cpu().numpy().astype(np.float64)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(pr.stream)
+        raw.run(pr.stream, general=True)
+        b.record(pr.stream)
+        torch.cuda.synchronize()
+        out["raw_cache_plain_kernels_us"] = a.elapsed_time(b) * 1e3
+        plain = raw.scores.cpu().numpy().astype(np.float64)
+        rel = float((np.abs(fast - plain) / np.maximum(np.abs(plain), 1e-300)).max())
+        out["raw_cache_rotated_by_sp_score_us"] = sum(ms) / len(ms) * 1e3
+        out["raw_cache_max_rel_diff_vs_plain_kernels"] = rel
+        out["ok"] = bool(out["ok"] and rel <= 2 * SCORE_RTOL)
+        del raw
     del pr
     torch.cuda.empty_cache()
     return out
@@ -390,7 +424,8 @@ def main():
         torch.cuda.empty_cache()
         also = []
         for number, mode in ((3, "mean" if args.layer_reduce == "max" else "max"), (2, "max"), (5, "max"), (4, "max")):
-            also.append(side_measurement(number, mode, steps=20, warmup=40 if number != 4 else 10))
+            also.append(side_measurement(number, mode, steps=20, warmup=40 if number != 4 else 10,
+                                         raw_cache_too=(number == 4)))
             ok = ok and also[-1]["ok"]
         also.append(short_prompt_measurement(steps=50, warmup=20))
         ok = ok and also[-1]["ok"]

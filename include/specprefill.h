@@ -116,9 +116,14 @@ typedef struct {
                                 un-rotated and are rotated here, rotate-half pairing
                                 (t, t + d/2), angle pos * theta^(-2t/d): key i of a sequence
                                 at position i, query row n of sequence b at d_q_pos[b*N+n];
-                                cosine/sine in fp32, rotated values rounded to bf16, then
-                                everything as for rope_theta = 0.  Runs the general kernels
-                                and needs the larger workspace the size query reports.     */
+                                cosine/sine in fp32 (angle formed in fp64), the two products
+                                and their sum separate fp32 operations, rotated values
+                                rounded to bf16 (nearest even): bit for bit what a cache
+                                rotated that way would hold, then everything as for
+                                rope_theta = 0.  Runs the two-pass kernels (the keys are
+                                turned in registers on their way to the matrix cores; the
+                                single-pass kernels take rotated caches only) and needs the
+                                larger workspace the size query reports.                    */
   const int32_t* d_q_pos;    /* int32 [B, N] query positions if rope_theta > 0, else NULL  */
   float* d_scores;           /* out fp32 [T]                                              */
   float* d_lse;              /* out fp32 [L, B, N, H] row log-sum-exp, or NULL            */

@@ -23,16 +23,6 @@ __global__ __launch_bounds__(1024) void tile_table_kernel(int B, const int32_t* 
   block_prefix_table(B, [&](int b) { return (cu[b + 1] - cu[b] + kTileKeys - 1) / kTileKeys; }, tile_cu);
 }
 
-// fp32 -> bf16 (round to nearest even) -> fp32: what storing a rotated value in a bf16 cache does
-__device__ __forceinline__ float round_to_bf16(float x) {
-  const uint32_t u = __float_as_uint(x);
-  return __uint_as_float((u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u);
-}
-__device__ __forceinline__ uint16_t bf16_bits(float x) {
-  const uint32_t u = __float_as_uint(x);
-  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
-}
-
 // Rotary encoding of one un-rotated row held in registers: pair (t, t + D/2) turns by the
 // angle whose (cos, sin) is rope_row[t]; results are rounded as a bf16 cache would hold them.
 template <int D>
@@ -40,9 +30,9 @@ __device__ __forceinline__ void rope_row_inplace(float (&kf)[D], const float2* _
 #pragma unroll
   for (int t = 0; t < D / 2; ++t) {
     const float2 cs = rope_row[t];
-    const float lo = kf[t], hi = kf[t + D / 2];
-    kf[t] = round_to_bf16(lo * cs.x - hi * cs.y);
-    kf[t + D / 2] = round_to_bf16(hi * cs.x + lo * cs.y);
+    const float2 turned = rope_turn(kf[t], kf[t + D / 2], cs);
+    kf[t] = turned.x;
+    kf[t + D / 2] = turned.y;
   }
 }
 
@@ -53,10 +43,7 @@ __global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ ta
   if (i >= n) return;
   const int t = (int)(i % half);
   const double pos = (double)(i / half);
-  const double inv_freq = exp2(-((double)t / (double)half) * log2_theta);
-  double sn, cs;
-  sincos(pos * inv_freq, &sn, &cs);
-  table[i] = make_float2((float)cs, (float)sn);
+  table[i] = rope_cos_sin(pos, t, half, log2_theta);
 }
 
 // rotated copy of the un-rotated queries [L, B, N, H, d]; one thread per (row, pair)
@@ -69,14 +56,12 @@ __global__ __launch_bounds__(256) void rope_q_kernel(const uint16_t* __restrict_
   const int64_t row = i / half;               // ((l * B + b) * N + nq) * H + h
   const int nq = (int)((row / H) % N);
   const int b = (int)((row / ((int64_t)H * N)) % B);
-  const double inv_freq = exp2(-((double)t / (double)half) * log2_theta);
-  double sn, cs;
-  sincos((double)q_pos[b * N + nq] * inv_freq, &sn, &cs);
-  const float c = (float)cs, s = (float)sn;
+  const float2 cs = rope_cos_sin((double)q_pos[b * N + nq], t, half, log2_theta);
   const uint16_t* src = q_raw + row * 2 * half;
   const float lo = __uint_as_float((uint32_t)src[t] << 16), hi = __uint_as_float((uint32_t)src[t + half] << 16);
-  q_rot[row * 2 * half + t] = bf16_bits(lo * c - hi * s);
-  q_rot[row * 2 * half + t + half] = bf16_bits(hi * c + lo * s);
+  const float2 turned = rope_turn(lo, hi, cs);
+  q_rot[row * 2 * half + t] = (uint16_t)(__float_as_uint(turned.x) >> 16);
+  q_rot[row * 2 * half + t + half] = (uint16_t)(__float_as_uint(turned.y) >> 16);
 }
 
 template <int D>
@@ -314,10 +299,11 @@ sp_status general_score(const sp_score_args* a, hipStream_t stream, bool allow_m
     float2* table = reinterpret_cast<float2*>(ws);
     ws += align_up(sizeof(float2) * (size_t)a->T * (a->d / 2), 256);
     uint16_t* q_rot = reinterpret_cast<uint16_t*>(ws);
+    ws += align_up(sizeof(uint16_t) * (size_t)a->L * a->B * a->N * a->H * a->d, 256);
     const double log2_theta = std::log2((double)a->rope_theta);
     const int half = a->d / 2;
     const int64_t n_tab = a->T * half;
-    if (n_tab > 0)
+    if (n_tab > 0 && !(allow_mfma && tiled_supported(a)))  // (the MFMA kernels bring a table in their own layout)
       hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n_tab + 255) / 256)), dim3(256), 0, stream, table, n_tab,
                          half, log2_theta);
     const int64_t n_q = (int64_t)a->L * a->B * a->N * a->H * half;
@@ -328,7 +314,7 @@ sp_status general_score(const sp_score_args* a, hipStream_t stream, bool allow_m
   }
 
   hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(1024), 0, stream, p.B, p.cu, p.tile_cu);
-  if (allow_mfma && tiled_supported(a)) {  // (never with an un-rotated cache: ws is this path's own part)
+  if (allow_mfma && tiled_supported(a)) {
     const sp_status st = tiled_score(a, p, ws, stream);
     clear_stream_status(a, stream);
     return st != SP_OK ? st : launch_status();

@@ -30,6 +30,38 @@ struct ScoreDev {
 
 void fill_score_dev(const sp_score_args* a, ScoreDev* p);
 
+// Rotary position encoding of an un-rotated cache (rope_theta > 0): the pair (t, t + d/2) of a row
+// at position pos turns by pos * theta^(-2t/d).  The angle is formed in fp64, its cosine and sine
+// are rounded to fp32, the two products and their sum or difference are separate fp32
+// operations, and the result is rounded to bf16 (nearest even) as a cache would hold it -- every
+// kernel that rotates goes through these two functions, so all of them produce the same bits.
+__device__ __forceinline__ float2 rope_cos_sin(double pos, int t, int half, double log2_theta) {
+  const double inv_freq = exp2(-((double)t / (double)half) * log2_theta);
+  double sn, cs;
+  sincos(pos * inv_freq, &sn, &cs);
+  return make_float2((float)cs, (float)sn);
+}
+// lo, hi: the pair's values (exact bf16 values held as fp32); returns the rotated pair before rounding
+__device__ __forceinline__ float2 rope_turn_exact(float lo, float hi, float2 cs) {
+#pragma clang fp contract(off)
+  const float a = lo * cs.x, b = hi * cs.y, c = hi * cs.x, d = lo * cs.y;
+  return make_float2(a - b, c + d);
+}
+// ... and rounded to bf16 (nearest even), as fp32 values
+__device__ __forceinline__ float2 rope_turn(float lo, float hi, float2 cs) {
+  const float2 r = rope_turn_exact(lo, hi, cs);
+  const uint32_t ul = __float_as_uint(r.x), uh = __float_as_uint(r.y);
+  return make_float2(__uint_as_float((ul + 0x7FFFu + ((ul >> 16) & 1u)) & 0xFFFF0000u),
+                     __uint_as_float((uh + 0x7FFFu + ((uh >> 16) & 1u)) & 0xFFFF0000u));
+}
+// two fp32 values -> two bf16 (nearest even) in one word, `even` in the low half: one instruction on gfx950
+__device__ __forceinline__ uint32_t pack_bf16_pair(float even, float odd) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  const f32x2_t v = {even, odd};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 // general two-pass kernels (sp_score.hip)
 size_t general_workspace_bytes(const sp_score_args* a, bool with_tiled);
 bool single_pass_wanted(const sp_score_args* a);

@@ -62,10 +62,55 @@ struct TiledDev {
   const int32_t* block_table;  // paged cache: [B][blocks_per_seq] page numbers, else null
   int lg_page, blocks_per_seq;
   int64_t page_stride;
+  // un-rotated cache: (cos, sin) of every position's rotation, in the order the waves consume it
+  // (see rope_tile_table_kernel), else null
+  const float4* rope_tiles;
   const uint16_t* k[SP_MAX_LAYERS];
 };
 
-template <int D>
+// (cos, sin) table for the MFMA kernels.  A lane of the key operand holds, for k-step t, the
+// eight elements 16t + 8*half + i of row `col`; their rotation partners (Sec. 3.2 scores need the
+// keys as the model sees them: rotated by their position) sit d/2 further on, i.e. in k-step
+// t + KS/2 of the same lane.  So per 32-key tile and t < KS/2 a lane needs eight (cos, sin) pairs:
+// four 16-byte loads, laid out here so that each of them is one dense 1 KiB wave-wide load:
+//   entry [((tile32 * KS/2 + t) * 4 + j) * 64 + half * 32 + col] = (cos, sin) of frequencies
+//   f = 16t + 8*half + 2j and f + 1 at position tile32 * 32 + col.
+// Positions are counted inside a sequence, so only those below the longest sequence are filled in
+// (the room is sized for one sequence of all T tokens).
+__global__ __launch_bounds__(256) void rope_tile_table_kernel(float4* __restrict__ table, int64_t n, int ks_half,
+                                                               int half_d, double log2_theta, int B,
+                                                               const int32_t* __restrict__ cu) {
+  __shared__ int longest;
+  if (threadIdx.x == 0) longest = 0;
+  __syncthreads();
+  int mine = 0;
+  for (int b = threadIdx.x; b < B; b += 256) mine = max(mine, cu[b + 1] - cu[b]);
+  if (mine > 0) atomicMax(&longest, mine);
+  __syncthreads();
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n || ((i >> 8) / ks_half) * 32 >= longest) return;
+  const int lane = (int)(i & 63), j = (int)((i >> 6) & 3);
+  const int t = (int)((i >> 8) % ks_half);
+  const int64_t tile32 = (i >> 8) / ks_half;
+  const int f = 16 * t + 8 * (lane >> 5) + 2 * j;
+  const double pos = (double)(tile32 * 32 + (lane & 31));
+  const float2 a = rope_cos_sin(pos, f, half_d, log2_theta), b = rope_cos_sin(pos, f + 1, half_d, log2_theta);
+  table[i] = make_float4(a.x, a.y, b.x, b.y);
+}
+
+// "at most n vector-memory instructions still in flight" for the kernels that also stream the
+// rotation table (more instructions per tile than wait_vmcnt_upto distinguishes)
+__device__ __forceinline__ void wait_vmcnt_upto_wide(int n) {
+  if (n >= 40) wait_vmcnt<40>();
+  else if (n >= 32) wait_vmcnt<32>();
+  else if (n >= 28) wait_vmcnt<28>();
+  else if (n >= 24) wait_vmcnt<24>();
+  else if (n >= 20) wait_vmcnt<20>();
+  else if (n >= 16) wait_vmcnt<16>();
+  else wait_vmcnt_upto(n);
+}
+
+template <int D, bool ROPE>
 struct TileWalker {
   static constexpr int KS = D / 16;            // MFMA k-steps per tile
   static constexpr int ROW_B = D * 2;          // bytes of one row (one key / one query row)
@@ -85,6 +130,7 @@ struct TileWalker {
   bf16x8 qf[KS];
   f32x16 acc[2];
   float run_m, run_s;
+  float4 cs[ROPE ? KS / 2 : 1][4];  // ROPE: the (cos, sin) pairs of the key tile that is rotated next
 
   __device__ __forceinline__ TileWalker(const TiledDev& p_, unsigned char* smem, int tile) : p(p_) {
     wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -124,7 +170,40 @@ struct TileWalker {
   __device__ __forceinline__ void note_issued(int k) { issued = __builtin_amdgcn_readfirstlane(issued + k); }
   __device__ __forceinline__ void mark_slot(int slot) { if (slot & 1) seq_b = issued; else seq_a = issued; }
   __device__ __forceinline__ void wait_tile(int slot) {
-    wait_vmcnt_upto(__builtin_amdgcn_readfirstlane(issued - ((slot & 1) ? seq_b : seq_a)));
+    const int newer = __builtin_amdgcn_readfirstlane(issued - ((slot & 1) ? seq_b : seq_a));
+    if (ROPE) wait_vmcnt_upto_wide(newer); else wait_vmcnt_upto(newer);
+  }
+  // ROPE: request the (cos, sin) pairs for key tile kb of this wave (the same for every slab; a
+  // tile wholly beyond the sequence takes tile 0's, its keys are masked anyway)
+  __device__ __forceinline__ void issue_rope(int kb) {
+    if constexpr (ROPE) {
+      const int tile32 = (key0 >> 5) + (kb * 32 < rows_in ? kb : 0);
+      const float4* src = p.rope_tiles + (int64_t)tile32 * (KS / 2) * 4 * 64 + lane;
+#pragma unroll
+      for (int t = 0; t < KS / 2; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cs[t][j] = src[(t * 4 + j) * 64];
+      note_issued(KS / 2 * 4);
+    }
+  }
+  // ROPE: turn the key operand in registers (kf[t] and kf[t + KS/2] hold the two halves of the pairs)
+  __device__ __forceinline__ void rotate_keys(bf16x8 (&kf)[KS]) {
+    if constexpr (ROPE) {
+#pragma unroll
+      for (int t = 0; t < KS / 2; ++t) {
+        u32x4 lo = __builtin_bit_cast(u32x4, kf[t]), hi = __builtin_bit_cast(u32x4, kf[t + KS / 2]);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {  // word w: elements 2w (low half) and 2w + 1 (high half)
+          const float4 c = cs[t][w];
+          const float2 e = rope_turn_exact(__uint_as_float(lo[w] << 16), __uint_as_float(hi[w] << 16), make_float2(c.x, c.y));
+          const float2 o = rope_turn_exact(__uint_as_float(lo[w] & 0xFFFF0000u), __uint_as_float(hi[w] & 0xFFFF0000u), make_float2(c.z, c.w));
+          lo[w] = pack_bf16_pair(e.x, o.x);
+          hi[w] = pack_bf16_pair(e.y, o.y);
+        }
+        kf[t] = __builtin_bit_cast(bf16x8, lo);
+        kf[t + KS / 2] = __builtin_bit_cast(bf16x8, hi);
+      }
+    }
   }
   // the slot is about to be overwritten: every LDS read of its previous tile must have been performed
   __device__ __forceinline__ void slot_free() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
@@ -241,6 +320,14 @@ struct TileWalker {
     bf16x8 kf[KS];
 #pragma unroll
     for (int t = 0; t < KS; ++t) kf[t] = read_unit(t, slot);
+    if constexpr (ROPE) {  // rotate, ask for the other tile's table (the registers are free now), multiply
+      rotate_keys(kf);
+      issue_rope(kb ^ 1);
+#pragma unroll
+      for (int t = 0; t < KS; ++t) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], a, 0, 0, 0);
+      acc[kb] = a;
+      return;
+    }
 #pragma unroll
     for (int t = 0; t < KS; ++t) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], a, 0, 0, 0);
     constexpr int kAhead = KS < 4 ? KS : 4;
@@ -361,10 +448,10 @@ struct SlabCursor {
   }
 };
 
-template <int D, int PASS, bool MEAN>
+template <int D, int PASS, bool MEAN, bool ROPE>
 __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledDev p) {
   extern __shared__ __align__(1024) unsigned char smem[];
-  using TW = TileWalker<D>;
+  using TW = TileWalker<D, ROPE>;
   const int tile = blockIdx.x * kTiledWaves + (threadIdx.x >> 6);
   if (tile >= p.tile_cu[p.B]) return;  // (no workgroup barrier anywhere in this kernel)
   const int l0 = blockIdx.y * p.layers_per_group;
@@ -400,6 +487,7 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
   int done = 0;  // pass 0: slabs whose statistics have been written out
   w.template issue_queries<PASS == 1>(l0, 0, 0, 0);
   w.issue_keys(l0, 0, 0, 1);
+  w.issue_rope(0);
   nxt.advance(p.H_kv, l1 - 1);
 
   auto body = [&](auto par_tag) __attribute__((always_inline)) {
@@ -621,7 +709,6 @@ static int padded_group(const sp_score_args* a) {
 }
 
 bool tiled_supported(const sp_score_args* a) {
-  if (a->rope_theta != 0.f) return false;  // un-rotated caches take the plain-FMA kernels
   if (a->H / a->H_kv > 8) return false;
   if (padded_group(a) * a->N > 32) return false;
   if (a->T < 1) return false;
@@ -642,18 +729,25 @@ static bool keep_mode(const sp_score_args* a) {
   return padded_group(a) * a->N <= kKeepMaxRows && keep_bytes(a) <= SP_TILED_KEEP_MAX_BYTES;
 }
 
-size_t tiled_extra_workspace_bytes(const sp_score_args* a) {
-  if (!tiled_supported(a)) return 0;
+static size_t tiled_main_workspace_bytes(const sp_score_args* a) {
   if (keep_mode(a)) return align_up(keep_bytes(a), 256);
   int lpg, groups;
   tiled_grouping(a, &lpg, &groups);
   return align_up(sizeof(float) * (size_t)groups * a->N * (size_t)a->T, 256);
 }
+// 16-byte entries of the rotation table: positions 0 .. T-1 in whole 32-key tiles
+static int64_t rope_tile_table_entries(const sp_score_args* a) { return (a->T + 31) / 32 * (a->d / 32) * 4 * 64; }
 
-template <int D, int PASS, bool MEAN>
+size_t tiled_extra_workspace_bytes(const sp_score_args* a) {
+  if (!tiled_supported(a)) return 0;
+  return tiled_main_workspace_bytes(a) +
+         (a->rope_theta > 0.f ? align_up(sizeof(float4) * (size_t)rope_tile_table_entries(a), 256) : 0);
+}
+
+template <int D, int PASS, bool MEAN, bool ROPE>
 static sp_status launch_tiled(const TiledDev& dev, hipStream_t stream) {
-  auto kernel = tiled_score_kernel<D, PASS, MEAN>;
-  const size_t smem = TileWalker<D>::smem_bytes();
+  auto kernel = tiled_score_kernel<D, PASS, MEAN, ROPE>;
+  const size_t smem = TileWalker<D, ROPE>::smem_bytes();
   static std::mutex mu;  // once per kernel and device
   static bool prepared[kMaxDevices] = {};
   {
@@ -671,10 +765,10 @@ static sp_status launch_tiled(const TiledDev& dev, hipStream_t stream) {
   return launch_status();
 }
 
-template <int D>
+template <int D, bool ROPE>
 static sp_status tiled_passes(const TiledDev& dev, const ScoreDev& gen, hipStream_t stream) {
   if (dev.logits) {
-    const sp_status st = launch_tiled<D, 2, false>(dev, stream);
+    const sp_status st = launch_tiled<D, 2, false, ROPE>(dev, stream);
     if (st != SP_OK) return st;
     launch_lse_combine(gen, stream);
     const dim3 grid((unsigned)((dev.T * 4 + 255) / 256));
@@ -682,10 +776,11 @@ static sp_status tiled_passes(const TiledDev& dev, const ScoreDev& gen, hipStrea
     else hipLaunchKernelGGL(logit_score_kernel<false>, grid, dim3(256), 0, stream, dev);
     return launch_status();
   }
-  sp_status st = launch_tiled<D, 0, false>(dev, stream);
+  sp_status st = launch_tiled<D, 0, false, ROPE>(dev, stream);
   if (st != SP_OK) return st;
   launch_lse_combine(gen, stream);
-  st = dev.layer_reduce == SP_LAYER_MEAN ? launch_tiled<D, 1, true>(dev, stream) : launch_tiled<D, 1, false>(dev, stream);
+  st = dev.layer_reduce == SP_LAYER_MEAN ? launch_tiled<D, 1, true, ROPE>(dev, stream)
+                                         : launch_tiled<D, 1, false, ROPE>(dev, stream);
   if (st != SP_OK) return st;
   hipLaunchKernelGGL(tiled_finish_kernel, dim3((unsigned)((dev.T + 255) / 256)), dim3(256), 0, stream, dev);
   return launch_status();
@@ -714,7 +809,16 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
   dev.block_table = gen.block_table; dev.lg_page = gen.lg_page; dev.blocks_per_seq = gen.blocks_per_seq;
   dev.page_stride = gen.k_page_stride;
   for (int l = 0; l < SP_MAX_LAYERS; ++l) dev.k[l] = gen.k[l];
-  return a->d == 64 ? tiled_passes<64>(dev, gen, stream) : tiled_passes<128>(dev, gen, stream);
+  dev.rope_tiles = nullptr;
+  if (a->rope_theta > 0.f) {  // the table follows this path's other workspace part
+    float4* table = reinterpret_cast<float4*>(static_cast<char*>(extra) + tiled_main_workspace_bytes(a));
+    const int64_t n = rope_tile_table_entries(a);
+    hipLaunchKernelGGL(rope_tile_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, table, n,
+                       a->d / 32, a->d / 2, std::log2((double)a->rope_theta), a->B, a->d_cu_seqlens);
+    dev.rope_tiles = table;
+    return a->d == 64 ? tiled_passes<64, true>(dev, gen, stream) : tiled_passes<128, true>(dev, gen, stream);
+  }
+  return a->d == 64 ? tiled_passes<64, false>(dev, gen, stream) : tiled_passes<128, false>(dev, gen, stream);
 }
 
 }  // namespace sp

@@ -357,9 +357,45 @@ def test_rotation_by_position_zero_changes_nothing():
     """All positions zero is the identity rotation: bit-identical to the already-rotated path."""
     q, k, cu, _ = _raw_inputs(12, (1,), 2, 8, 2, 64, 1)      # one key at position 0, one query at position 0
     zero_pos = np.zeros((1, 1), dtype=np.int32)
-    a, la = hp.gpu_score(q, k, cu, 2, 0.125, orc.LAYER_MAX, general=True)
-    b, lb = hp.gpu_score(q, k, cu, 2, 0.125, orc.LAYER_MAX, rope_theta=1e4, q_pos=zero_pos)
-    assert (a.view(np.uint32) == b.view(np.uint32)).all() and (la.view(np.uint32) == lb.view(np.uint32)).all()
+    for general in (True, False):   # the plain kernels, and the MFMA kernels sp_score picks for this shape
+        a, la = hp.gpu_score(q, k, cu, 2, 0.125, orc.LAYER_MAX, general=general)
+        b, lb = hp.gpu_score(q, k, cu, 2, 0.125, orc.LAYER_MAX, general=general, rope_theta=1e4, q_pos=zero_pos)
+        assert (a.view(np.uint32) == b.view(np.uint32)).all() and (la.view(np.uint32) == lb.view(np.uint32)).all()
+
+
+@pytest.mark.parametrize("shape", [
+    ((300, 1, 97, 64, 65), 3, 8, 8, 128, 1),     # one row per KV head: logits kept between the passes, head dim 128
+    ((1500,), 5, 12, 4, 64, 2),                   # three heads per KV head (padded to four), several layer groups
+    ((40, 2000), 2, 32, 8, 128, 8),               # thirty-two rows per KV head, both layer modes below
+])
+@pytest.mark.parametrize("mode", MODES)
+def test_mfma_kernels_rotate_like_the_plain_kernels(shape, mode):
+    """rope_theta > 0 on the MFMA kernels (keys turned in registers on their way to the matrix
+    cores) against the plain kernels, which turn them one row per lane: same rounding chain, so
+    the two agree as closely as they do on an already-rotated cache; and against the oracle."""
+    seqlens, L, H, H_kv, d, N = shape
+    theta = 5e5
+    q, k, cu, q_pos = _raw_inputs(13, seqlens, L, H, H_kv, d, N)
+    scale = 1.0 / math.sqrt(d)
+    fast, lse_fast = hp.gpu_score(q, k, cu, H_kv, scale, mode, rope_theta=theta, q_pos=q_pos, exclusive_device=False)
+    plain, lse_plain = hp.gpu_score(q, k, cu, H_kv, scale, mode, rope_theta=theta, q_pos=q_pos, general=True)
+    hp.assert_scores_close(fast, plain.astype(np.float64), f"MFMA vs plain kernels, raw cache {shape} mode={mode}")
+    np.testing.assert_allclose(lse_fast, lse_plain, rtol=0, atol=2e-4)
+    q_rot = np.stack([np.stack([orc.rope_rotate_bits(q[l, b], q_pos[b], theta) for b in range(len(seqlens))])
+                      for l in range(L)])
+    k_rot = []
+    for l in range(L):
+        kr = np.empty_like(k[l])
+        for b in range(len(seqlens)):
+            lo, hi = int(cu[b]), int(cu[b + 1])
+            kr[lo:hi] = orc.rope_rotate_bits(k[l][lo:hi], np.arange(hi - lo), theta)
+        k_rot.append(kr)
+    want, _ = orc.token_importance(q_rot, k_rot, cu, scale, mode)
+    hp.assert_scores_close(fast, want, f"MFMA kernels, raw cache {shape} mode={mode}")
+    # and the canonical path on the oracle-rotated cache gives the same scores bit for bit:
+    # rotating inside the kernel is the same as reading a rotated cache
+    canon, _ = hp.gpu_score(q_rot, k_rot, cu, H_kv, scale, mode, exclusive_device=False)
+    assert np.array_equal(fast.view(np.uint32), canon.view(np.uint32))
 
 
 # The ragged-batch MFMA kernels (what sp_score picks for B > 1): every tile-boundary case of
