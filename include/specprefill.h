@@ -71,8 +71,10 @@ typedef enum { SP_LAYER_MAX = 0, SP_LAYER_MEAN = 1 } sp_layer_reduce;
                                         sp_pool_select), never silently wrong. */
 #define SP_SCORE_WORKSPACE_KEPT 2u   /* The caller promises that args->d_workspace was last written by
                                         an sp_score call with the same shape fields (B, T, N, L, H,
-                                        H_kv, d, layer_reduce, paging) that completed without
-                                        SP_ETIMEOUT, and has not been touched since.  A single-pass
+                                        H_kv, d, layer_reduce, paging) and SP_SCORE_EXCLUSIVE_DEVICE
+                                        set that completed without SP_ETIMEOUT, and has not been
+                                        touched since (not by sp_score_general or
+                                        sp_score_pool_select either: they write it too).  A single-pass
                                         call leaves its exchange area ready for the next call, so
                                         the kernel that re-initialises it can then be skipped (a
                                         few microseconds per call in a serving loop that keeps its

@@ -83,9 +83,8 @@ __global__ __launch_bounds__(256) void pool_chunk_kernel(const SelDev p) {
 
 // One workgroup per sequence.
 __global__ __launch_bounds__(1024) void select_kernel(const SelDev p) {
-  __shared__ int hist[256];
-  __shared__ int sh[1024];
-  __shared__ int s_bucket, s_need;
+  __shared__ int hist[3 * 256];
+  __shared__ int sh[16];
   const int b = blockIdx.x, t = threadIdx.x;
   const int c0 = p.cu_chunks[b];
   const int n = p.cu_chunks[b + 1] - c0;
@@ -113,24 +112,9 @@ __global__ __launch_bounds__(1024) void select_kernel(const SelDev p) {
 
   // radix select: after the loop `prefix` is the key of the k-th largest chunk score and
   // `need` is how many chunks with exactly that score are still to be taken
-  uint64_t prefix = 0;
-  int need = k;
-  for (int pass = 7; pass >= 0; --pass) {
-    if (t < 256) hist[t] = 0;
-    __syncthreads();
-    const int shift = pass * 8;
-    const uint64_t himask = (pass == 7) ? 0ull : (~0ull << (shift + 8));
-    for (int j = t; j < n; j += 1024) {
-      const uint64_t key = order_key(cs[j]);
-      if ((key & himask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255u)], 1);
-    }
-    __syncthreads();
-    if (t < kWave) find_bucket(hist, need, t, &s_bucket, &s_need);
-    __syncthreads();
-    prefix |= (uint64_t)s_bucket << shift;
-    need = s_need;
-    __syncthreads();
-  }
+  uint64_t prefix;
+  int need;
+  radix_select_kth([&](int j) { return order_key(cs[j]); }, n, k, hist, &prefix, &need);
 
   // ordered pass: thread t owns chunks [j0, j1) in index order
   const int per = (n + 1023) / 1024;
