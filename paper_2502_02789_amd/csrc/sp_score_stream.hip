@@ -615,6 +615,7 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   dev.lgS = pl.S == 1 ? 0 : pl.S == 2 ? 1 : pl.S == 4 ? 2 : 3;
   dev.lgSPL = pl.slabs_per_layer == 1 ? 0 : pl.slabs_per_layer == 2 ? 1 : pl.slabs_per_layer == 4 ? 2 : 3;
   dev.slabs_per_layer = pl.slabs_per_layer; dev.n_slabs = pl.n_slabs; dev.KPW = pl.KPW; dev.nwg = pl.nwg;
+  dev.layer_step = 1;
   dev.lgKPW = 0;
   while ((1 << dev.lgKPW) < pl.KPW) ++dev.lgKPW;
   dev.own_step = pl.KPW; dev.tile_step = 32;  // every workgroup one run of KPW keys (and all KV heads of them)

@@ -1,6 +1,7 @@
 // Single-pass scorer for one prompt of up to 32K keys: teams of workgroups, one team per group
-// of KV heads.  SP_LAYER_MAX only (Sec. 3.2.2 of arXiv 2502.02789 as printed: maximum over heads
-// and layers, mean over queries).
+// of KV heads (SP_LAYER_MAX, Sec. 3.2.2 of arXiv 2502.02789 as printed: maximum over heads and
+// layers, mean over queries) or per group of layers (SP_LAYER_MEAN: maximum over heads, mean over
+// layers and queries).
 //
 // Same arithmetic and the same per-wave streaming as sp_score_stream.hip (see sp_stream_core.h):
 // every K-cache byte is read from HBM once, the raw logits of the last NSETS slabs wait in
@@ -9,9 +10,12 @@
 // workgroups and travel in two hops.  Here the grid is cut into TC teams; team t owns the KV heads
 // [t * H_kv/TC, (t+1) * H_kv/TC) and walks over (layer, own KV head) slabs; inside a team the
 // prompt's 32-key tiles are dealt out to the workgroups in turn (KPW keys each) and all eight
-// waves of a workgroup work on the SAME KV head, TPW tiles each.  A softmax row therefore has only P = 256 / TC partners (64 for a 32K prompt), and
-// because the maximum over heads and layers commutes with everything, teams never talk to each
-// other until the very end:
+// waves of a workgroup work on the SAME KV head, TPW tiles each.  A softmax row therefore has only
+// P = 256 / TC partners (64 for a 32K prompt), and because the maximum over heads and layers
+// commutes with everything, teams never talk to each other until the very end.  (With the mean
+// over layers team t owns the layers t, t + TC, ... and all their KV heads instead: a layer's
+// maximum over heads is then complete inside a workgroup, which adds the layer's maxima to a
+// running sum at each end of a layer, and the teams' sums add up at the very end.)
 //
 //   * per slab a workgroup publishes ONE 128-byte line: the base-2 log-sum-exp of its keys for
 //     the slab's 32 rows, written by the wave that completes the slab (the waves' own values are
@@ -52,6 +56,7 @@ constexpr int kTeamDepBytes = 8 * 32 * 4;                  // one slab's deposit
 
 struct TeamDev : StreamShape {
   int TC, lgTC;       // teams; team = workgroup % TC, index in team = workgroup / TC
+  int by_layers;      // 0: a team owns KV heads (SP_LAYER_MAX); 1: it owns every TC-th layer (SP_LAYER_MEAN)
   int P;              // workgroups per team (a multiple of 32, at most kTeamMaxPartners)
   int M_pad;          // P * KPW
   uint32_t* partial;  // two copies of [team][slab][partner][32]: base-2 log-sum-exp of the partner's
@@ -98,7 +103,8 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
 
   __device__ __forceinline__ Teamer(const TeamDev& p_, unsigned char* smem)
       : Core(p_, (uint32_t)reinterpret_cast<uintptr_t>(smem), reinterpret_cast<float*>(smem + kFixedBytes),
-             (int)(blockIdx.x >> p_.lgTC), (int)(blockIdx.x & (p_.TC - 1)) * p_.slabs_per_layer),
+             (int)(blockIdx.x >> p_.lgTC), p_.by_layers ? 0 : (int)(blockIdx.x & (p_.TC - 1)) * p_.slabs_per_layer,
+             p_.by_layers ? (int)(blockIdx.x & (p_.TC - 1)) : 0),
         p(p_) {
     team = blockIdx.x & (p.TC - 1);
     pidx = blockIdx.x >> p.lgTC;
@@ -318,7 +324,7 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
   }
 };
 
-template <int D, int TPW, bool PAGED>
+template <int D, int TPW, bool PAGED, bool MEAN>
 __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
   extern __shared__ __align__(1024) unsigned char smem[];
   using Tm = Teamer<D, TPW, PAGED>;
@@ -326,6 +332,36 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
   Tm tm(p, smem);
   const int cells = p.N * p.KPW;  // (query, key) cells of this workgroup
   auto cell_at = [&](int c) __attribute__((always_inline)) { return tm.smax + c + kSmaxPad * (c >> p.lgKPW); };  // skips the row padding
+  // SP_LAYER_MEAN: the team owns whole layers, so a layer's maximum over heads is complete inside
+  // the workgroup; the sum over the team's layers of these maxima (as probabilities) is kept here,
+  // cell = threadIdx + 512 * j.  Slab `done` was just finished by this wave: if it closes a layer,
+  // the layer's maxima join the sums and the cells start over; after the last slab the sums go
+  // back into the cells.  (The cells of a wave's keys are touched by no other wave, so this could
+  // be done wave by wave without the barriers; measured, that is 8 us slower per call on the
+  // 32K-token shape, 416 against 408 us.)
+  float tot[MEAN ? 8 : 1];
+#pragma unroll
+  for (int j = 0; j < (MEAN ? 8 : 1); ++j) tot[j] = 0.f;
+  auto close_layer = [&](int done) __attribute__((always_inline)) {
+    if (MEAN && ((done + 1) & (p.slabs_per_layer - 1)) == 0) {
+      const bool last = done + 1 == p.n_slabs;
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
+      __syncthreads();
+      int t = threadIdx.x;
+      asm volatile("" : "+v"(t));  // the cells' addresses are formed here, once per layer, not kept in registers all along
+#pragma unroll
+      for (int j = 0; j < (MEAN ? 8 : 1); ++j) {
+        const int cell = t + kThreads * j;
+        if (cell < cells) {
+          const uint32_t addr = Tm::lds_addr_of(cell_at(cell));
+          tot[j] += fast_exp2(__uint_as_float(lds_peek(addr)));
+          lds_poke32(addr, last ? __float_as_uint(tot[j]) : 0xff800000u);  // the sum at the end, else -inf
+        }
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
+  };
   for (int i = threadIdx.x; i < cells; i += kThreads) *cell_at(i) = -INFINITY;
   if (threadIdx.x < 16)  // arrival counters, lock and flag: 0; "last slab done / published": none
     *reinterpret_cast<uint32_t*>(smem + Tm::RING_BYTES + NSETS * kTeamDepBytes + threadIdx.x * 4) =
@@ -348,8 +384,10 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
     tm.wait_tile(SLOT0);
     tm.read_queries(SLOT0);
     tm.template issue_stream<2>(slab, SLOT0);
-    if (slab >= NSETS)  // set SET still holds slab - NSETS
+    if (slab >= NSETS) {  // set SET still holds slab - NSETS
       tm.template finish_set<SET>(tm.take_lse(slab - NSETS));
+      close_layer(slab - NSETS);
+    }
     tm.run_m = -INFINITY;
     tm.run_s = 0.f;
 #pragma unroll
@@ -403,6 +441,7 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
       case 6: tm.template finish_set<6 % NSETS>(lse); break;
       default: tm.template finish_set<7 % NSETS>(lse); break;
     }
+    close_layer(s);
   }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS atomics have been performed
   if (tm.expired && tm.lane == 0) {  // a wait of this wave gave up
@@ -467,9 +506,13 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
       const int key = threadIdx.x + j * kThreads;
       if (key < p.KPW && tm.key_of_local(key) < p.M) {
         for (int q = 0; q < gq; ++q) {
-          float m = -INFINITY;
-          for (int t = 0; t < p.TC; ++t) m = fmaxf(m, __uint_as_float(lds_peek(ring + ((t * gq + q) * p.KPW + key) * 4)));
-          sum[j] += fast_exp2(m);
+          if (MEAN) {  // the teams' sums over their layers add up to the sum over all layers
+            for (int t = 0; t < p.TC; ++t) sum[j] += __uint_as_float(lds_peek(ring + ((t * gq + q) * p.KPW + key) * 4));
+          } else {
+            float m = -INFINITY;
+            for (int t = 0; t < p.TC; ++t) m = fmaxf(m, __uint_as_float(lds_peek(ring + ((t * gq + q) * p.KPW + key) * 4)));
+            sum[j] += fast_exp2(m);
+          }
         }
       }
     }
@@ -478,7 +521,7 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
   for (int j = 0; j < 2; ++j) {
     const int key = threadIdx.x + j * kThreads;
     if (key < p.KPW && tm.key_of_local(key) < p.M)
-      p.scores[tm.key_of_local(key)] = void_result ? __uint_as_float(0x7fc00000u) : sum[j] / (float)nv;
+      p.scores[tm.key_of_local(key)] = void_result ? __uint_as_float(0x7fc00000u) : sum[j] / (MEAN ? (float)nv * (float)p.L : (float)nv);
   }
 }
 
@@ -522,7 +565,8 @@ static TeamPlan make_team_plan(const sp_score_args* a, int cus) {
   TeamPlan pl{};
   pl.ok = false;
   const int G = a->H / a->H_kv;
-  if (a->B != 1 || a->T < 1 || a->layer_reduce != SP_LAYER_MAX) return pl;
+  if (a->B != 1 || a->T < 1) return pl;
+  const bool by_layers = a->layer_reduce == SP_LAYER_MEAN;  // teams own layers instead of KV heads
   // Where both single-pass kernels fit, this one is taken where it was measured to be the faster
   // (16 layers, 8 look-ahead rows; team / all-workgroup kernel, us): head dim 128: 8K keys 90 / 83,
   // 12K 109 / 113, 16K 126 / 135, 32K 218 / 230; head dim 64: 8K 75 / 64, 16K 86 / 84, 32K 163 / 158.
@@ -534,9 +578,9 @@ static TeamPlan make_team_plan(const sp_score_args* a, int cus) {
   // the most teams (fewest partners per softmax row) and the fewest key tiles per wave and slab
   // that still cover the prompt
   for (int tc = 8; tc >= 4; tc >>= 1) {
-    if (a->H_kv % tc != 0) continue;
-    const int kpt = a->H_kv / tc;
-    if (kpt & (kpt - 1)) continue;  // slabs per layer: a power of two
+    if (by_layers ? a->L % tc != 0 : a->H_kv % tc != 0) continue;
+    const int kpt = by_layers ? a->H_kv : a->H_kv / tc;  // slabs per layer of a team
+    if (kpt & (kpt - 1)) continue;  // a power of two
     const int partners = std::min(kTeamMaxPartners, cus / tc) / 32 * 32;  // the sampler reads lines in batches of 32
     if (partners < 32) continue;
     for (int tpw = 1; tpw <= 2; ++tpw) {
@@ -547,7 +591,7 @@ static TeamPlan make_team_plan(const sp_score_args* a, int cus) {
       if (smem > 160 * 1024) continue;
       pl.ok = true;
       pl.TC = tc; pl.P = partners; pl.TPW = tpw; pl.KPW = kpw; pl.kpt = kpt;
-      pl.n_slabs = a->L * kpt;
+      pl.n_slabs = (by_layers ? a->L / tc : a->L) * kpt;
       pl.M_pad = partners * kpw;
       pl.partial_bytes = align_up((size_t)tc * pl.n_slabs * partners * 128, 256);
       pl.part_bytes = align_up((size_t)tc * a->N * pl.M_pad * sizeof(float), 256);
@@ -572,9 +616,20 @@ size_t team_status_offset(const sp_score_args* a) {
   return pl.ok ? 2 * pl.partial_bytes + pl.part_bytes : 0;
 }
 
-template <int D, int TPW, bool PAGED>
+// Every variant the dispatch below names, instantiated explicitly: left to implicit instantiation, the
+// host side of half of them (the launch stubs) was not emitted.
+template __global__ void team_score_kernel<128, 1, false, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 1, false, true>(const TeamDev);
+template __global__ void team_score_kernel<128, 1, true, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 1, true, true>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, false, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, false, true>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, true, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, true, true>(const TeamDev);
+
+template <int D, int TPW, bool PAGED, bool MEAN>
 static sp_status launch_team(const TeamDev& dev, const TeamPlan& pl, hipStream_t stream) {
-  auto kernel = team_score_kernel<D, TPW, PAGED>;
+  auto kernel = team_score_kernel<D, TPW, PAGED, MEAN>;
   // once per kernel and device, under a lock: allow the large dynamic LDS size and make sure the
   // whole grid can be resident at once
   static std::mutex mu;
@@ -608,6 +663,8 @@ sp_status team_score(const sp_score_args* a, hipStream_t stream) {
   dev.M = (int)a->T; dev.L = a->L; dev.N = a->N; dev.H = a->H; dev.G = a->H / a->H_kv;
   dev.lgG = dev.G == 1 ? 0 : dev.G == 2 ? 1 : dev.G == 4 ? 2 : 3;
   dev.S = 1; dev.lgS = 0;
+  dev.by_layers = a->layer_reduce == SP_LAYER_MEAN ? 1 : 0;
+  dev.layer_step = dev.by_layers ? pl.TC : 1;
   dev.slabs_per_layer = pl.kpt;
   dev.lgSPL = 0;
   while ((1 << dev.lgSPL) < pl.kpt) ++dev.lgSPL;
@@ -655,12 +712,14 @@ sp_status team_score(const sp_score_args* a, hipStream_t stream) {
     if (hipGetLastError() != hipSuccess) return SP_ELAUNCH;
   }
   sp_status st;
-  if (a->d_block_table) {
-    if (a->d == 128) st = pl.TPW == 1 ? launch_team<128, 1, true>(dev, pl, stream) : launch_team<128, 2, true>(dev, pl, stream);
-    else st = pl.TPW == 1 ? launch_team<64, 1, true>(dev, pl, stream) : launch_team<64, 2, true>(dev, pl, stream);
+  // (head dim 128 only: make_team_plan takes nothing else)
+  const bool paged = a->d_block_table != nullptr, mean = dev.by_layers != 0;
+  if (pl.TPW == 1) {
+    st = paged ? (mean ? launch_team<128, 1, true, true>(dev, pl, stream) : launch_team<128, 1, true, false>(dev, pl, stream))
+               : (mean ? launch_team<128, 1, false, true>(dev, pl, stream) : launch_team<128, 1, false, false>(dev, pl, stream));
   } else {
-    if (a->d == 128) st = pl.TPW == 1 ? launch_team<128, 1, false>(dev, pl, stream) : launch_team<128, 2, false>(dev, pl, stream);
-    else st = pl.TPW == 1 ? launch_team<64, 1, false>(dev, pl, stream) : launch_team<64, 2, false>(dev, pl, stream);
+    st = paged ? (mean ? launch_team<128, 2, true, true>(dev, pl, stream) : launch_team<128, 2, true, false>(dev, pl, stream))
+               : (mean ? launch_team<128, 2, false, true>(dev, pl, stream) : launch_team<128, 2, false, false>(dev, pl, stream));
   }
   return st;
 }

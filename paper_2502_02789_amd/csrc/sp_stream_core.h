@@ -34,6 +34,7 @@ struct StreamShape {
   int M, L, N, H, G, lgG;
   int S, lgS;                    // KV heads a workgroup's waves work on side by side in one slab
   int slabs_per_layer, lgSPL;    // slabs per layer (of this workgroup's sequence of slabs)
+  int layer_step;                // the workgroup's layers are layer_base, layer_base + layer_step, ...
   int n_slabs;
   int KPW, lgKPW;                // keys owned by a workgroup
   int own_step, tile_step;       // key tile x of owner o starts at key o * own_step + x * tile_step: (KPW, 32) gives
@@ -87,6 +88,7 @@ struct StreamCore {
   int wave, lane, half, col;
   int owner;             // which share of the prompt's key tiles this workgroup owns (see own_step, tile_step)
   int kvh_base;          // first KV head of this workgroup's sequence of slabs
+  int layer_base;        // first layer of it
   int kvh_local, kbg;    // this wave's KV head inside a slab, and its group of key tiles
   int budget;            // polls left; a wait that finds it used up gives up and sets `expired`
   bool expired;
@@ -104,8 +106,9 @@ struct StreamCore {
   // (D=64).  With it the 16 lanes of an operand read hit 16 distinct bank groups, and a
   // wave-wide direct load still fills 1 KiB of consecutive LDS.
   // ring_base: LDS byte address of the workgroup's RING_BYTES of tile ring.
-  __device__ __forceinline__ StreamCore(const StreamShape& p_, uint32_t ring_base, float* smax_, int owner_, int kvh_base_)
-      : p(p_), smax(smax_), owner(owner_), kvh_base(kvh_base_) {
+  __device__ __forceinline__ StreamCore(const StreamShape& p_, uint32_t ring_base, float* smax_, int owner_, int kvh_base_,
+                                        int layer_base_ = 0)
+      : p(p_), smax(smax_), owner(owner_), kvh_base(kvh_base_), layer_base(layer_base_) {
     wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     lane = threadIdx.x & 63;
     half = lane >> 5;
@@ -151,7 +154,7 @@ struct StreamCore {
   // prompt key of the workgroup's local key number `local` (tile local / 32, position local % 32)
   __device__ __forceinline__ int key_of_local(int local) const { return tile_key(local >> 5) + (local & 31); }
 
-  __device__ __forceinline__ int layer_of(int slab) const { return slab >> p.lgSPL; }
+  __device__ __forceinline__ int layer_of(int slab) const { return layer_base + (slab >> p.lgSPL) * p.layer_step; }
   __device__ __forceinline__ int kvh_of(int slab) const {
     return kvh_base + ((slab & (p.slabs_per_layer - 1)) << p.lgS) + kvh_local;
   }

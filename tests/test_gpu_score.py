@@ -318,6 +318,35 @@ def test_team_kernel_shapes(shape):
     assert np.array_equal(got1, got2) and np.array_equal(lse1, lse2)
 
 
+@pytest.mark.parametrize("shape", [
+    dict(tokens=9001, L=8, H=32, H_kv=8, N=8, n_valid=5),   # eight teams of one layer each, ragged tail, invalid rows
+    dict(tokens=20011, L=4, H=16, H_kv=8, N=3),             # four teams, two heads per KV head
+    dict(tokens=10007, L=12, H=16, H_kv=4, N=8),            # four KV heads, three layers per team
+    dict(tokens=9500, L=4, H=16, H_kv=16, N=2, paged=True), # sixteen KV heads, behind a block table
+])
+def test_team_kernel_mean_over_layers(shape):
+    """SP_LAYER_MEAN on the team kernel: a team owns every TC-th layer (the maximum over a layer's
+    heads is then complete inside a workgroup, and the teams' sums over their layers add up),
+    against the oracle; twice on one workspace, bitwise equal."""
+    shape = dict(shape)
+    tokens, n_valid, paged = shape.pop("tokens"), shape.pop("n_valid", None), shape.pop("paged", False)
+    w = synth.scaled(synth.workload(3), seqlens=(tokens,), **shape)
+    inp = synth.make_qk(w)
+    scale = 1.0 / math.sqrt(w.d)
+    nv = None if n_valid is None else np.array([n_valid], dtype=np.int32)
+    want, want_lse = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, orc.LAYER_MEAN, nv)
+    runs = []
+    for _ in range(2):
+        if paged:
+            pools, table = hp.paged_copy(inp["k"], inp["cu_seqlens"], 16, seed=3)
+            runs.append(hp.gpu_score_paged(inp["q"], pools, table, inp["cu_seqlens"], w.H_kv, scale, orc.LAYER_MEAN, n_valid=nv))
+        else:
+            runs.append(hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, scale, orc.LAYER_MEAN, n_valid=nv))
+    hp.assert_scores_close(runs[0][0], want, f"team kernel, mean over layers {shape}")
+    np.testing.assert_allclose(runs[0][1], want_lse, rtol=0, atol=2e-4)
+    assert np.array_equal(runs[0][0], runs[1][0]) and np.array_equal(runs[0][1], runs[1][1])
+
+
 def _raw_inputs(seed, seqlens, L, H, H_kv, d, N):
     """Un-rotated bf16 Q [L,B,N,H,d] and per-layer K [T,H_kv,d], plus query positions [B,N]."""
     rng = np.random.default_rng(seed)
