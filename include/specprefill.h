@@ -143,10 +143,19 @@ typedef struct {
   int32_t blocks_per_seq;    /* row length of the table, >= 1                                 */
   int64_t k_page_stride;     /* elements, multiple of 8                                       */
   uint32_t flags;            /* SP_SCORE_* bits, 0 = none                                     */
+  int32_t max_seqlen;        /* 0: nothing stated.  > 0: the caller's promise that no sequence has more
+                                prompt tokens than this (the lengths themselves live on the device, where
+                                the host side of sp_score cannot see them).  With it sp_score can take, for
+                                batches of prompts of up to 8192 keys (4096 with 5..8 query rows per KV
+                                head) whose KV heads carry at most eight query rows, a kernel that reads
+                                the K cache once and keeps all logits of a sequence on chip.  A sequence
+                                longer than promised is not scored: all of its scores are NaN (which
+                                sp_pool_select reports in band), never silently wrong.                  */
 } sp_score_args;
 
 /* Bytes of workspace sp_score needs for these shapes (pointers are not read).
- * Returns 0 if the shape fields are invalid.  The size grows with T: per-tile row statistics
+ * Returns 0 if the shape fields are invalid (flags and max_seqlen are shape fields here: they
+ * decide which kernels run).  The size grows with T: per-tile row statistics
  * (L*N*H*8 bytes per 64 tokens) always, plus, for batches whose KV heads have at most eight
  * query rows (H/H_kv * N <= 8), 16 or 32 bytes per token, layer and KV head of logits kept
  * between the two passes (0.7 GB for 167K tokens of a 32-layer, 8-KV-head model). */

@@ -42,7 +42,7 @@ class ScoreArgs(C.Structure):
         ("rope_theta", C.c_float), ("d_q_pos", C.c_void_p), ("d_scores", C.c_void_p), ("d_lse", C.c_void_p),
         ("d_workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
         ("d_block_table", C.c_void_p), ("page_size", C.c_int32), ("blocks_per_seq", C.c_int32),
-        ("k_page_stride", C.c_int64), ("flags", C.c_uint32),
+        ("k_page_stride", C.c_int64), ("flags", C.c_uint32), ("max_seqlen", C.c_int32),
     ]
 
 
@@ -136,7 +136,7 @@ def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, sca
                     layer_reduce: int = SP_LAYER_MAX, n_valid=None, lse=None, workspace=None,
                     k_token_stride: Optional[int] = None, k_head_stride: Optional[int] = None,
                     T: Optional[int] = None, rope_theta: float = 0.0, q_pos=None,
-                    block_table=None, page_size: int = 0, flags: int = 0) -> ScoreArgs:
+                    block_table=None, page_size: int = 0, flags: int = 0, max_seqlen: int = 0) -> ScoreArgs:
     """q: bf16 [L,B,N,H,d]; k_layers: L bf16 tensors [T,H_kv,d] (any token/head strides), or, with
     block_table (int32 [B, blocks_per_seq]), L page pools [pages, page_size, H_kv, d] (then T must be given)."""
     L, B, N, H, d = q.shape
@@ -171,6 +171,7 @@ def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, sca
     a.d_workspace = _ptr(workspace)
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     a.flags = int(flags)
+    a.max_seqlen = int(max_seqlen)
     return a
 
 

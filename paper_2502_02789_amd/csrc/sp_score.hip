@@ -382,7 +382,7 @@ static sp_status check_score_args(const sp_score_args* a) {
   if (a->rope_theta > 0.f && a->d_q_pos == nullptr) return SP_ENULL;
   if (!sp::finite_f32(a->scale) || a->scale <= 0.f) return SP_EINVAL;
   if (a->flags & ~(uint32_t)(SP_SCORE_EXCLUSIVE_DEVICE | SP_SCORE_WORKSPACE_KEPT)) return SP_EINVAL;
-  if (a->k_token_stride < 0 || a->k_head_stride < 0) return SP_EINVAL;
+  if (a->k_token_stride < 0 || a->k_head_stride < 0 || a->max_seqlen < 0) return SP_EINVAL;
   if (a->d_block_table) {
     if (a->page_size < 8 || (a->page_size & (a->page_size - 1)) != 0 || a->blocks_per_seq < 1) return SP_EINVAL;
     if (a->k_page_stride < 0) return SP_EINVAL;

@@ -12,7 +12,7 @@ TIE_RTOL = 1e-6            # stage-isolated selection: chunks this close to the 
 
 
 def gpu_score(q_bits, k_bits_layers, cu, H_kv, scale, mode, n_valid=None, general=False, want_lse=True,
-              head_major=False, rope_theta=0.0, q_pos=None, exclusive_device=True):
+              head_major=False, rope_theta=0.0, q_pos=None, exclusive_device=True, max_seqlen=0):
     import torch
     from paper_2502_02789_amd import binding as sp_binding, device as dev
     q = dev.bf16_from_bits(q_bits)
@@ -24,7 +24,7 @@ def gpu_score(q_bits, k_bits_layers, cu, H_kv, scale, mode, n_valid=None, genera
     nv_d = None if n_valid is None else torch.from_numpy(np.asarray(n_valid, dtype=np.int32)).cuda()
     qp_d = None if q_pos is None else torch.from_numpy(np.ascontiguousarray(q_pos, dtype=np.int32)).cuda()
     s = dev.Scorer(q, ks, cu_d, H_kv=H_kv, scale=scale, layer_reduce=mode, n_valid=nv_d, want_lse=want_lse,
-                   rope_theta=rope_theta, q_pos=qp_d, exclusive_device=exclusive_device)
+                   rope_theta=rope_theta, q_pos=qp_d, exclusive_device=exclusive_device, max_seqlen=max_seqlen)
     s.scores.fill_(float("nan"))
     s.run(general=general)
     sp_binding.sp_score_check(s.args)          # synchronises; raises if a device-side wait expired
@@ -58,7 +58,7 @@ def paged_copy(k_bits_layers, cu, page_size, seed):
     return pools, table
 
 
-def gpu_score_paged(q_bits, pools, table, cu, H_kv, scale, mode, general=False, n_valid=None):
+def gpu_score_paged(q_bits, pools, table, cu, H_kv, scale, mode, general=False, n_valid=None, max_seqlen=0):
     import torch
     from paper_2502_02789_amd import binding as sp_binding, device as dev
     q = dev.bf16_from_bits(q_bits)
@@ -67,7 +67,7 @@ def gpu_score_paged(q_bits, pools, table, cu, H_kv, scale, mode, general=False, 
     tab_d = torch.from_numpy(np.ascontiguousarray(table, dtype=np.int32)).cuda()
     nv_d = None if n_valid is None else torch.from_numpy(np.asarray(n_valid, dtype=np.int32)).cuda()
     s = dev.Scorer(q, ks, cu_d, H_kv=H_kv, scale=scale, layer_reduce=mode, want_lse=True, n_valid=nv_d, block_table=tab_d,
-                   page_size=pools[0].shape[1], total_tokens=int(cu[-1]))
+                   page_size=pools[0].shape[1], total_tokens=int(cu[-1]), max_seqlen=max_seqlen)
     s.scores.fill_(float("nan"))
     s.run(general=general)
     sp_binding.sp_score_check(s.args)
