@@ -5,25 +5,29 @@
 // prompt keys (Sec. 3.2 equation of arXiv 2502.02789), max over heads, max/mean over layers,
 // mean over queries (Sec. 3.2.2).  The K cache is read ONCE and no logit ever leaves the chip:
 //
-//   * A workgroup owns one whole sequence for a group of layers and walks over the group's
-//     (layer, KV head) slabs.  Inside a slab its eight waves take the sequence's 64-key tiles in
-//     turn (wave w: tiles w, w + 8, ...), stream them through the per-wave two-slot LDS ring of
-//     the tiled kernels and multiply them with the KV head's query rows on the matrix cores --
-//     with the QUERY rows as the rows of the result, so that a lane ends up with all R <= 8 logits
-//     of one key (one v_permlane32_swap per register joins the two 32-key halves of a tile).
+//   * The work is cut into units (one whole sequence, one group of layers), numbered with the
+//     longest sequences first, and dealt out to one workgroup per compute unit in rounds whose
+//     direction alternates: every workgroup gets nearly the same number of keys without any shared
+//     counter, and nobody ever waits for another workgroup.
+//   * A workgroup walks over the (layer, KV head) slabs of its unit.  Inside a slab its eight waves
+//     take the sequence's 64-key tiles in turn (wave w: tiles w, w + 8, ...), stream them through
+//     the per-wave two-slot LDS ring of the tiled kernels and multiply them with the KV head's
+//     query rows on the matrix cores -- with the QUERY rows as the rows of the result, so that a
+//     lane ends up with all R <= 8 logits of one key (one v_permlane32_swap per register joins
+//     the two 32-key halves of a tile).
 //   * Those R logits per key stay in registers for the whole slab (R registers per tile), each
 //     lane keeps a running (max, sum exp2) per row, and at the end of the slab the lanes' and the
 //     eight waves' statistics are merged (shuffles, one small LDS table, ONE workgroup barrier):
 //     every wave then knows the rows' log-sum-exps and turns its held logits into
 //     log2-probabilities, folds the heads of a group and keeps the running maximum over KV heads
 //     and layers (or the sum over layers of the per-layer maxima) per key in registers.
-//   * The stream of tiles never stops at a slab's end: the loads of the next slab's first tiles
-//     are in flight while the statistics are merged, and the barrier is a bare s_barrier (no
-//     vector-memory wait in front of it).
-//   * Each (sequence, layer group) writes its [N][M] partial result; the tiled kernels' finish
-//     kernel merges the layer groups and averages over the valid queries.
+//   * The stream of tiles never stops, neither at a slab's end nor between units: the loads run two
+//     tiles ahead of the arithmetic straight into the next slab or unit, and the barrier is a bare
+//     s_barrier (no vector-memory wait in front of it).
+//   * Each unit writes its [N][M] partial result; the tiled kernels' finish kernel merges the
+//     layer groups and averages over the valid queries.
 //
-// A sequence must fit the registers: 64 * 8 * kSeqMaxTiles<R> keys.  The host cannot see the
+// A sequence must fit the registers: 64 * 8 * SeqLimits<R>::kMaxTiles keys.  The host cannot see the
 // sequence lengths (they live on the device), so this path is taken only on the caller's promise
 // sp_score_args.max_seqlen; a sequence that breaks the promise gets NaN scores (finish kernel).
 #include <mutex>
@@ -44,10 +48,36 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-template <int D>
-struct SeqAhead {  // the next item of a wave's stream: ph < 0 the slab's query tile, else 32-key half-tile ph of the wave
-  int l, g, ph;
+// One unit of work: sequence b for the layers [l0, l1) of layer group grp.  Units are numbered with the
+// longest sequences first (all layer groups of a sequence next to each other).
+struct SeqUnit {
+  int k;  // position in this workgroup's list of units
+  int b, grp, seq0, M, nt, l0, l1;
 };
+
+// Units are dealt out to the gridDim.x workgroups in rounds, the direction changing with every round
+// (workgroup j: units j, 2W-1-j, 2W+j, ...): with the sizes in descending order every workgroup gets
+// nearly the same number of keys, and no counter has to be shared.
+template <int MAXT>
+__device__ __forceinline__ bool seq_next_unit(const TiledDev& p, int wave, int k, SeqUnit* u) {
+  const int W = gridDim.x, n_units = p.B * p.n_groups;
+  for (;; ++k) {
+    const int idx = k * W + ((k & 1) ? W - 1 - (int)blockIdx.x : (int)blockIdx.x);
+    if (idx >= n_units) return false;
+    const int grp = idx % p.n_groups;
+    const int b = p.seq_order[idx / p.n_groups];
+    const int seq0 = p.cu[b];
+    const int M = p.cu[b + 1] - seq0;
+    const int n_tiles = (M + kWaveKeys - 1) / kWaveKeys;
+    const int l0 = grp * p.layers_per_group;
+    const int l1 = min(p.L, l0 + p.layers_per_group);
+    // (no keys, or more than the registers hold: nothing to do here, see seq_order_kernel and the finish kernel)
+    if (M <= 0 || n_tiles > MAXT * kTiledWaves || l0 >= l1) continue;
+    u->k = k; u->b = b; u->grp = grp; u->seq0 = seq0; u->M = M; u->l0 = l0; u->l1 = l1;
+    u->nt = __builtin_amdgcn_readfirstlane((n_tiles - wave + kTiledWaves - 1) / kTiledWaves);  // this wave's tiles
+    return true;
+  }
+}
 
 template <int D, int R, int LG, bool MEAN>
 __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev p) {
@@ -56,29 +86,53 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
   constexpr int MAXT = SeqLimits<R>::kMaxTiles;
   constexpr int GP = 1 << LG;   // heads of a KV group, padded to a power of two
   constexpr int NQ = R >> LG;   // queries whose rows fit the R held rows
-  const int b = blockIdx.x;
-  const int seq0 = p.cu[b];
-  const int M = p.cu[b + 1] - seq0;
-  const int n_tiles = (M + kWaveKeys - 1) / kWaveKeys;
-  const int l0 = blockIdx.y * p.layers_per_group;
-  const int l1 = min(p.L, l0 + p.layers_per_group);
-  if (l0 >= l1) return;
-  if (M <= 0 || n_tiles > MAXT * kTiledWaves) {
-    // no keys: the rows' log-sum-exps are 0 by convention; too many: the sequence is not scored
-    // (NaN here, and the finish kernel writes NaN scores for it)
-    if (p.lse_out)
-      for (int i = threadIdx.x; i < (l1 - l0) * p.N * p.H; i += kTiledThreads)
-        p.lse_out[(((int64_t)(l0 + i / (p.N * p.H)) * p.B + b) * p.N) * p.H + i % (p.N * p.H)] =
-            M <= 0 ? 0.f : __uint_as_float(0x7FC00000u);
-    return;
-  }
-  TW w(p, smem, typename TW::WholeSequence{}, b);
-  const int nt = __builtin_amdgcn_readfirstlane((n_tiles - w.wave + kTiledWaves - 1) / kTiledWaves);  // this wave's tiles
-  const int n_slabs = (l1 - l0) * p.H_kv;
+  TW w(p, smem, typename TW::WholeSequence{}, 0);
+  SeqUnit cur;
+  if (!seq_next_unit<MAXT>(p, w.wave, 0, &cur)) return;
   const uint32_t xchg = (uint32_t)reinterpret_cast<uintptr_t>(smem) + kTiledWaves * 2 * TW::TILE_B;  // [2][waves][R] (max, sum)
+
+  // The stream of tiles runs two items ahead of the arithmetic and straight on into the workgroup's
+  // next unit: `ah` is the unit, slab and item that is requested next.
+  SeqUnit ahu = cur;
+  bool ah_live = true;  // false: past the last unit (the last slab is requested again, nobody consumes it)
+  int ah_l = cur.l0, ah_g = 0, ah_ph = -1;  // ph < 0: the slab's query tile, else 32-key half-tile ph of this wave
+  auto issue_next = [&](int slot) __attribute__((always_inline)) {
+    w.b = ahu.b;
+    w.seq0 = ahu.seq0;
+    if (ah_ph < 0) {
+      w.template issue_queries<false>(ah_l, ah_g, slot, 0);
+    } else {
+      const int key_first = ((w.wave + (ah_ph >> 1) * kTiledWaves) * 2 + (ah_ph & 1)) * 32;
+      const int rows = min(32, ahu.M - key_first);
+      w.issue_key_rows(ah_l, ah_g, rows > 0 ? key_first : 0, rows, slot);
+    }
+    if (++ah_ph == 2 * ahu.nt) {
+      ah_ph = -1;
+      if (++ah_g == p.H_kv) {
+        ah_g = 0;
+        if (++ah_l == ahu.l1) {
+          if (ah_live && seq_next_unit<MAXT>(p, w.wave, ahu.k + 1, &ahu)) {
+            ah_l = ahu.l0;
+          } else {
+            ah_live = false;
+            ah_l = ahu.l1 - 1;
+            ah_g = p.H_kv - 1;
+          }
+        }
+      }
+    }
+  };
+  issue_next(0);
+  issue_next(1);
+  int pos = 0;    // items consumed so far; item number x sits in ring slot x & 1
+  int slabs = 0;  // slabs finished so far (the exchange table has two halves used in turn)
 
   float held[MAXT][R];
   float smax[MAXT][NQ], tot[MEAN ? MAXT : 1][NQ];
+
+#pragma unroll 1
+  for (;;) {
+  const int nt = cur.nt, M = cur.M, b = cur.b;
 #pragma unroll
   for (int t = 0; t < MAXT; ++t)
 #pragma unroll
@@ -86,25 +140,8 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
       smax[t][n] = -INFINITY;
       if (MEAN) tot[MEAN ? t : 0][n] = 0.f;
     }
-
-  SeqAhead<D> ah{l0, 0, -1};
-  auto issue_next = [&](int slot) __attribute__((always_inline)) {
-    if (ah.ph < 0) {
-      w.template issue_queries<false>(ah.l, ah.g, slot, 0);
-    } else {
-      const int key_first = ((w.wave + (ah.ph >> 1) * kTiledWaves) * 2 + (ah.ph & 1)) * 32;
-      const int rows = min(32, M - key_first);
-      w.issue_key_rows(ah.l, ah.g, rows > 0 ? key_first : 0, rows, slot);
-    }
-    if (++ah.ph == 2 * nt) {
-      ah.ph = -1;
-      if (++ah.g == p.H_kv) { ah.g = 0; ah.l = min(ah.l + 1, l1 - 1); }  // past the end: the last layer again (nobody consumes it)
-    }
-  };
-  issue_next(0);
-  issue_next(1);
-  int pos = 0;  // items consumed so far; item number x sits in ring slot x & 1
-  int l = l0, g = 0;
+  int l = cur.l0, g = 0;
+  const int n_slabs = (cur.l1 - cur.l0) * p.H_kv;
 
 #pragma unroll 1
   for (int s = 0; s < n_slabs; ++s) {
@@ -153,7 +190,8 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
     });
 
     // the rows' statistics over the wave's keys, then over the workgroup's
-    const int par = s & 1;
+    const int par = slabs & 1;
+    ++slabs;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const float mw = wave_max(rm[r]);
@@ -185,7 +223,7 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
       for (int r = 0; r < R; ++r) lse2[r] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(lse), r));
       if (p.lse_out && w.wave == 0) {
         const int n = ln >> LG, j = ln & (GP - 1);
-        if (ln < R && n < p.N && j < p.G)
+        if (ln < R && n < p.N && j < p.G)  // (never empty: lane 0 is always inside)
           p.lse_out[(((int64_t)l * p.B + b) * p.N + n) * p.H + g * p.G + j] = lse * 0.6931471805599453f;
         w.note_issued(1);
       }
@@ -215,8 +253,10 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
     }
     if (++g == p.H_kv) { g = 0; ++l; }
   }
-  wait_vmcnt<0>();  // loads issued past the end land before the wave (and its LDS) goes away
 
+  // the unit's result.  (These stores are left out of the count of vector-memory instructions in
+  // flight -- a store whose lanes are all beyond the sequence may not be issued at all --, which only
+  // makes the next tile waits stricter than they need be.)
   static_for<0, MAXT>([&](auto tc) __attribute__((always_inline)) {
     constexpr int t = decltype(tc)::value;
     if (t < nt) {
@@ -225,10 +265,39 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
 #pragma unroll
         for (int n = 0; n < NQ; ++n)
           if (n < p.N)
-            p.group_scores[((int64_t)blockIdx.y * p.N + n) * p.T + seq0 + key] = MEAN ? tot[MEAN ? t : 0][n] : smax[t][n];
+            p.group_scores[((int64_t)cur.grp * p.N + n) * p.T + cur.seq0 + key] = MEAN ? tot[MEAN ? t : 0][n] : smax[t][n];
       }
     }
   });
+  if (!seq_next_unit<MAXT>(p, w.wave, cur.k + 1, &cur)) break;
+  }
+  wait_vmcnt<0>();  // loads issued past the end land before the wave (and its LDS) goes away
+}
+
+// order[r] = the sequence with the r-th most keys (equal lengths: lower index first); one workgroup,
+// every thread ranks its sequences by counting those ahead of them
+// (and the log-sum-exp rows of the sequences the scoring kernel leaves out: 0 by convention where there are no
+// keys, NaN where there are more than `limit`)
+__global__ __launch_bounds__(1024) void seq_order_kernel(int B, const int32_t* __restrict__ cu, int32_t* __restrict__ order,
+                                                         float* __restrict__ lse_out, int limit, int L, int rows) {
+  constexpr int kChunk = 4096;
+  __shared__ int32_t len[kChunk];
+  for (int b0 = 0; b0 < B; b0 += 1024) {  // (all threads take part in every round: barriers inside)
+    const int b = b0 + threadIdx.x;
+    const int mine = b < B ? cu[b + 1] - cu[b] : 0;
+    int rank = 0;
+    for (int c0 = 0; c0 < B; c0 += kChunk) {
+      const int n = min(kChunk, B - c0);
+      __syncthreads();
+      for (int i = threadIdx.x; i < n; i += 1024) len[i] = cu[c0 + i + 1] - cu[c0 + i];
+      __syncthreads();
+      for (int i = 0; i < n; ++i) rank += (len[i] > mine || (len[i] == mine && c0 + i < b)) ? 1 : 0;
+    }
+    if (b < B) order[rank] = b;
+    if (b < B && lse_out && (mine <= 0 || mine > limit))
+      for (int i = 0; i < L * rows; ++i)
+        lse_out[((int64_t)(i / rows) * B + b) * rows + i % rows] = mine <= 0 ? 0.f : __uint_as_float(0x7FC00000u);
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -264,11 +333,31 @@ bool seq_supported(const sp_score_args* a) {
   return true;
 }
 
-size_t seq_workspace_bytes(const sp_score_args* a) {
-  if (!seq_supported(a)) return 0;
+static size_t seq_scores_bytes(const sp_score_args* a) {
   int lpg, groups;
   seq_grouping(a, &lpg, &groups);
   return align_up(sizeof(float) * (size_t)groups * a->N * (size_t)a->T, 256);
+}
+
+size_t seq_workspace_bytes(const sp_score_args* a) {
+  if (!seq_supported(a)) return 0;
+  return seq_scores_bytes(a) + align_up(sizeof(int32_t) * (size_t)a->B, 256);  // partial results, then the sequence order
+}
+
+static int seq_cu_count() {  // compute units of the current device
+  static std::mutex mu;
+  static int cached[kMaxDevices] = {};
+  std::lock_guard<std::mutex> lock(mu);
+  const int slot = current_device();
+  if (cached[slot] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, slot) != hipSuccess || n < 1) {
+      (void)hipGetLastError();
+      n = 256;
+    }
+    cached[slot] = n;
+  }
+  return cached[slot];
 }
 
 template <int D, int R, int LG, bool MEAN>
@@ -287,7 +376,9 @@ static sp_status launch_seq(const TiledDev& dev, hipStream_t stream) {
       prepared[slot] = true;
     }
   }
-  hipLaunchKernelGGL(kernel, dim3(dev.B, dev.n_groups), dim3(kTiledThreads), smem, stream, dev);
+  // one workgroup per compute unit walks over its share of the (sequence, layer group) units
+  const int wgs = std::min(dev.B * dev.n_groups, seq_cu_count());
+  hipLaunchKernelGGL(kernel, dim3(wgs), dim3(kTiledThreads), smem, stream, dev);
   return launch_status();
 }
 
@@ -299,7 +390,12 @@ static sp_status seq_by_rows(const TiledDev& dev, int R, hipStream_t stream) {
 
 // `dev` as the tiled kernels fill it in, with group_scores, layers_per_group, n_groups and
 // seq_limit set for this path; the caller runs the finish kernel afterwards
-sp_status seq_score(const sp_score_args* a, const TiledDev& dev, hipStream_t stream) {
+sp_status seq_score(const sp_score_args* a, const TiledDev& dev_, hipStream_t stream) {
+  TiledDev dev = dev_;
+  int32_t* order = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(dev.group_scores) + seq_scores_bytes(a));
+  hipLaunchKernelGGL(seq_order_kernel, dim3(1), dim3(1024), 0, stream, a->B, a->d_cu_seqlens, order, a->d_lse,
+                     seq_max_keys(a), a->L, a->N * a->H);
+  dev.seq_order = order;
   const int R = seq_rows(a);
   const bool mean = a->layer_reduce == SP_LAYER_MEAN;
   if (a->d == 64) return mean ? seq_by_rows<64, true>(dev, R, stream) : seq_by_rows<64, false>(dev, R, stream);

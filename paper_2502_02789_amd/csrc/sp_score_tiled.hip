@@ -427,6 +427,7 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
   dev.ws_lse = gen.ws_lse; dev.part = gen.part;
   dev.lse_out = a->d_lse;
   dev.seq_limit = 0;
+  dev.seq_order = nullptr;
   if (seq_supported(a)) {  // one pass over K, a workgroup per (sequence, layer group)
     seq_grouping(a, &dev.layers_per_group, &dev.n_groups);
     dev.group_scores = static_cast<float*>(extra);

@@ -39,6 +39,7 @@ struct TiledDev {
   int keep_units;        // 1 or 2: units of four query rows per KV head
   float* scores;
   float* lse_out;        // optional [L][B][N][H] natural-log row log-sum-exps (written by the single-pass batch kernel itself)
+  const int32_t* seq_order;  // single-pass batch kernel: sequence numbers, longest first
   int seq_limit;         // single-pass batch kernel: sequences longer than this many keys are not scored (NaN), 0 = no limit
   const int32_t* block_table;  // paged cache: [B][blocks_per_seq] page numbers, else null
   int lg_page, blocks_per_seq;
