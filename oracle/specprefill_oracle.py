@@ -21,6 +21,8 @@ Steps and where the paper defines them
   pool_select          Algorithm 1, chunk_select_from_smoothed_attention
   gather               Sec. 3.2.4  position-id restoration (+ token ids, embedding rows)
   keys_from_pages      Sec. 3.3 / Algorithm 1  keys fetched through the engine's slot mapping (block table)
+  fp8_e4m3_bits_to_f64 not in the paper: decoding of a K cache stored as 8-bit floats (OCP FP8, E4M3) with one
+                       scale per layer and KV head; the scores are then the paper's on the decoded keys
   rope_rotate_bits     not in the paper: the rotary position encoding a Llama-family draft
                        applies to Q and K before they are cached (needed only when the
                        library is handed an un-rotated cache)
@@ -50,6 +52,27 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
     """Exact widening of bf16 bit patterns (uint16) to fp64."""
     b = np.ascontiguousarray(bits, dtype=np.uint16)
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def fp8_e4m3_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact decoding of OCP 8-bit floats, format E4M3 (1 sign, 4 exponent, 3 mantissa bits, bias 7):
+    exponent field 0 is subnormal (m/8 * 2^-6), there are no infinities, and the one NaN is
+    S.1111.111; the largest finite value is 1.75 * 2^8 = 448."""
+    b = np.ascontiguousarray(bits, dtype=np.uint8).astype(np.int64)
+    sign = np.where(b >> 7 == 1, -1.0, 1.0)
+    e = (b >> 3) & 15
+    m = (b & 7).astype(np.float64)
+    normal = (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64))
+    sub = (m / 8.0) * 2.0 ** -6
+    out = sign * np.where(e == 0, sub, normal)
+    return np.where((e == 15) & ((b & 7) == 7), np.nan, out)
+
+
+def keys_from_fp8(k_codes: np.ndarray, k_scale_layer: np.ndarray) -> np.ndarray:
+    """One layer of an 8-bit K cache -> fp64 keys: k_codes uint8 [T, H_kv, d], k_scale_layer fp32 [H_kv];
+    key[i, g, :] = scale[g] * decode(code[i, g, :]), the product taken in fp64."""
+    scale = np.asarray(k_scale_layer, dtype=np.float32).astype(np.float64)
+    return fp8_e4m3_bits_to_f64(k_codes) * scale[None, :, None]
 
 
 # ----------------------------------------------------------------------------
@@ -146,8 +169,10 @@ def aggregate(tensor: np.ndarray, layer_reduce: int = LAYER_MAX) -> np.ndarray:
 # ----------------------------------------------------------------------------
 def token_importance(q_bits: np.ndarray, k_bits_layers: Sequence[np.ndarray], cu_seqlens: np.ndarray,
                      scale: float, layer_reduce: int = LAYER_MAX,
-                     n_valid: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
-    """q_bits uint16 [L, B, N, H, d]; k_bits_layers: L arrays uint16 [T, H_kv, d].
+                     n_valid: Optional[np.ndarray] = None,
+                     k_scale: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """q_bits uint16 [L, B, N, H, d]; k_bits_layers: L arrays uint16 [T, H_kv, d] (bf16 bit patterns), or,
+    with k_scale (fp32 [L, H_kv]), L arrays uint8 [T, H_kv, d] of 8-bit float codes (keys_from_fp8).
 
     Returns (scores fp64 [T], lse fp64 [L, B, N, H]).  Only the first n_valid[b]
     queries of sequence b count (EOS validity, Sec. 3.3); their mean is taken.
@@ -160,7 +185,7 @@ def token_importance(q_bits: np.ndarray, k_bits_layers: Sequence[np.ndarray], cu
     q = bf16_bits_to_f64(q_bits)
     acc = [None] * B
     for l in range(L):
-        k = bf16_bits_to_f64(k_bits_layers[l])
+        k = bf16_bits_to_f64(k_bits_layers[l]) if k_scale is None else keys_from_fp8(k_bits_layers[l], k_scale[l])
         for b in range(B):
             lo, hi = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
             if hi == lo:

@@ -227,3 +227,37 @@ def random_scores(seed: int, T: int, ties: bool = False) -> np.ndarray:
     if ties:
         x = (np.floor(g.random(T) * 4.0) / 4.0 + 0.25).astype(np.float32)
     return x
+
+
+# ----------------------------------------------------------------------------
+# 8-bit K cache (input formatting only): OCP FP8 E4M3 codes with one scale per layer and KV head
+# ----------------------------------------------------------------------------
+def _e4m3_positive_values() -> np.ndarray:
+    """The 127 finite non-negative E4M3 values, code 0x00 .. 0x7E, ascending."""
+    code = np.arange(127)
+    e, m = code >> 3, code & 7
+    return np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+
+
+def quantize_k_fp8(k_bits_layers):
+    """bf16 K layers [T, H_kv, d] -> (list of uint8 code arrays, fp32 scales [L, H_kv]).
+
+    What an engine with an 8-bit K cache stores: per layer and KV head one scale = (largest |value|) / 448
+    (1 if the head is all zero), each value divided by it (in fp64) and rounded to the nearest E4M3 value,
+    ties to the even code, saturating at +-448."""
+    vals = _e4m3_positive_values()
+    mids = (vals[1:] + vals[:-1]) / 2.0
+    codes, scales = [], []
+    for k in k_bits_layers:
+        x = bf16_bits_to_f32(k).astype(np.float64)
+        amax = np.abs(x).max(axis=(0, 2))
+        sc = np.where(amax > 0, amax / 448.0, 1.0).astype(np.float32)
+        y = np.abs(x) / sc.astype(np.float64)[None, :, None]
+        idx = np.searchsorted(mids, y, side="left")             # y <= mids[idx]: value idx is the nearest from below/at the tie
+        tie = (idx < len(mids)) & (y == mids[np.minimum(idx, len(mids) - 1)])
+        idx = np.where(tie & (idx % 2 == 1), idx + 1, idx)       # a tie goes to the even code
+        idx = np.minimum(idx, 126)
+        c = idx.astype(np.uint8) | np.where(np.signbit(x), np.uint8(0x80), np.uint8(0)).astype(np.uint8)
+        codes.append(np.ascontiguousarray(c))
+        scales.append(sc)
+    return codes, np.stack(scales).astype(np.float32)

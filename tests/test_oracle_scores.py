@@ -398,3 +398,67 @@ def test_keys_from_pages_identity_table_is_a_reshape():
     cu = np.array([0, 48], dtype=np.int32)
     table = np.arange(6, dtype=np.int32)[None, :]
     assert np.array_equal(orc.keys_from_pages(pool, table, cu), pool.reshape(48, 2, 4))
+
+
+# ----------------------------------------------------------------------------
+# 8-bit K cache: the decoding the oracle applies before the Sec. 3.2 arithmetic
+# ----------------------------------------------------------------------------
+def test_fp8_e4m3_decoding_against_the_format_definition_and_a_library():
+    """Literal values of the OCP E4M3 format (bias 7, subnormals, no infinities, one NaN, max 448),
+    then all 256 codes against torch's own float8_e4m3fn conversion."""
+    literal = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x0F: 1.875 * 2.0 ** -6,
+               0x30: 0.5, 0x38: 1.0, 0x39: 1.125, 0x3C: 1.5, 0x40: 2.0, 0x77: 1.875 * 2.0 ** 7, 0x78: 256.0,
+               0x7E: 448.0, 0x81: -(2.0 ** -9), 0xB8: -1.0, 0xFE: -448.0}
+    codes = np.array(sorted(literal), dtype=np.uint8)
+    got = orc.fp8_e4m3_bits_to_f64(codes)
+    assert got.tolist() == [literal[int(c)] for c in codes]
+    assert np.signbit(orc.fp8_e4m3_bits_to_f64(np.array([0x80], dtype=np.uint8)))[0]
+    assert np.isnan(orc.fp8_e4m3_bits_to_f64(np.array([0x7F, 0xFF], dtype=np.uint8))).all()
+    every = np.arange(256, dtype=np.uint8)
+    mine = orc.fp8_e4m3_bits_to_f64(every)
+    pos = mine[:0x7F]
+    assert (np.diff(pos) > 0).all() and (mine[0x80:0xFF] == -pos).all()     # codes are monotone, sign-symmetric
+    torch = pytest.importorskip("torch")
+    if hasattr(torch, "float8_e4m3fn"):
+        lib = torch.from_numpy(every.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+        ok = ~np.isnan(mine)
+        assert np.array_equal(mine[ok], lib[ok]) and np.isnan(lib[~ok]).all()
+
+
+def test_fp8_keys_with_unit_scale_equal_the_same_keys_in_bf16():
+    """Every E4M3 value is a bf16 value, so with scale 1 the 8-bit cache and the bf16 cache holding the
+    same numbers must give identical scores; a common scale on all heads is the same as scaling the logits."""
+    rng = np.random.default_rng(5)
+    L, B, N, H, H_kv, d, M = 2, 1, 2, 4, 2, 16, 37
+    q = synth.f32_to_bf16_bits(rng.normal(size=(L, B, N, H, d)).astype(np.float32))
+    codes = [rng.integers(0, 0x7F, size=(M, H_kv, d)).astype(np.uint8) | (rng.integers(0, 2, size=(M, H_kv, d)) << 7).astype(np.uint8)
+             for _ in range(L)]
+    codes = [np.where((c & 0x7F) > 0x60, c & 0xBF, c).astype(np.uint8) for c in codes]     # keep magnitudes moderate
+    as_bf16 = [synth.f32_to_bf16_bits(orc.fp8_e4m3_bits_to_f64(c).astype(np.float32)) for c in codes]
+    assert all((orc.bf16_bits_to_f64(b) == orc.fp8_e4m3_bits_to_f64(c)).all() for b, c in zip(as_bf16, codes))
+    cu = np.array([0, M])
+    ones = np.ones((L, H_kv), dtype=np.float32)
+    for mode in (orc.LAYER_MAX, orc.LAYER_MEAN):
+        want, want_lse = orc.token_importance(q, as_bf16, cu, 0.11, mode)
+        got, got_lse = orc.token_importance(q, codes, cu, 0.11, mode, k_scale=ones)
+        assert np.array_equal(got, want) and np.array_equal(got_lse, want_lse)
+        half, half_lse = orc.token_importance(q, codes, cu, 0.22, mode, k_scale=0.5 * ones)
+        np.testing.assert_allclose(half, want, rtol=1e-12)
+    # one scale per layer AND head: changing a single head's scale changes the scores
+    skew = ones.copy()
+    skew[1, 0] = 3.0
+    other, _ = orc.token_importance(q, codes, cu, 0.11, orc.LAYER_MAX, k_scale=skew)
+    assert np.abs(other - want).max() > 1e-6
+    kq = orc.keys_from_fp8(codes[1], skew[1])
+    assert np.array_equal(kq[:, 0], 3.0 * orc.fp8_e4m3_bits_to_f64(codes[1][:, 0])) and \
+        np.array_equal(kq[:, 1], orc.fp8_e4m3_bits_to_f64(codes[1][:, 1]))
+
+
+def test_fp8_quantiser_of_the_input_generator_rounds_to_nearest_even_and_saturates():
+    vals = orc.fp8_e4m3_bits_to_f64(np.arange(0x7F, dtype=np.uint8))
+    # a head whose largest value is 448 has scale 1: exact values keep their codes, midpoints go to the even code
+    x = np.zeros((1, 1, 8), dtype=np.float32)
+    x[0, 0, :] = [448.0, 1.0, (vals[0x38] + vals[0x39]) / 2, (vals[0x39] + vals[0x3A]) / 2, -1.5, 0.0, 2.0 ** -10, 3.0 * 2.0 ** -10]
+    codes, scales = synth.quantize_k_fp8([synth.f32_to_bf16_bits(x)])
+    assert scales.tolist() == [[1.0]]
+    assert codes[0][0, 0].tolist() == [0x7E, 0x38, 0x38, 0x3A, 0xBC, 0x00, 0x00, 0x02]
