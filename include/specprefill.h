@@ -55,6 +55,17 @@ typedef enum {
  * heads AND layers; the alternative keeps the maximum over heads but averages layers. */
 typedef enum { SP_LAYER_MAX = 0, SP_LAYER_MEAN = 1 } sp_layer_reduce;
 
+/* How the K cache stores its elements.  SP_K_FP8_E4M3: one byte per element, OCP 8-bit floating point,
+ * format E4M3 (1 sign, 4 exponent, 3 mantissa bits, bias 7, subnormals, no infinities, S.1111.111 = NaN,
+ * largest finite value 448), and the key the paper's Sec. 3.2 equation sees is
+ *     K_l[i, g, t] = d_k_scale[l * H_kv + g] * decode(byte)
+ * (one fp32 scale per layer and KV head, as an engine with an 8-bit KV cache keeps them).  Every E4M3
+ * value is a bf16 value, so the products with the bf16 queries are formed exactly as for a bf16 cache and
+ * accumulated in fp32; the scale joins the logit scale.  Scores therefore meet the same tolerance against
+ * the definition evaluated on the decoded keys as a bf16 cache does.  NaN codes are a precondition
+ * violation like NaN in a bf16 cache. */
+typedef enum { SP_K_BF16 = 0, SP_K_FP8_E4M3 = 1 } sp_k_dtype;
+
 #define SP_MAX_LAYERS 128
 #define SP_MAX_QUERIES 16
 
@@ -151,6 +162,11 @@ typedef struct {
                                 the K cache once and keeps all logits of a sequence on chip.  A sequence
                                 longer than promised is not scored: all of its scores are NaN (which
                                 sp_pool_select reports in band), never silently wrong.                  */
+  int32_t k_dtype;           /* sp_k_dtype, 0 = bf16.  With SP_K_FP8_E4M3 the layers hold bytes: the strides
+                                (token, head, page) still count ELEMENTS and must then be multiples of 16;
+                                rope_theta must be 0 (SP_EUNSUPPORTED otherwise), and sp_score runs its
+                                two-pass kernels (half the bytes per pass).                              */
+  const float* d_k_scale;    /* fp32 [L, H_kv] scales of an SP_K_FP8_E4M3 cache, or NULL (all 1)          */
 } sp_score_args;
 
 /* Bytes of workspace sp_score needs for these shapes (pointers are not read).
@@ -251,8 +267,8 @@ SP_API sp_status sp_pool_select_static(const sp_pool_select_args* args, void* hi
  * The workgroups of the launch never wait for one another (the last one to finish its share
  * completes the call), so nothing depends on what else runs on the device; they do count their
  * arrivals in one word per device, so two of these calls must not overlap on one GPU.
- * Supported: B == 1, 1 <= T <= 2048, H/H_kv * N <= 16, L * H * N <= 4096, rope_theta == 0, no block
- * table, at most 2048 chunks; anything else returns SP_EUNSUPPORTED and launches nothing (use the
+ * Supported: B == 1, 1 <= T <= 2048, H/H_kv * N <= 16, L * H * N <= 4096, rope_theta == 0, a bf16 cache, no
+ * block table, at most 2048 chunks; anything else returns SP_EUNSUPPORTED and launches nothing (use the
  * separate calls).  The part after the logits is done by one workgroup: the call pays while
  * L * H * N * T stays small (a few layers of a few thousand keys); the separate calls, which use
  * the whole device throughout, overtake it beyond that.

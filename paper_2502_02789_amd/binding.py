@@ -17,6 +17,7 @@ SP_LAYER_MAX, SP_LAYER_MEAN = 0, 1
 SP_MAX_LAYERS, SP_MAX_QUERIES = 128, 16
 SP_SCORE_EXCLUSIVE_DEVICE = 1
 SP_SCORE_WORKSPACE_KEPT = 2
+SP_K_BF16, SP_K_FP8_E4M3 = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecprefill.so")
 
@@ -43,6 +44,7 @@ class ScoreArgs(C.Structure):
         ("d_workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
         ("d_block_table", C.c_void_p), ("page_size", C.c_int32), ("blocks_per_seq", C.c_int32),
         ("k_page_stride", C.c_int64), ("flags", C.c_uint32), ("max_seqlen", C.c_int32),
+        ("k_dtype", C.c_int32), ("d_k_scale", C.c_void_p),
     ]
 
 
@@ -136,9 +138,10 @@ def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, sca
                     layer_reduce: int = SP_LAYER_MAX, n_valid=None, lse=None, workspace=None,
                     k_token_stride: Optional[int] = None, k_head_stride: Optional[int] = None,
                     T: Optional[int] = None, rope_theta: float = 0.0, q_pos=None,
-                    block_table=None, page_size: int = 0, flags: int = 0, max_seqlen: int = 0) -> ScoreArgs:
+                    block_table=None, page_size: int = 0, flags: int = 0, max_seqlen: int = 0, k_scale=None) -> ScoreArgs:
     """q: bf16 [L,B,N,H,d]; k_layers: L bf16 tensors [T,H_kv,d] (any token/head strides), or, with
-    block_table (int32 [B, blocks_per_seq]), L page pools [pages, page_size, H_kv, d] (then T must be given)."""
+    block_table (int32 [B, blocks_per_seq]), L page pools [pages, page_size, H_kv, d] (then T must be given).
+    uint8 layers are taken as an 8-bit float cache (SP_K_FP8_E4M3) with k_scale fp32 [L, H_kv] (None: all 1)."""
     L, B, N, H, d = q.shape
     a = ScoreArgs()
     a.B, a.N, a.L, a.H, a.H_kv, a.d = B, N, L, H, H_kv, d
@@ -172,6 +175,9 @@ def make_score_args(q, k_layers: Sequence, cu_seqlens, scores, *, H_kv: int, sca
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     a.flags = int(flags)
     a.max_seqlen = int(max_seqlen)
+    a.k_dtype = SP_K_FP8_E4M3 if k_layers[0].element_size() == 1 else SP_K_BF16
+    a.d_k_scale = _ptr(k_scale)
+    a._keepalive_scale = k_scale
     return a
 
 

@@ -274,7 +274,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_short_kernel(const FusedD
 }
 
 static bool fused_shape_ok(const sp_score_args* a) {
-  if (a->B != 1 || a->T < 1 || a->T > kFusedMaxKeys || a->rope_theta != 0.f || a->d_block_table) return false;
+  if (a->B != 1 || a->T < 1 || a->T > kFusedMaxKeys || a->rope_theta != 0.f || a->d_block_table || a->k_dtype != SP_K_BF16) return false;
   if (a->H_kv < 1 || a->H % a->H_kv != 0 || (a->d != 64 && a->d != 128)) return false;
   const int G = a->H / a->H_kv;
   if (G * a->N > kFusedMaxRows || (int64_t)a->L * a->H * a->N > kFusedMaxSoftmaxRows) return false;

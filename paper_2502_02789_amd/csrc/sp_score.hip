@@ -78,6 +78,34 @@ __device__ __forceinline__ void load_k_row(const uint16_t* __restrict__ kp, bool
   }
 }
 
+// the same from an 8-bit cache (OCP E4M3 codes, one byte per element): decoded exactly to fp32
+template <int D>
+__device__ __forceinline__ void load_k_row_fp8(const unsigned char* __restrict__ kp, bool valid, float (&kf)[D]) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  const uint4* p4 = reinterpret_cast<const uint4*>(kp);
+#pragma unroll
+  for (int c = 0; c < D / 16; ++c) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (valid) v = p4[c];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[j], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[j], true);
+      kf[16 * c + 4 * j + 0] = lo[0]; kf[16 * c + 4 * j + 1] = lo[1];
+      kf[16 * c + 4 * j + 2] = hi[0]; kf[16 * c + 4 * j + 3] = hi[1];
+    }
+  }
+}
+// row `off` (in elements) of layer l, either storage; scale of (layer, KV head) for an 8-bit cache
+template <int D>
+__device__ __forceinline__ void load_key(const ScoreDev& p, int l, int64_t off, bool valid, float (&kf)[D]) {
+  if (p.k_fp8) load_k_row_fp8<D>(reinterpret_cast<const unsigned char*>(p.k[l]) + off, valid, kf);
+  else load_k_row<D>(p.k[l] + off, valid, kf);
+}
+__device__ __forceinline__ float key_scale(const ScoreDev& p, int l, int g) {
+  return (p.k_fp8 && p.k_scale) ? p.scale * p.k_scale[l * p.H_kv + g] : p.scale;
+}
+
 // element offset of key `key` of sequence b (first token seq0) inside a layer, KV head 0
 __device__ __forceinline__ int64_t key_row_offset(const ScoreDev& p, int b, int seq0, int key) {
   if (!p.block_table) return (int64_t)(seq0 + key) * p.k_token_stride;
@@ -117,13 +145,14 @@ __global__ __launch_bounds__(64) void lse_partial_kernel(const ScoreDev p) {
   const int key = (tile - p.tile_cu[b]) * kTileKeys + lane;
   const bool valid = key < M;
   float kf[D];
-  load_k_row<D>(p.k[l] + key_row_offset(p, b, seq0, valid ? key : 0) + (int64_t)g * p.k_head_stride, valid, kf);
+  load_key<D>(p, l, key_row_offset(p, b, seq0, valid ? key : 0) + (int64_t)g * p.k_head_stride, valid, kf);
   if (p.rope) rope_row_inplace<D>(kf, p.rope + (int64_t)(valid ? key : 0) * (D / 2));
+  const float scale = key_scale(p, l, g);
   for (int n = 0; n < p.N; ++n) {
     for (int j = 0; j < p.G; ++j) {
       const int h = g * p.G + j;
       const uint16_t* qp = p.q + ((((int64_t)l * p.B + b) * p.N + n) * p.H + h) * D;
-      const float s = valid ? p.scale * dot_row<D>(qp, kf) : -INFINITY;
+      const float s = valid ? scale * dot_row<D>(qp, kf) : -INFINITY;
       const float m = wave_max(s);                       // finite: lane 0 of a tile is always valid
       const float e = valid ? expf(s - m) : 0.f;
       const float z = wave_sum(e);
@@ -190,8 +219,9 @@ __global__ __launch_bounds__(256) void score_accum_kernel(const ScoreDev p) {
     for (int n = 0; n < SP_MAX_QUERIES; ++n) nmax[n] = -INFINITY;
     for (int g = wave; g < p.H_kv; g += 4) {
       float kf[D];
-      load_k_row<D>(p.k[l] + row_off + (int64_t)g * p.k_head_stride, valid, kf);
+      load_key<D>(p, l, row_off + (int64_t)g * p.k_head_stride, valid, kf);
       if (p.rope) rope_row_inplace<D>(kf, p.rope + (int64_t)(valid ? key : 0) * (D / 2));
+      const float scale = key_scale(p, l, g);
 #pragma unroll
       for (int n = 0; n < SP_MAX_QUERIES; ++n) {
         if (n < p.N) {
@@ -199,7 +229,7 @@ __global__ __launch_bounds__(256) void score_accum_kernel(const ScoreDev p) {
           for (int j = 0; j < p.G; ++j) {
             const int h = g * p.G + j;
             const int64_t row = (((int64_t)l * p.B + b) * p.N + n) * p.H + h;
-            const float s = p.scale * dot_row<D>(p.q + row * D, kf);
+            const float s = scale * dot_row<D>(p.q + row * D, kf);
             mx = fmaxf(mx, s - p.ws_lse[row]);
           }
           nmax[n] = mx;
@@ -246,6 +276,7 @@ static bool shape_ok(const sp_score_args* a) {
   if (a->T < 0 || a->T >= (int64_t)INT32_MAX) return false;
   if ((int64_t)a->L * a->B * a->N * a->H >= (int64_t)INT32_MAX) return false;
   if (a->layer_reduce != SP_LAYER_MAX && a->layer_reduce != SP_LAYER_MEAN) return false;
+  if (a->k_dtype != SP_K_BF16 && a->k_dtype != SP_K_FP8_E4M3) return false;
   return true;
 }
 
@@ -253,7 +284,7 @@ static int general_max_tiles(const sp_score_args* a) { return (int)(a->T / kTile
 
 // the single-pass kernels are taken only on the caller's promise of an otherwise idle device
 bool single_pass_wanted(const sp_score_args* a) {
-  return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && (team_supported(a) || stream_supported(a));
+  return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && a->k_dtype == SP_K_BF16 && (team_supported(a) || stream_supported(a));
 }
 // where the single-pass kernel that sp_score would pick keeps its "a wait expired" word
 static size_t single_pass_status_offset(const sp_score_args* a) {
@@ -354,6 +385,8 @@ void fill_score_dev(const sp_score_args* a, ScoreDev* p) {
   while (a->d_block_table && (1 << p->lg_page) < a->page_size) ++p->lg_page;
   p->blocks_per_seq = a->blocks_per_seq;
   p->k_page_stride = a->k_page_stride;
+  p->k_fp8 = a->k_dtype == SP_K_FP8_E4M3;
+  p->k_scale = a->d_k_scale;
   for (int l = 0; l < SP_MAX_LAYERS; ++l)
     p->k[l] = l < a->L ? static_cast<const uint16_t*>(a->k_layers[l]) : nullptr;
 }
@@ -389,6 +422,12 @@ static sp_status check_score_args(const sp_score_args* a) {
     if (a->k_page_stride & 7) return SP_EALIGN;
   }
   if ((a->k_token_stride & 7) || (a->k_head_stride & 7) || !sp::aligned16(a->d_q)) return SP_EALIGN;
+  if (a->k_dtype == SP_K_FP8_E4M3) {
+    if (a->rope_theta > 0.f) return SP_EUNSUPPORTED;
+    if ((a->k_token_stride & 15) || (a->k_head_stride & 15) || (a->d_block_table && (a->k_page_stride & 15))) return SP_EALIGN;
+  } else if (a->d_k_scale) {
+    return SP_EINVAL;
+  }
   for (int l = 0; l < a->L; ++l)
     if (!sp::aligned16(a->k_layers[l])) return SP_EALIGN;
   if (!a->d_workspace || a->workspace_bytes < sp_score_workspace_bytes(a)) return SP_EWORKSPACE;

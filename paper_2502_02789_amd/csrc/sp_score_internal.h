@@ -25,6 +25,8 @@ struct ScoreDev {
   const int32_t* block_table;  // paged cache: [B][blocks_per_seq] page numbers, else null
   int lg_page, blocks_per_seq;
   int64_t k_page_stride;
+  const float* k_scale;  // 8-bit cache: [L][H_kv] scales (null: all 1); the layers then hold bytes
+  int k_fp8;
   const uint16_t* k[SP_MAX_LAYERS];
 };
 

@@ -325,7 +325,7 @@ void seq_grouping(const sp_score_args* a, int* layers_per_group, int* n_groups) 
 }
 
 bool seq_supported(const sp_score_args* a) {
-  if (a->rope_theta > 0.f || a->max_seqlen <= 0) return false;
+  if (a->rope_theta > 0.f || a->max_seqlen <= 0 || a->k_dtype != SP_K_BF16) return false;
   const int R = seq_rows(a), Gp = seq_padded_group(a);
   if (R == 0 || a->max_seqlen > seq_max_keys(a)) return false;
   if (Gp < 4) return false;                                 // instantiated: groups of 3..8 heads

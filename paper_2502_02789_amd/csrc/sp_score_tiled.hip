@@ -332,6 +332,7 @@ static int padded_group(const sp_score_args* a) {
 }
 
 bool tiled_supported(const sp_score_args* a) {
+  if (a->k_dtype != SP_K_BF16) return false;
   if (a->H / a->H_kv > 8) return false;
   if (padded_group(a) * a->N > 32) return false;
   if (a->T < 1) return false;

@@ -39,7 +39,8 @@ class Scorer:
                  n_valid: Optional[torch.Tensor] = None, want_lse: bool = False,
                  rope_theta: float = 0.0, q_pos: Optional[torch.Tensor] = None,
                  block_table: Optional[torch.Tensor] = None, page_size: int = 0, total_tokens: Optional[int] = None,
-                 exclusive_device: bool = True, keep_workspace: bool = False, max_seqlen: int = 0):
+                 exclusive_device: bool = True, keep_workspace: bool = False, max_seqlen: int = 0,
+                 k_scale: Optional[torch.Tensor] = None):
         """exclusive_device: promise that nothing else runs on the GPU during the call
         (SP_SCORE_EXCLUSIVE_DEVICE), which lets sp_score take its single-pass kernels.
         keep_workspace: from the second run() on, pass SP_SCORE_WORKSPACE_KEPT (this object owns
@@ -57,7 +58,7 @@ class Scorer:
         probe = sp.make_score_args(q, self.k_layers, cu_seqlens, self.scores, H_kv=H_kv, scale=scale,
                                    layer_reduce=layer_reduce, n_valid=n_valid, lse=self.lse,
                                    rope_theta=rope_theta, q_pos=q_pos, T=T, block_table=block_table,
-                                   page_size=page_size, flags=flags, max_seqlen=max_seqlen)
+                                   page_size=page_size, flags=flags, max_seqlen=max_seqlen, k_scale=k_scale)
         need = sp.sp_score_workspace_bytes(probe)
         if need == 0:
             raise sp.SpError("sp_score_workspace_bytes", sp.SP_EINVAL)
@@ -65,7 +66,7 @@ class Scorer:
         self.args = sp.make_score_args(q, self.k_layers, cu_seqlens, self.scores, H_kv=H_kv, scale=scale,
                                        layer_reduce=layer_reduce, n_valid=n_valid, lse=self.lse,
                                        workspace=self.workspace, rope_theta=rope_theta, q_pos=q_pos, T=T,
-                                       block_table=block_table, page_size=page_size, flags=flags, max_seqlen=max_seqlen)
+                                       block_table=block_table, page_size=page_size, flags=flags, max_seqlen=max_seqlen, k_scale=k_scale)
 
         self._base_flags, self._keep, self._kept = flags, keep_workspace, False
 

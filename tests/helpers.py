@@ -31,7 +31,7 @@ def gpu_score(q_bits, k_bits_layers, cu, H_kv, scale, mode, n_valid=None, genera
     return s.scores.cpu().numpy(), (s.lse.cpu().numpy() if want_lse else None)
 
 
-def paged_copy(k_bits_layers, cu, page_size, seed):
+def paged_copy(k_bits_layers, cu, page_size, seed, fill=0x7F00):
     """Scatters contiguous [T, H_kv, d] layers into shuffled page pools (with unused pages in
     between); returns (pools, block_table).  Unused rows hold a bit pattern that decodes to a huge
     value, so a kernel that reads a wrong row does not go unnoticed."""
@@ -50,7 +50,7 @@ def paged_copy(k_bits_layers, cu, page_size, seed):
             nxt += 1
     pools = []
     for k in k_bits_layers:
-        pool = np.full((n_pages, page_size) + k.shape[1:], 0x7F00, dtype=np.uint16)   # bf16 1.7e38
+        pool = np.full((n_pages, page_size) + k.shape[1:], fill, dtype=k.dtype)   # bf16 1.7e38 (8-bit caches: pass 0x7E = 448)
         for b in range(B):
             for i in range(int(lens[b])):
                 pool[table[b, i // page_size], i % page_size] = k[cu[b] + i]

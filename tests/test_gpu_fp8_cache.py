@@ -1,0 +1,122 @@
+"""GPU parity of sp_score on a K cache held as 8-bit floats (OCP E4M3 codes with one scale per layer and
+KV head) against the fp64 oracle evaluated on the decoded keys (Sec. 3.2 equation, Sec. 3.2.2), element
+by element, to the same tolerance as a bf16 cache."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import specprefill_oracle as orc
+from paper_2502_02789_amd import synth
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+MODES = [orc.LAYER_MAX, orc.LAYER_MEAN]
+
+
+def gpu_score_fp8(q_bits, codes, k_scale, cu, H_kv, scale, mode, general=False, n_valid=None, max_seqlen=0,
+                  exclusive_device=True, paged=0):
+    import torch
+    from paper_2502_02789_amd import binding as sp_binding, device as dev
+    q = dev.bf16_from_bits(q_bits)
+    cu_d = torch.from_numpy(np.asarray(cu, dtype=np.int32)).cuda()
+    nv_d = None if n_valid is None else torch.from_numpy(np.asarray(n_valid, dtype=np.int32)).cuda()
+    sc_d = None if k_scale is None else torch.from_numpy(np.ascontiguousarray(k_scale, dtype=np.float32)).cuda()
+    kw = {}
+    if paged:
+        pools, table = hp.paged_copy(codes, cu, paged, seed=paged, fill=0x7E)
+        ks = [torch.from_numpy(p).cuda() for p in pools]
+        kw = dict(block_table=torch.from_numpy(np.ascontiguousarray(table, dtype=np.int32)).cuda(), page_size=paged,
+                  total_tokens=int(cu[-1]))
+    else:
+        ks = [torch.from_numpy(np.ascontiguousarray(c)).cuda() for c in codes]
+    s = dev.Scorer(q, ks, cu_d, H_kv=H_kv, scale=scale, layer_reduce=mode, n_valid=nv_d, want_lse=True,
+                   exclusive_device=exclusive_device, max_seqlen=max_seqlen, k_scale=sc_d, **kw)
+    s.scores.fill_(float("nan"))
+    s.run(general=general)
+    sp_binding.sp_score_check(s.args)
+    return s.scores.cpu().numpy(), s.lse.cpu().numpy()
+
+
+def _check(w, mode, general, n_valid=None, unit_scale=False, **kw):
+    inp = synth.make_qk(w)
+    codes, k_scale = synth.quantize_k_fp8(inp["k"])
+    if unit_scale:
+        k_scale = None
+    scale = 1.0 / math.sqrt(w.d)
+    want, want_lse = orc.token_importance(inp["q"], codes, inp["cu_seqlens"], scale, mode, n_valid,
+                                          k_scale=np.ones((w.L, w.H_kv), dtype=np.float32) if unit_scale else k_scale)
+    got, lse = gpu_score_fp8(inp["q"], codes, k_scale, inp["cu_seqlens"], w.H_kv, scale, mode, general=general,
+                             n_valid=n_valid, **kw)
+    hp.assert_scores_close(got, want, f"{w.name} fp8 mode={mode} general={general}")
+    # (with the scales left out the decoded keys are up to 448 in size and the log-sum-exps in the thousands:
+    # fp32 holds them to 1e-7 relative, hence the relative part)
+    np.testing.assert_allclose(lse, want_lse, rtol=1e-6 if unit_scale else 0, atol=2e-4)
+    # the quantisation is visible: these are not the bf16 cache's scores
+    bf16, _ = orc.token_importance(inp["q"], inp["k"], inp["cu_seqlens"], scale, mode, n_valid)
+    if not unit_scale:
+        assert np.abs(bf16 - want).max() > 1e-3 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("general", [False, True])
+@pytest.mark.parametrize("mode", MODES)
+def test_one_prompt_several_tiles_and_ragged_tail(mode, general):
+    _check(synth.scaled(synth.workload(3), seqlens=(1500 + 13,), L=2), mode, general)
+    _check(synth.scaled(synth.workload(2), seqlens=(777,), L=3), mode, general)
+
+
+@pytest.mark.parametrize("general", [False, True])
+def test_ragged_batch_valid_query_counts_and_missing_scales(general):
+    w = synth.scaled(synth.workload(4), seqlens=(300, 0, 1, 65, 64, 129, 700), L=2, N=2, salient_frac=0.02, salient_run=1)
+    for mode in MODES:
+        _check(w, mode, general, n_valid=np.array([1, 1, 2, 2, 1, 2, 1], dtype=np.int32))
+    _check(w, orc.LAYER_MAX, general, unit_scale=True)
+
+
+@pytest.mark.parametrize("shape", [dict(H=8, H_kv=8), dict(H=16, H_kv=2), dict(H=6, H_kv=3, N=5), dict(H=5, H_kv=1, N=3)])
+def test_other_head_groupings(shape):
+    w = synth.scaled(synth.workload(2), seqlens=(517, 90), L=2, **shape)
+    for general in (False, True):
+        _check(w, orc.LAYER_MAX, general)
+
+
+@pytest.mark.parametrize("page", [16, 64])
+def test_paged_8bit_cache(page):
+    w = synth.scaled(synth.workload(4), seqlens=(300, 33, 1000), L=2, salient_frac=0.02, salient_run=1)
+    for general in (False, True):
+        _check(w, orc.LAYER_MAX, general, paged=page)
+
+
+def test_argument_rules_of_an_8bit_cache():
+    import torch
+    from paper_2502_02789_amd import binding as sp, device as dev
+    w = synth.scaled(synth.workload(1), seqlens=(128,))
+    inp = synth.make_qk(w)
+    codes, k_scale = synth.quantize_k_fp8(inp["k"])
+    q = dev.bf16_from_bits(inp["q"])
+    ks = [torch.from_numpy(c).cuda() for c in codes]
+    cu = torch.from_numpy(inp["cu_seqlens"]).cuda()
+    s = dev.Scorer(q, ks, cu, H_kv=w.H_kv, scale=0.125, k_scale=torch.from_numpy(k_scale).cuda())
+    s.args.rope_theta = 10000.0
+    s.args.d_q_pos = s.args.d_cu_seqlens
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score(s.args)
+    assert e.value.status == sp.SP_EUNSUPPORTED
+    s.args.rope_theta = 0.0
+    s.args.d_q_pos = None
+    s.args.k_token_stride = w.H_kv * w.d + 8          # a multiple of 8 but not of 16
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score(s.args)
+    assert e.value.status == sp.SP_EALIGN
+    s.args.k_token_stride = w.H_kv * w.d
+    s.args.k_dtype = 2
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score(s.args)
+    assert e.value.status in (sp.SP_EINVAL, sp.SP_EWORKSPACE)
+    # scales make no sense for a bf16 cache
+    b = dev.Scorer(q, [dev.bf16_from_bits(k) for k in inp["k"]], cu, H_kv=w.H_kv, scale=0.125)
+    b.args.d_k_scale = s.args.d_k_scale
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score(b.args)
+    assert e.value.status == sp.SP_EINVAL
