@@ -176,8 +176,8 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(w.acc[0][i]), __float_as_uint(w.acc[1][i]), false, false);
-          held[t][i] = left > 0 ? __uint_as_float(sw[0]) * p.c : -INFINITY;
-          if (R == 8) held[t][4 + i] = left > 0 ? __uint_as_float(sw[1]) * p.c : -INFINITY;
+          held[t][i] = left > 0 ? __uint_as_float(sw[0]) * w.c2 : -INFINITY;
+          if (R == 8) held[t][4 + i] = left > 0 ? __uint_as_float(sw[1]) * w.c2 : -INFINITY;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {

@@ -67,10 +67,10 @@ struct SlabCursor {
   }
 };
 
-template <int D, int PASS, bool MEAN, bool ROPE>
+template <int D, int PASS, bool MEAN, bool ROPE, bool FP8>
 __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledDev p) {
   extern __shared__ __align__(1024) unsigned char smem[];
-  using TW = TileWalker<D, ROPE>;
+  using TW = TileWalker<D, ROPE, FP8>;
   const int tile = blockIdx.x * kTiledWaves + (threadIdx.x >> 6);
   if (tile >= p.tile_cu[p.B]) return;  // (no workgroup barrier anywhere in this kernel)
   const int l0 = blockIdx.y * p.layers_per_group;
@@ -111,6 +111,7 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
 
   auto body = [&](auto par_tag) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_tag)::value;  // parity of the slab = ring slot of its query tile
+    w.slab_scale(cur.l, cur.g);
     w.wait_tile(PAR);
     w.read_queries(PAR);
     float neg_lse2 = 0.f;
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(kTiledThreads) void tiled_score_kernel(const TiledD
       for (int kb = 0; kb < 2; ++kb) {
         float x[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = fmaf(w.acc[kb][i], p.c, neg_lse2);
+        for (int i = 0; i < 16; ++i) x[i] = fmaf(w.acc[kb][i], w.c2, neg_lse2);
         if (p.lgG >= 1) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) x[i] = max_quad_xor1(x[i]);
@@ -332,7 +333,8 @@ static int padded_group(const sp_score_args* a) {
 }
 
 bool tiled_supported(const sp_score_args* a) {
-  if (a->k_dtype != SP_K_BF16) return false;
+  // (an 8-bit cache behind a block table: the 8 or 16 rows of one direct load must lie in one page)
+  if (a->k_dtype == SP_K_FP8_E4M3 && a->d_block_table && a->page_size < (a->d == 64 ? 16 : 8)) return false;
   if (a->H / a->H_kv > 8) return false;
   if (padded_group(a) * a->N > 32) return false;
   if (a->T < 1) return false;
@@ -369,10 +371,10 @@ size_t tiled_extra_workspace_bytes(const sp_score_args* a) {
          (a->rope_theta > 0.f ? align_up(sizeof(float4) * (size_t)rope_tile_table_entries(a), 256) : 0);
 }
 
-template <int D, int PASS, bool MEAN, bool ROPE>
+template <int D, int PASS, bool MEAN, bool ROPE, bool FP8>
 static sp_status launch_tiled(const TiledDev& dev, hipStream_t stream) {
-  auto kernel = tiled_score_kernel<D, PASS, MEAN, ROPE>;
-  const size_t smem = TileWalker<D, ROPE>::smem_bytes();
+  auto kernel = tiled_score_kernel<D, PASS, MEAN, ROPE, FP8>;
+  const size_t smem = TileWalker<D, ROPE, FP8>::smem_bytes();
   static std::mutex mu;  // once per kernel and device
   static bool prepared[kMaxDevices] = {};
   {
@@ -390,10 +392,10 @@ static sp_status launch_tiled(const TiledDev& dev, hipStream_t stream) {
   return launch_status();
 }
 
-template <int D, bool ROPE>
+template <int D, bool ROPE, bool FP8>
 static sp_status tiled_passes(const TiledDev& dev, const ScoreDev& gen, hipStream_t stream) {
   if (dev.logits) {
-    const sp_status st = launch_tiled<D, 2, false, ROPE>(dev, stream);
+    const sp_status st = launch_tiled<D, 2, false, ROPE, FP8>(dev, stream);
     if (st != SP_OK) return st;
     launch_lse_combine(gen, stream);
     const dim3 grid((unsigned)((dev.T * 4 + 255) / 256));
@@ -401,11 +403,11 @@ static sp_status tiled_passes(const TiledDev& dev, const ScoreDev& gen, hipStrea
     else hipLaunchKernelGGL(logit_score_kernel<false>, grid, dim3(256), 0, stream, dev);
     return launch_status();
   }
-  sp_status st = launch_tiled<D, 0, false, ROPE>(dev, stream);
+  sp_status st = launch_tiled<D, 0, false, ROPE, FP8>(dev, stream);
   if (st != SP_OK) return st;
   launch_lse_combine(gen, stream);
-  st = dev.layer_reduce == SP_LAYER_MEAN ? launch_tiled<D, 1, true, ROPE>(dev, stream)
-                                         : launch_tiled<D, 1, false, ROPE>(dev, stream);
+  st = dev.layer_reduce == SP_LAYER_MEAN ? launch_tiled<D, 1, true, ROPE, FP8>(dev, stream)
+                                         : launch_tiled<D, 1, false, ROPE, FP8>(dev, stream);
   if (st != SP_OK) return st;
   hipLaunchKernelGGL(tiled_finish_kernel, dim3((unsigned)((dev.T + 255) / 256)), dim3(256), 0, stream, dev);
   return launch_status();
@@ -427,6 +429,7 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
   dev.q = gen.q; dev.cu = gen.cu; dev.n_valid = gen.n_valid; dev.tile_cu = gen.tile_cu;
   dev.ws_lse = gen.ws_lse; dev.part = gen.part;
   dev.lse_out = a->d_lse;
+  dev.k_scale = a->d_k_scale;
   dev.seq_limit = 0;
   dev.seq_order = nullptr;
   if (seq_supported(a)) {  // one pass over K, a workgroup per (sequence, layer group)
@@ -460,9 +463,11 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
     hipLaunchKernelGGL(rope_tile_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, table, n,
                        a->d / 32, a->d / 2, std::log2((double)a->rope_theta), a->B, a->d_cu_seqlens);
     dev.rope_tiles = table;
-    return a->d == 64 ? tiled_passes<64, true>(dev, gen, stream) : tiled_passes<128, true>(dev, gen, stream);
+    return a->d == 64 ? tiled_passes<64, true, false>(dev, gen, stream) : tiled_passes<128, true, false>(dev, gen, stream);
   }
-  return a->d == 64 ? tiled_passes<64, false>(dev, gen, stream) : tiled_passes<128, false>(dev, gen, stream);
+  if (a->k_dtype == SP_K_FP8_E4M3)
+    return a->d == 64 ? tiled_passes<64, false, true>(dev, gen, stream) : tiled_passes<128, false, true>(dev, gen, stream);
+  return a->d == 64 ? tiled_passes<64, false, false>(dev, gen, stream) : tiled_passes<128, false, false>(dev, gen, stream);
 }
 
 }  // namespace sp

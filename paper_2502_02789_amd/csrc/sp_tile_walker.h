@@ -47,6 +47,7 @@ struct TiledDev {
   // un-rotated cache: (cos, sin) of every position's rotation, in the order the waves consume it
   // (see rope_tile_table_kernel), else null
   const float4* rope_tiles;
+  const float* k_scale;  // 8-bit cache (FP8 kernels): [L][H_kv] scales of the keys, or null (all 1)
   const uint16_t* k[SP_MAX_LAYERS];
 };
 
@@ -62,14 +63,25 @@ __device__ __forceinline__ void wait_vmcnt_upto_wide(int n) {
   else wait_vmcnt_upto(n);
 }
 
-template <int D, bool ROPE>
+// FP8: the keys are OCP E4M3 bytes (one byte per element, a scale per layer and KV head); the query
+// rows stay bf16.  A key row is then half as long; its 16-byte units hold 16 elements, i.e. TWO MFMA
+// k-steps, so a lane reads whole units (upper half-wave: the odd ones), widens the bytes to bf16 in
+// registers (exact) and the query operand is read in the matching order (k-step 2j + e of half-wave h
+// multiplies elements 16 (2j + h) + 8e ... + 7: any order will do as long as both operands agree).
+template <int D, bool ROPE, bool FP8 = false>
 struct TileWalker {
+  static_assert(!(ROPE && FP8), "8-bit caches are taken as already rotated");
   static constexpr int KS = D / 16;            // MFMA k-steps per tile
-  static constexpr int ROW_B = D * 2;          // bytes of one row (one key / one query row)
-  static constexpr int TILE_B = 32 * ROW_B;    // 32 rows
+  static constexpr int ROW_B = D * 2;          // bytes of one query row (and of one bf16 key)
+  static constexpr int TILE_B = 32 * ROW_B;    // 32 rows: a ring slot
   static constexpr int UNITS = ROW_B / 16;     // 16-byte units per row
   static constexpr int LOADS = TILE_B / 1024;  // wave-wide 16-byte loads per tile
   static constexpr int RPI = 64 / UNITS;       // rows covered by one such load
+  static constexpr int ESZ = FP8 ? 1 : 2;      // bytes per key element
+  static constexpr int KROW_B = D * ESZ;       // the same for a key tile
+  static constexpr int KUNITS = KROW_B / 16;
+  static constexpr int KLOADS = 32 * KROW_B / 1024;
+  static constexpr int KRPI = 64 / KUNITS;
 
   const TiledDev& p;
   int wave, lane, half, col;
@@ -77,6 +89,8 @@ struct TileWalker {
   int64_t tok0;          // flat token index of the tile's first key
   int issued, seq_a, seq_b;  // vector-memory instructions issued so far; value right after the loads into slot 0 / 1
   uint32_t ring_lds, lse_lds, part_lds, rd0, u0;
+  uint32_t krd0, qrd0;   // FP8: where this lane reads its key units / its query units from (ring slot 0)
+  float c2, scale;        // logits -> base-2 / natural-log domain for the current slab (an 8-bit cache's key scale included)
   int part_n;            // slabs waiting in the statistics buffer
   uint32_t ld_off[4];
   bf16x8 qf[KS];
@@ -126,6 +140,28 @@ struct TileWalker {
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj)
       ld_off[jj] = (uint32_t)((int64_t)i * p.ts * 2) + (uint32_t)((u0 ^ ((4 * jj) & (UNITS - 1))) << 4);
+    c2 = p.c;
+    scale = p.scale;
+    krd0 = qrd0 = 0;
+    if constexpr (FP8) {
+      // key tile: row r at r*KROW_B, unit u at position u ^ (r & (KUNITS - 1)); the lane of a wave-wide load
+      // that fills row (lane / KUNITS) of its KRPI rows, position lane % KUNITS, fetches that unit
+      const int ki = lane / KUNITS;
+      u0 = (lane % KUNITS) ^ (ki & (KUNITS - 1));
+      ld_off[0] = (uint32_t)((int64_t)ki * p.ts) + (u0 << 4);
+      krd0 = ring_lds + col * KROW_B + ((half ^ (col & (KUNITS - 1))) << 4);
+      qrd0 = ring_lds + col * ROW_B + (((2 * half) ^ key) << 4);
+    }
+  }
+  // the scale of the keys of (layer l, KV head g) joins the logit scale (8-bit cache)
+  __device__ __forceinline__ void slab_scale(int l, int g) {
+    if constexpr (FP8) {
+      if (p.k_scale) {
+        const float ks = p.k_scale[l * p.H_kv + g];
+        c2 = p.c * ks;
+        scale = p.scale * ks;
+      }
+    }
   }
 
   static size_t smem_bytes() { return (size_t)kTiledWaves * (2 * TILE_B + 512 + kPartBufBytes); }
@@ -188,57 +224,58 @@ struct TileWalker {
     asm volatile("" : "+s"(rows));
     if (p.block_table) {
       issue_keys_paged(l, g, key_first, rows, dst);
-      note_issued(LOADS);
+      note_issued(KLOADS);
       mark_slot(slot);
       return;
     }
     const int64_t tok = (int64_t)seq0 + key_first;
-    const unsigned char* base = reinterpret_cast<const unsigned char*>(p.k[l]) + 2 * ((int64_t)g * p.hs + tok * p.ts);
+    const unsigned char* base = reinterpret_cast<const unsigned char*>(p.k[l]) + ESZ * ((int64_t)g * p.hs + tok * p.ts);
     if (rows == 32) {
 #pragma unroll
-      for (int j = 0; j < LOADS; ++j) {
-        uint32_t lane_off = ld_off[j & 3];
+      for (int j = 0; j < KLOADS; ++j) {
+        uint32_t lane_off = ld_off[FP8 ? 0 : (j & 3)];
         asm volatile("" : "+v"(lane_off));
-        __builtin_amdgcn_global_load_lds(base + (int64_t)(j * RPI) * p.ts * 2 + (size_t)lane_off, lds_ptr(dst + j * 1024),
+        __builtin_amdgcn_global_load_lds(base + (int64_t)(j * KRPI) * p.ts * ESZ + (size_t)lane_off, lds_ptr(dst + j * 1024),
                                          16, 0, 0);
       }
     } else {
       int ln = lane;
       asm volatile("" : "+v"(ln));
-      const int i = ln / UNITS;
+      const int i = ln / KUNITS;
 #pragma unroll
-      for (int j = 0; j < LOADS; ++j) {
-        const int r = j * RPI + i;
-        const int64_t row_off = r < rows ? (int64_t)r * p.ts * 2 : 0;
-        const uint32_t unit = u0 ^ ((4 * j) & (UNITS - 1));
+      for (int j = 0; j < KLOADS; ++j) {
+        const int r = j * KRPI + i;
+        const int64_t row_off = r < rows ? (int64_t)r * p.ts * ESZ : 0;
+        const uint32_t unit = FP8 ? u0 : (u0 ^ ((4 * j) & (UNITS - 1)));
         __builtin_amdgcn_global_load_lds(base + row_off + (unit << 4), lds_ptr(dst + j * 1024), 16, 0, 0);
       }
     }
-    note_issued(LOADS);
+    note_issued(KLOADS);
     mark_slot(slot);
   }
 
   // The same from a paged cache.  key_first: in-sequence index of the tile's row 0 (a multiple of
-  // 32).  The RPI (4 or 8) rows of one load lie in one page: pages hold a power of two >= 8 keys.
+  // 32).  The KRPI (4 or 8; 8 or 16 with an 8-bit cache) rows of one load lie in one page: pages hold a power of
+  // two >= 8 keys (>= 16 where a load has 16 rows; the host checks).
   // Loads whose rows are all beyond the sequence, and lanes beyond it, re-read a valid row.
   __device__ __forceinline__ void issue_keys_paged(int l, int g, int key_first, int rows, uint32_t dst) {
-    const unsigned char* layer = reinterpret_cast<const unsigned char*>(p.k[l]) + 2 * (int64_t)g * p.hs;
+    const unsigned char* layer = reinterpret_cast<const unsigned char*>(p.k[l]) + ESZ * (int64_t)g * p.hs;
     const int32_t* table = p.block_table + (int64_t)b * p.blocks_per_seq;
     const int pmask = (1 << p.lg_page) - 1;
     int ln = lane;
     asm volatile("" : "+v"(ln));
-    const int i = ln / UNITS;
+    const int i = ln / KUNITS;
     const unsigned char* base = layer;
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-      const bool inside = j * RPI < rows;
-      const int kk = inside ? key_first + j * RPI : key_first;
-      if (j == 0 || !inside || ((j * RPI) & pmask) == 0)  // first load, fallback row, or a new page begins
-        base = layer + 2 * ((int64_t)table[kk >> p.lg_page] * p.page_stride + (int64_t)(kk & pmask) * p.ts);
+    for (int j = 0; j < KLOADS; ++j) {
+      const bool inside = j * KRPI < rows;
+      const int kk = inside ? key_first + j * KRPI : key_first;
+      if (j == 0 || !inside || ((j * KRPI) & pmask) == 0)  // first load, fallback row, or a new page begins
+        base = layer + ESZ * ((int64_t)table[kk >> p.lg_page] * p.page_stride + (int64_t)(kk & pmask) * p.ts);
       else
-        base += (int64_t)RPI * p.ts * 2;
-      const int64_t row_off = (j * RPI + i < rows) ? (int64_t)i * p.ts * 2 : 0;
-      const uint32_t unit = u0 ^ ((4 * j) & (UNITS - 1));
+        base += (int64_t)KRPI * p.ts * ESZ;
+      const int64_t row_off = (j * KRPI + i < rows) ? (int64_t)i * p.ts * ESZ : 0;
+      const uint32_t unit = FP8 ? u0 : (u0 ^ ((4 * j) & (UNITS - 1)));
       __builtin_amdgcn_global_load_lds(base + row_off + (unit << 4), lds_ptr(dst + j * 1024), 16, 0, 0);
     }
   }
@@ -284,8 +321,37 @@ struct TileWalker {
         lds_ptr((base ^ (uint32_t)(t << 5)) + slot * TILE_B));
   }
   __device__ __forceinline__ void read_queries(int slot) {
+    if constexpr (FP8) {  // k-step 2j + e of this half-wave: query elements 16 (2j + h) + 8e ... = unit 4j + 2h + e
+      uint32_t base = qrd0;
+      asm volatile("" : "+v"(base));
+#pragma unroll
+      for (int t = 0; t < KS; ++t)
+        qf[t] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+            lds_ptr((base ^ (uint32_t)((4 * (t >> 1) + (t & 1)) << 4)) + slot * TILE_B));
+      return;
+    }
 #pragma unroll
     for (int t = 0; t < KS; ++t) qf[t] = read_unit(t, slot);
+  }
+  // FP8: the key operand of all k-steps: unit 2j + h of the lane's key, its 16 bytes widened to bf16 (exact)
+  __device__ __forceinline__ void read_keys_fp8(bf16x8 (&kf)[KS], int slot) {
+    uint32_t base = krd0;
+    asm volatile("" : "+v"(base));
+#pragma unroll
+    for (int j = 0; j < KS / 2; ++j) {
+      const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(
+          lds_ptr((base ^ (uint32_t)((2 * j) << 4)) + slot * TILE_B));
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        u32x4 o;
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          o[2 * x] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v[2 * e + x], 1.0f, false));
+          o[2 * x + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v[2 * e + x], 1.0f, true));
+        }
+        kf[2 * j + e] = __builtin_bit_cast(bf16x8, o);
+      }
+    }
   }
   // QROWS = false: register i of acc[kb] holds key (i / 4) * 8 + (i % 4) (+ 4 for the upper half-wave) of the
   // tile for query row `col`; QROWS = true: the operands change places, so that it holds that QUERY ROW for
@@ -294,6 +360,15 @@ struct TileWalker {
   __device__ __forceinline__ void mfma_tile(int kb, int slot) {
     f32x16 a = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     bf16x8 kf[KS];
+    if constexpr (FP8) {
+      read_keys_fp8(kf, slot);
+#pragma unroll
+      for (int t = 0; t < KS; ++t)
+        a = QROWS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t], kf[t], a, 0, 0, 0)
+                  : __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], a, 0, 0, 0);
+      acc[kb] = a;
+      return;
+    }
 #pragma unroll
     for (int t = 0; t < KS; ++t) kf[t] = read_unit(t, slot);
     if constexpr (ROPE) {  // rotate, ask for the other tile's table (the registers are free now), multiply
@@ -335,14 +410,14 @@ struct TileWalker {
     for (int i = 1; i < 16; ++i) tm = fmaxf(tm, a[i]);
     const float m_new = fmaxf(run_m, tm);
     const float ref = (m_new == -INFINITY) ? 0.f : m_new;
-    const float off = -ref * p.c;
-    float s0 = run_s * fast_exp2(fmaf(run_m, p.c, off)), s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    const float off = -ref * c2;
+    float s0 = run_s * fast_exp2(fmaf(run_m, c2, off)), s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; i += 4) {
-      s0 += fast_exp2(fmaf(a[i], p.c, off));
-      s1 += fast_exp2(fmaf(a[i + 1], p.c, off));
-      s2 += fast_exp2(fmaf(a[i + 2], p.c, off));
-      s3 += fast_exp2(fmaf(a[i + 3], p.c, off));
+      s0 += fast_exp2(fmaf(a[i], c2, off));
+      s1 += fast_exp2(fmaf(a[i + 1], c2, off));
+      s2 += fast_exp2(fmaf(a[i + 2], c2, off));
+      s3 += fast_exp2(fmaf(a[i + 3], c2, off));
     }
     run_m = m_new;
     run_s = (s0 + s1) + (s2 + s3);
@@ -355,12 +430,12 @@ struct TileWalker {
     const float pm = __shfl_xor(run_m, 32, kWave), ps = __shfl_xor(run_s, 32, kWave);
     const float mn = fmaxf(run_m, pm);
     const float ref = (mn == -INFINITY) ? 0.f : mn;
-    const float z = run_s * fast_exp2((run_m - ref) * p.c) + ps * fast_exp2((pm - ref) * p.c);
+    const float z = run_s * fast_exp2((run_m - ref) * c2) + ps * fast_exp2((pm - ref) * c2);
     int c = col;
     asm volatile("" : "+v"(c));
     const int rows = p.Gp * p.N;
     if (half == 0 && c < rows)
-      lds_poke64<0>(part_lds + (part_n * rows + c) * 8, ((uint64_t)__float_as_uint(z) << 32) | __float_as_uint(mn * p.scale));
+      lds_poke64<0>(part_lds + (part_n * rows + c) * 8, ((uint64_t)__float_as_uint(z) << 32) | __float_as_uint(mn * scale));
     part_n = __builtin_amdgcn_readfirstlane(part_n + 1);
   }
   __device__ __forceinline__ bool partials_full(int buf_bytes) const { return (part_n + 1) * p.Gp * p.N * 8 > buf_bytes; }
@@ -380,7 +455,7 @@ struct TileWalker {
 #pragma unroll
         for (int i = 0; i < 16; ++i)
           lds_poke32(stage + ((kb * 32 + (i >> 2) * 8 + h * 4 + (i & 3)) * kKeepRows + c) * 4,
-                     __float_as_uint(acc[kb][i] * p.c));
+                     __float_as_uint(acc[kb][i] * c2));
     }
     return lds_peek128(stage + ln * 16);  // (LDS operations of a wave are performed in order)
   }
