@@ -197,11 +197,11 @@ class Problem:
         return n_keep * (row + 4 * 4)
 
 
-def side_measurement(number, layer_reduce, steps, warmup, raw_cache_too=False):
+def side_measurement(number, layer_reduce, steps, warmup, raw_cache_too=False, fp8_too=False):
     """GPU-only timing of another workload / layer reduction (no oracle leg), cross-checked
     against the library's plain two-pass kernels on the same inputs.  raw_cache_too: the same
     buffers once more taken as an UN-rotated cache that sp_score rotates itself (rope_theta > 0),
-    cross-checked the same way."""
+    cross-checked the same way.  fp8_too: the same keys as an 8-bit cache."""
     import numpy as np
     import torch
     from paper_2502_02789_amd import binding as sp
@@ -245,6 +245,43 @@ def side_measurement(number, layer_reduce, steps, warmup, raw_cache_too=False):
         rel2 = float((np.abs(two.scores.cpu().numpy().astype(np.float64) - plain) / np.maximum(np.abs(plain), 1e-300)).max())
         out["ok"] = bool(out["ok"] and rel2 <= 2 * SCORE_RTOL)
         del two
+        torch.cuda.empty_cache()
+    if fp8_too:
+        # the same keys once more as an 8-bit cache (OCP E4M3 codes, one scale per layer and KV head; quantised
+        # here with torch, which is input preparation), cross-checked against the plain kernels on the same codes
+        from paper_2502_02789_amd import device as dev
+        mode = sp.SP_LAYER_MAX if layer_reduce == "max" else sp.SP_LAYER_MEAN
+        codes, scales = [], []
+        for k in pr.scorer.k_layers:
+            amax = k.abs().amax(dim=(0, 2)).float()
+            sc = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
+            codes.append((k.float() / sc[None, :, None]).to(torch.float8_e4m3fn).view(torch.uint8))
+            scales.append(sc)
+        k_scale = torch.stack(scales).contiguous()
+        f8 = dev.Scorer(pr.scorer.q, codes, pr.scorer.cu, H_kv=w.H_kv, scale=1.0 / math.sqrt(w.d), layer_reduce=mode,
+                        exclusive_device=True, max_seqlen=max(w.seqlens) if w.B > 1 else 0, k_scale=k_scale)
+        ms = []
+        for i in range(warmup + steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(pr.stream)
+            f8.run(pr.stream)
+            b.record(pr.stream)
+            if i >= warmup:
+                ms.append((a, b))
+        torch.cuda.synchronize()
+        t8 = sum(a.elapsed_time(b) for a, b in ms) / len(ms)
+        fast8 = f8.scores.cpu().numpy().astype(np.float64)
+        f8.run(pr.stream, general=True)
+        torch.cuda.synchronize()
+        plain8 = f8.scores.cpu().numpy().astype(np.float64)
+        rel8 = float((np.abs(fast8 - plain8) / np.maximum(np.abs(plain8), 1e-300)).max())
+        algo8 = w.k_bytes() // 2 + 4 * w.T
+        out["fp8_cache_sp_score_us"] = t8 * 1e3
+        out["fp8_cache_gbps"] = algo8 / (t8 * 1e-3) / 1e9
+        out["fp8_cache_frac_of_hbm_peak"] = algo8 / (t8 * 1e-3) / 1e9 / HBM_PEAK_GBPS
+        out["fp8_cache_max_rel_diff_vs_plain_kernels"] = rel8
+        out["ok"] = bool(out["ok"] and rel8 <= 2 * SCORE_RTOL)
+        del f8, codes
         torch.cuda.empty_cache()
     if raw_cache_too:
         from paper_2502_02789_amd import device as dev
@@ -335,6 +372,8 @@ def main():
     ap.add_argument("--cpu-sample-layers", type=int, default=0,
                     help="layers the oracle is timed on (0: as many as fit about 15 s, all of them if possible)")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--only-also", type=int, default=0, metavar="N",
+                    help="print only the side measurement of workload N (with its 8-bit and raw-cache variants) and exit")
     ap.add_argument("--no-also", action="store_true",
                     help="skip the GPU-only side measurements of the other workloads and of the layer-mean mode")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
@@ -354,6 +393,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.only_also:
+        print(json.dumps(side_measurement(args.only_also, args.layer_reduce, steps=args.steps, warmup=args.warmup,
+                                          raw_cache_too=(args.only_also == 4), fp8_too=True)), flush=True)
+        return
     pr = Problem(args.workload, args.layer_reduce)
     w = pr.w
     if args.calibrate_copy:
@@ -446,9 +489,13 @@ def main():
         del pr
         torch.cuda.empty_cache()
         also = []
-        for number, mode in ((3, "mean" if args.layer_reduce == "max" else "max"), (2, "max"), (5, "max"), (4, "max")):
+        other = "mean" if args.layer_reduce == "max" else "max"
+        # (workload, layer reduction, also as an 8-bit cache); the last entry is the headline workload again, for
+        # its 8-bit figures
+        for number, mode, fp8 in ((3, other, False), (2, "max", False), (5, "max", False), (4, "max", True),
+                                  (3, args.layer_reduce, True)):
             also.append(side_measurement(number, mode, steps=20, warmup=40 if number != 4 else 10,
-                                         raw_cache_too=(number == 4)))
+                                         raw_cache_too=(number == 4), fp8_too=fp8))
             ok = ok and also[-1]["ok"]
         also.append(short_prompt_measurement(steps=50, warmup=20))
         ok = ok and also[-1]["ok"]

@@ -79,10 +79,10 @@ __device__ __forceinline__ bool seq_next_unit(const TiledDev& p, int wave, int k
   }
 }
 
-template <int D, int R, int LG, bool MEAN>
+template <int D, int R, int LG, bool MEAN, bool FP8>
 __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev p) {
   extern __shared__ __align__(1024) unsigned char smem[];
-  using TW = TileWalker<D, false>;
+  using TW = TileWalker<D, false, FP8>;
   constexpr int MAXT = SeqLimits<R>::kMaxTiles;
   constexpr int GP = 1 << LG;   // heads of a KV group, padded to a power of two
   constexpr int NQ = R >> LG;   // queries whose rows fit the R held rows
@@ -153,6 +153,7 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
       issue_next(slot);
       ++pos;
     }
+    w.slab_scale(l, g);
     float rm[R], rs[R];  // this lane's running max and sum of exp2 per row, base-2 logits
 #pragma unroll
     for (int r = 0; r < R; ++r) { rm[r] = -INFINITY; rs[r] = 0.f; }
@@ -325,7 +326,8 @@ void seq_grouping(const sp_score_args* a, int* layers_per_group, int* n_groups) 
 }
 
 bool seq_supported(const sp_score_args* a) {
-  if (a->rope_theta > 0.f || a->max_seqlen <= 0 || a->k_dtype != SP_K_BF16) return false;
+  if (a->rope_theta > 0.f || a->max_seqlen <= 0) return false;
+  if (a->k_dtype == SP_K_FP8_E4M3 && a->d_block_table && a->page_size < (a->d == 64 ? 16 : 8)) return false;
   const int R = seq_rows(a), Gp = seq_padded_group(a);
   if (R == 0 || a->max_seqlen > seq_max_keys(a)) return false;
   if (Gp < 4) return false;                                 // instantiated: groups of 3..8 heads
@@ -360,10 +362,10 @@ static int seq_cu_count() {  // compute units of the current device
   return cached[slot];
 }
 
-template <int D, int R, int LG, bool MEAN>
+template <int D, int R, int LG, bool MEAN, bool FP8>
 static sp_status launch_seq(const TiledDev& dev, hipStream_t stream) {
-  auto kernel = seq_score_kernel<D, R, LG, MEAN>;
-  const size_t smem = TileWalker<D, false>::smem_bytes();
+  auto kernel = seq_score_kernel<D, R, LG, MEAN, FP8>;
+  const size_t smem = TileWalker<D, false, FP8>::smem_bytes();
   static std::mutex mu;  // once per kernel and device
   static bool prepared[kMaxDevices] = {};
   {
@@ -382,10 +384,14 @@ static sp_status launch_seq(const TiledDev& dev, hipStream_t stream) {
   return launch_status();
 }
 
-template <int D, bool MEAN>
+template <int D, bool MEAN, bool FP8>
 static sp_status seq_by_rows(const TiledDev& dev, int R, hipStream_t stream) {
-  if (dev.lgG == 2) return R == 4 ? launch_seq<D, 4, 2, MEAN>(dev, stream) : launch_seq<D, 8, 2, MEAN>(dev, stream);
-  return launch_seq<D, 8, 3, MEAN>(dev, stream);
+  if (dev.lgG == 2) return R == 4 ? launch_seq<D, 4, 2, MEAN, FP8>(dev, stream) : launch_seq<D, 8, 2, MEAN, FP8>(dev, stream);
+  return launch_seq<D, 8, 3, MEAN, FP8>(dev, stream);
+}
+template <int D, bool FP8>
+static sp_status seq_by_mode(const TiledDev& dev, int R, bool mean, hipStream_t stream) {
+  return mean ? seq_by_rows<D, true, FP8>(dev, R, stream) : seq_by_rows<D, false, FP8>(dev, R, stream);
 }
 
 // `dev` as the tiled kernels fill it in, with group_scores, layers_per_group, n_groups and
@@ -398,8 +404,9 @@ sp_status seq_score(const sp_score_args* a, const TiledDev& dev_, hipStream_t st
   dev.seq_order = order;
   const int R = seq_rows(a);
   const bool mean = a->layer_reduce == SP_LAYER_MEAN;
-  if (a->d == 64) return mean ? seq_by_rows<64, true>(dev, R, stream) : seq_by_rows<64, false>(dev, R, stream);
-  return mean ? seq_by_rows<128, true>(dev, R, stream) : seq_by_rows<128, false>(dev, R, stream);
+  const bool fp8 = a->k_dtype == SP_K_FP8_E4M3;
+  if (a->d == 64) return fp8 ? seq_by_mode<64, true>(dev, R, mean, stream) : seq_by_mode<64, false>(dev, R, mean, stream);
+  return fp8 ? seq_by_mode<128, true>(dev, R, mean, stream) : seq_by_mode<128, false>(dev, R, mean, stream);
 }
 
 }  // namespace sp

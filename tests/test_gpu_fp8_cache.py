@@ -120,3 +120,15 @@ def test_argument_rules_of_an_8bit_cache():
     with pytest.raises(sp.SpError) as e:
         sp.sp_score(b.args)
     assert e.value.status == sp.SP_EINVAL
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("shape", [dict(H=8, H_kv=2, N=1, d=128), dict(H=8, H_kv=2, N=2, d=64), dict(H=10, H_kv=2, N=1, d=128)])
+def test_batch_of_short_prompts_in_one_pass(shape, mode):
+    """The single-pass batch kernel (max_seqlen promised) on an 8-bit cache: tile edges, a sequence of
+    several tiles per wave, empty and one-key sequences."""
+    lens = (0, 1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 500, 512, 513, 1029, 1100) + tuple(40 + 7 * i for i in range(48))
+    w = synth.scaled(synth.workload(4), seqlens=lens, L=8, salient_frac=0.02, salient_run=1, **shape)
+    _check(w, mode, False, max_seqlen=1100, exclusive_device=False)
+    if shape["d"] == 128:
+        _check(w, mode, False, max_seqlen=1100, paged=16)
