@@ -284,7 +284,8 @@ static int general_max_tiles(const sp_score_args* a) { return (int)(a->T / kTile
 
 // the single-pass kernels are taken only on the caller's promise of an otherwise idle device
 bool single_pass_wanted(const sp_score_args* a) {
-  return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && a->k_dtype == SP_K_BF16 && (team_supported(a) || stream_supported(a));
+  // (an 8-bit cache: the team kernel only)
+  return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && (team_supported(a) || (a->k_dtype == SP_K_BF16 && stream_supported(a)));
 }
 // where the single-pass kernel that sp_score would pick keeps its "a wait expired" word
 static size_t single_pass_status_offset(const sp_score_args* a) {

@@ -74,9 +74,9 @@ struct TeamDev : StreamShape {
   float* lse_out;
 };
 
-template <int D, int TPW, bool PAGED>
-struct Teamer : StreamCore<D, TPW, PAGED> {
-  using Core = StreamCore<D, TPW, PAGED>;
+template <int D, int TPW, bool PAGED, bool FP8>
+struct Teamer : StreamCore<D, TPW, PAGED, FP8> {
+  using Core = StreamCore<D, TPW, PAGED, FP8>;
   using Core::NSETS; using Core::RING_BYTES;
   using Core::wave; using Core::lane; using Core::half; using Core::col;
   using Core::issued; using Core::run_m; using Core::run_s;
@@ -324,10 +324,10 @@ struct Teamer : StreamCore<D, TPW, PAGED> {
   }
 };
 
-template <int D, int TPW, bool PAGED, bool MEAN>
+template <int D, int TPW, bool PAGED, bool MEAN, bool FP8>
 __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
   extern __shared__ __align__(1024) unsigned char smem[];
-  using Tm = Teamer<D, TPW, PAGED>;
+  using Tm = Teamer<D, TPW, PAGED, FP8>;
   constexpr int NSETS = Tm::NSETS, TPS = Tm::TPS;
   Tm tm(p, smem);
   const int cells = p.N * p.KPW;  // (query, key) cells of this workgroup
@@ -381,6 +381,7 @@ __global__ __launch_bounds__(kThreads) void team_score_kernel(const TeamDev p) {
     // prefers; left alone it favours the older wave throughout, and the slab is only published
     // when the slowest wave is done with it.
     if ((slab ^ (tm.wave >> 2)) & 1) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(0);
+    tm.slab_scale(slab);
     tm.wait_tile(SLOT0);
     tm.read_queries(SLOT0);
     tm.template issue_stream<2>(slab, SLOT0);
@@ -572,6 +573,7 @@ static TeamPlan make_team_plan(const sp_score_args* a, int cus) {
   // 12K 109 / 113, 16K 126 / 135, 32K 218 / 230; head dim 64: 8K 75 / 64, 16K 86 / 84, 32K 163 / 158.
   if (a->d != 128 || a->T <= 8192) return pl;
   if (a->rope_theta != 0.f) return pl;  // un-rotated caches take the general kernels
+  if (a->k_dtype == SP_K_FP8_E4M3 && a->d_block_table) return pl;  // 8-bit caches: contiguous only here
   if (G != 1 && G != 2 && G != 4 && G != 8) return pl;
   if (G * a->N > 32) return pl;
   cus = std::min(cus, kMaxWG);
@@ -618,18 +620,22 @@ size_t team_status_offset(const sp_score_args* a) {
 
 // Every variant the dispatch below names, instantiated explicitly: left to implicit instantiation, the
 // host side of half of them (the launch stubs) was not emitted.
-template __global__ void team_score_kernel<128, 1, false, false>(const TeamDev);
-template __global__ void team_score_kernel<128, 1, false, true>(const TeamDev);
-template __global__ void team_score_kernel<128, 1, true, false>(const TeamDev);
-template __global__ void team_score_kernel<128, 1, true, true>(const TeamDev);
-template __global__ void team_score_kernel<128, 2, false, false>(const TeamDev);
-template __global__ void team_score_kernel<128, 2, false, true>(const TeamDev);
-template __global__ void team_score_kernel<128, 2, true, false>(const TeamDev);
-template __global__ void team_score_kernel<128, 2, true, true>(const TeamDev);
+template __global__ void team_score_kernel<128, 1, false, false, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 1, false, true, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 1, true, false, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 1, true, true, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, false, false, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, false, true, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, true, false, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, true, true, false>(const TeamDev);
+template __global__ void team_score_kernel<128, 1, false, false, true>(const TeamDev);  // 8-bit caches (contiguous only)
+template __global__ void team_score_kernel<128, 1, false, true, true>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, false, false, true>(const TeamDev);
+template __global__ void team_score_kernel<128, 2, false, true, true>(const TeamDev);
 
-template <int D, int TPW, bool PAGED, bool MEAN>
+template <int D, int TPW, bool PAGED, bool MEAN, bool FP8 = false>
 static sp_status launch_team(const TeamDev& dev, const TeamPlan& pl, hipStream_t stream) {
-  auto kernel = team_score_kernel<D, TPW, PAGED, MEAN>;
+  auto kernel = team_score_kernel<D, TPW, PAGED, MEAN, FP8>;
   // once per kernel and device, under a lock: allow the large dynamic LDS size and make sure the
   // whole grid can be resident at once
   static std::mutex mu;
@@ -686,6 +692,8 @@ sp_status team_score(const sp_score_args* a, hipStream_t stream) {
   dev.lg_page = 0;
   while (a->d_block_table && (1 << dev.lg_page) < a->page_size) ++dev.lg_page;
   dev.page_stride = a->k_page_stride;
+  dev.k_scale = a->d_k_scale;
+  dev.H_kv = a->H_kv;
   for (int l = 0; l < SP_MAX_LAYERS; ++l)
     dev.k[l] = l < a->L ? static_cast<const uint16_t*>(a->k_layers[l]) : nullptr;
   dev.TC = pl.TC;
@@ -714,7 +722,10 @@ sp_status team_score(const sp_score_args* a, hipStream_t stream) {
   sp_status st;
   // (head dim 128 only: make_team_plan takes nothing else)
   const bool paged = a->d_block_table != nullptr, mean = dev.by_layers != 0;
-  if (pl.TPW == 1) {
+  if (a->k_dtype == SP_K_FP8_E4M3) {
+    if (pl.TPW == 1) st = mean ? launch_team<128, 1, false, true, true>(dev, pl, stream) : launch_team<128, 1, false, false, true>(dev, pl, stream);
+    else st = mean ? launch_team<128, 2, false, true, true>(dev, pl, stream) : launch_team<128, 2, false, false, true>(dev, pl, stream);
+  } else if (pl.TPW == 1) {
     st = paged ? (mean ? launch_team<128, 1, true, true>(dev, pl, stream) : launch_team<128, 1, true, false>(dev, pl, stream))
                : (mean ? launch_team<128, 1, false, true>(dev, pl, stream) : launch_team<128, 1, false, false>(dev, pl, stream));
   } else {

@@ -47,6 +47,8 @@ struct StreamShape {
   const int32_t* block_table;    // paged cache: page numbers of the (single) prompt, else null
   int lg_page;
   int64_t page_stride;
+  const float* k_scale;          // 8-bit cache (FP8 kernels): [L][H_kv] scales of the keys, or null (all 1)
+  int H_kv;
   const uint16_t* k[SP_MAX_LAYERS];
 };
 
@@ -71,8 +73,15 @@ __device__ __forceinline__ void lds_fmax_tile(uint32_t lds_addr, const float (&x
   (lds_fmax<((I >> 2) * 8 + (I & 3) * 2) * 4>(lds_addr, x[I]), ...);
 }
 
-template <int D, int TPW, bool PAGED>
+// FP8: the keys are OCP E4M3 bytes (one byte per element, a scale per layer and KV head); the query
+// rows stay bf16.  A key row is then half as long; its 16-byte units hold 16 elements, i.e. TWO MFMA
+// k-steps, so a lane reads whole units (upper half-wave: the odd ones), widens the bytes to bf16 in
+// registers (exact), and the query operand is read in the matching order (k-step 2j + e of half-wave h
+// multiplies elements 16 (2j + h) + 8e ... + 7: any order will do as long as both operands agree).  The
+// key scale is applied to the products' sums right after the matrix instructions.
+template <int D, int TPW, bool PAGED, bool FP8 = false>
 struct StreamCore {
+  static_assert(!(PAGED && FP8), "8-bit caches behind a block table take the two-pass kernels");
   static constexpr int NSETS = 8 / TPW;        // slabs of logits alive in registers
   static constexpr int TPS = TPW + 1;          // stream tiles per slab: query tile + key tiles
   static constexpr int KS = D / 16;            // MFMA k-steps per tile
@@ -82,6 +91,11 @@ struct StreamCore {
   static constexpr int LOADS = TILE_B / 1024;  // wave-wide 16-byte loads per tile
   static constexpr int RPI = 64 / UNITS;       // rows covered by one such load
   static constexpr int RING_BYTES = kWaves * 2 * TILE_B;
+  static constexpr int ESZ = FP8 ? 1 : 2;      // bytes per key element
+  static constexpr int KROW_B = D * ESZ;       // bytes of one key; units, loads and rows per load of a key tile
+  static constexpr int KUNITS = KROW_B / 16;
+  static constexpr int KLOADS = 32 * KROW_B / 1024;
+  static constexpr int KRPI = 64 / KUNITS;
 
   const StreamShape& p;
   float* smax;           // [N][KPW + kSmaxPad] running max of log2-probabilities (cells: smax_cell)
@@ -97,6 +111,9 @@ struct StreamCore {
   uint32_t ring_lds;     // LDS byte address of this wave's two-slot ring
   uint32_t rd0;          // LDS byte address of this lane's operand unit for k-step 0 in slot 0
   uint32_t ld_off[4];    // per-lane global byte offset of key load j (depends on j & 3 only)
+  uint32_t krd0, qrd0;   // FP8: where this lane reads its key units / its query units from (ring slot 0)
+  uint32_t kunit;        // FP8: the 16-byte unit of a key row this lane fetches in every load
+  float ks;              // FP8: the key scale of the slab at hand
   bf16x8 qf[KS];
   f32x16 acc[NSETS][TPW];
   float run_m, run_s;    // running (max of raw logits, sum of 2^((x-max)*c)) of this lane's row
@@ -132,6 +149,23 @@ struct StreamCore {
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj)
       ld_off[jj] = (uint32_t)((int64_t)i * p.ts * 2) + (uint32_t)((u0 ^ ((4 * jj) & (UNITS - 1))) << 4);
+    krd0 = qrd0 = kunit = 0;
+    ks = 1.f;
+    if constexpr (FP8) {
+      // key tile: row r at r*KROW_B, unit u at position u ^ (r & (KUNITS - 1)); the lane of a wave-wide load
+      // that fills row lane / KUNITS of its KRPI rows, position lane % KUNITS, fetches that unit
+      const int ki = lane / KUNITS;
+      kunit = (uint32_t)(((lane % KUNITS) ^ (ki & (KUNITS - 1))) << 4);
+      ld_off[0] = (uint32_t)((int64_t)ki * p.ts) + kunit;
+      krd0 = ring_lds + col * KROW_B + ((half ^ (col & (KUNITS - 1))) << 4);
+      qrd0 = ring_lds + col * ROW_B + (((2 * half) ^ key) << 4);
+    }
+  }
+  // FP8: the scale of the keys of slab `slab` (this wave's KV head)
+  __device__ __forceinline__ void slab_scale(int slab) {
+    if constexpr (FP8) {
+      if (p.k_scale) ks = p.k_scale[layer_of(slab) * p.H_kv + kvh_of(slab)];
+    }
   }
 
   __device__ __forceinline__ static __attribute__((address_space(3))) void* lds_ptr(uint32_t addr) {
@@ -200,25 +234,26 @@ struct StreamCore {
     }
     const int start_eff = min(key_start, (p.M - 1) & ~31);
     const unsigned char* base = reinterpret_cast<const unsigned char*>(p.k[layer_of(slab)]) +
-                                2 * ((int64_t)kvh_of(slab) * p.hs + (int64_t)start_eff * p.ts);
+                                ESZ * ((int64_t)kvh_of(slab) * p.hs + (int64_t)start_eff * p.ts);
     if (start_eff + 32 <= p.M) {  // whole tile inside the prompt
 #pragma unroll
-      for (int j = 0; j < LOADS; ++j) {
-        uint32_t lane_off = ld_off[j & 3];
+      for (int j = 0; j < KLOADS; ++j) {
+        uint32_t lane_off = ld_off[FP8 ? 0 : (j & 3)];
         asm volatile("" : "+v"(lane_off));  // scalar row base + 32-bit lane offset; nothing 64-bit per lane to keep around
-        const unsigned char* src = base + (int64_t)(j * RPI) * p.ts * 2 + (size_t)lane_off;
+        const unsigned char* src = base + (int64_t)(j * KRPI) * p.ts * ESZ + (size_t)lane_off;
         __builtin_amdgcn_global_load_lds(src, lds_ptr(dst + j * 1024), 16, 0, 0);
       }
     } else {
       const int rows_in = p.M - start_eff;  // 1..31
       int ln = lane;
       asm volatile("" : "+v"(ln));
-      const int i = ln / UNITS;
+      const int i = ln / KUNITS;
 #pragma unroll
-      for (int j = 0; j < LOADS; ++j) {
-        const bool in = j * RPI + i < rows_in;
-        const int64_t row_off = in ? (int64_t)(j * RPI) * p.ts * 2 + (int64_t)ld_off[j & 3]
-                                   : (int64_t)(ld_off[j & 3] & (uint32_t)(ROW_B - 1));  // same unit of row 0
+      for (int j = 0; j < KLOADS; ++j) {
+        const bool in = j * KRPI + i < rows_in;
+        const uint32_t lo = ld_off[FP8 ? 0 : (j & 3)];
+        const int64_t row_off = in ? (int64_t)(j * KRPI) * p.ts * ESZ + (int64_t)lo
+                                   : (int64_t)(FP8 ? kunit : (lo & (uint32_t)(ROW_B - 1)));  // same unit of row 0
         __builtin_amdgcn_global_load_lds(base + row_off, lds_ptr(dst + j * 1024), 16, 0, 0);
       }
     }
@@ -257,7 +292,7 @@ struct StreamCore {
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     const int s = min(slab + ADV, p.n_slabs - 1);
     if (I == 0) issue_queries(s, slot); else issue_keys(s, I - 1, slot);
-    note_issued(LOADS);
+    note_issued(I == 0 ? LOADS : KLOADS);
     if (slot & 1) seq1 = issued; else seq0 = issued;
   }
   // the tile in ring slot `slot` has landed once at most the instructions issued after its
@@ -276,14 +311,53 @@ struct StreamCore {
   }
 
   __device__ __forceinline__ void read_queries(int slot) {
+    if constexpr (FP8) {  // k-step 2j + e of this half-wave: query elements 16 (2j + h) + 8e ... = unit 4j + 2h + e
+      uint32_t base = qrd0;
+      asm volatile("" : "+v"(base));
+#pragma unroll
+      for (int t = 0; t < KS; ++t)
+        qf[t] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+            lds_ptr((base ^ (uint32_t)((4 * (t >> 1) + (t & 1)) << 4)) + slot * TILE_B));
+      return;
+    }
 #pragma unroll
     for (int t = 0; t < KS; ++t) qf[t] = read_unit(t, slot);
+  }
+  // FP8: the key operand of all k-steps: unit 2j + h of the lane's key, its 16 bytes widened to bf16 (exact)
+  __device__ __forceinline__ void read_keys_fp8(bf16x8 (&kf)[KS], int slot) {
+    uint32_t base = krd0;
+    asm volatile("" : "+v"(base));
+#pragma unroll
+    for (int j = 0; j < KS / 2; ++j) {
+      const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(
+          lds_ptr((base ^ (uint32_t)((2 * j) << 4)) + slot * TILE_B));
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        u32x4 o;
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          o[2 * x] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v[2 * e + x], 1.0f, false));
+          o[2 * x + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v[2 * e + x], 1.0f, true));
+        }
+        kf[2 * j + e] = __builtin_bit_cast(bf16x8, o);
+      }
+    }
   }
 
   template <int SET>
   __device__ __forceinline__ void mfma_tile(int kb, int slot) {
     f32x16 a = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     bf16x8 kf[KS];
+    if constexpr (FP8) {
+      read_keys_fp8(kf, slot);
+#pragma unroll
+      for (int t = 0; t < KS; ++t) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], a, 0, 0, 0);
+      const float k = ks;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) a[i] *= k;
+      acc[SET][kb] = a;
+      return;
+    }
 #pragma unroll
     for (int t = 0; t < KS; ++t) kf[t] = read_unit(t, slot);
 #pragma unroll

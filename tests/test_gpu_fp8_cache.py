@@ -132,3 +132,12 @@ def test_batch_of_short_prompts_in_one_pass(shape, mode):
     _check(w, mode, False, max_seqlen=1100, exclusive_device=False)
     if shape["d"] == 128:
         _check(w, mode, False, max_seqlen=1100, paged=16)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("n_keys", [9000 + 13, 16384, 30001])
+def test_one_long_prompt_on_the_single_pass_kernel(n_keys, mode):
+    """The 8B shape with more than 8K keys and the device promised exclusive: sp_score takes the team kernel,
+    which streams the 8-bit keys once."""
+    w = synth.scaled(synth.workload(3), seqlens=(n_keys,), L=4 if n_keys < 20000 else 2)
+    _check(w, mode, False, n_valid=np.array([5], dtype=np.int32) if n_keys == 16384 else None)
