@@ -22,7 +22,7 @@ from tests import helpers as hp
 pytestmark = pytest.mark.gpu
 
 
-def _run_whole_path(w, mode, with_table=False):
+def _run_whole_path(w, mode, with_table=False, max_seqlen=0):
     import torch
     from paper_2502_02789_amd import binding as sp, device as dev
     inp = synth.make_qk(w, threads=16)
@@ -31,7 +31,7 @@ def _run_whole_path(w, mode, with_table=False):
     table = synth.make_embedding(w.vocab, w.embed_dim, w.seed, threads=16) if with_table else None
     cu = torch.from_numpy(inp["cu_seqlens"]).cuda()
     scorer = dev.Scorer(dev.bf16_from_bits(inp["q"]), [dev.bf16_from_bits(k) for k in inp["k"]], cu,
-                        H_kv=w.H_kv, scale=scale, layer_reduce=mode, want_lse=True)
+                        H_kv=w.H_kv, scale=scale, layer_reduce=mode, want_lse=True, max_seqlen=max_seqlen)
     scorer.run()
     cap = sp.sp_keep_upper_bound(list(w.seqlens), w.chunk, w.keep_rate)
     sel = dev.Selector(scorer.scores, cu, chunk=w.chunk, pool_window=w.pool_window, keep_rate=w.keep_rate,
@@ -86,6 +86,14 @@ def test_workload_2_full():
 
 def test_workload_4_ragged_batch_full_tokens():
     _run_whole_path(synth.scaled(synth.workload(4), L=4), orc.LAYER_MAX)
+
+
+@pytest.mark.parametrize("mode", [orc.LAYER_MAX, orc.LAYER_MEAN])
+def test_workload_4_ragged_batch_full_tokens_in_one_pass(mode):
+    """The same batch with its longest prompt stated, as bench.py runs it: the single-pass batch kernel
+    (eight layers: enough (sequence, layer) units for that kernel to be taken)."""
+    w = synth.scaled(synth.workload(4), L=8)
+    _run_whole_path(w, mode, max_seqlen=max(w.seqlens))
 
 
 def test_workload_5_full_tokens_and_full_embedding_table():
