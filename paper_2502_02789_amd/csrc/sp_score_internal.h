@@ -77,6 +77,9 @@ bool tiled_supported(const sp_score_args* a);
 size_t tiled_extra_workspace_bytes(const sp_score_args* a);
 sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, hipStream_t stream);
 
+// single-pass kernel for batches of short prompts with few query rows per KV head (sp_score_seq.hip)
+bool seq_supported(const sp_score_args* a);
+
 // single-pass streaming kernel (sp_score_stream.hip)
 bool stream_supported(const sp_score_args* a);
 size_t stream_workspace_bytes(const sp_score_args* a);

@@ -48,11 +48,12 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// One unit of work: sequence b for the layers [l0, l1) of layer group grp.  Units are numbered with the
-// longest sequences first (all layer groups of a sequence next to each other).
+// One unit of work: sequence b for the slabs [s0, s1) of slab group grp (slab s = KV head s % H_kv of layer
+// s / H_kv; with SP_LAYER_MEAN a group holds whole layers).  Units are numbered with the longest sequences
+// first (all groups of a sequence next to each other).
 struct SeqUnit {
   int k;  // position in this workgroup's list of units
-  int b, grp, seq0, M, nt, l0, l1;
+  int b, grp, seq0, M, nt, s0, s1;
 };
 
 // Units are dealt out to the gridDim.x workgroups in rounds, the direction changing with every round
@@ -69,11 +70,11 @@ __device__ __forceinline__ bool seq_next_unit(const TiledDev& p, int wave, int k
     const int seq0 = p.cu[b];
     const int M = p.cu[b + 1] - seq0;
     const int n_tiles = (M + kWaveKeys - 1) / kWaveKeys;
-    const int l0 = grp * p.layers_per_group;
-    const int l1 = min(p.L, l0 + p.layers_per_group);
+    const int s0 = grp * p.slabs_per_group;
+    const int s1 = min(p.L * p.H_kv, s0 + p.slabs_per_group);
     // (no keys, or more than the registers hold: nothing to do here, see seq_order_kernel and the finish kernel)
-    if (M <= 0 || n_tiles > MAXT * kTiledWaves || l0 >= l1) continue;
-    u->k = k; u->b = b; u->grp = grp; u->seq0 = seq0; u->M = M; u->l0 = l0; u->l1 = l1;
+    if (M <= 0 || n_tiles > MAXT * kTiledWaves || s0 >= s1) continue;
+    u->k = k; u->b = b; u->grp = grp; u->seq0 = seq0; u->M = M; u->s0 = s0; u->s1 = s1;
     u->nt = __builtin_amdgcn_readfirstlane((n_tiles - wave + kTiledWaves - 1) / kTiledWaves);  // this wave's tiles
     return true;
   }
@@ -95,10 +96,11 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
   // next unit: `ah` is the unit, slab and item that is requested next.
   SeqUnit ahu = cur;
   bool ah_live = true;  // false: past the last unit (the last slab is requested again, nobody consumes it)
-  int ah_l = cur.l0, ah_g = 0, ah_ph = -1;  // ph < 0: the slab's query tile, else 32-key half-tile ph of this wave
+  int ah_s = cur.s0, ah_ph = -1;  // the slab; ph < 0: its query tile, else 32-key half-tile ph of this wave
   auto issue_next = [&](int slot) __attribute__((always_inline)) {
     w.b = ahu.b;
     w.seq0 = ahu.seq0;
+    const int ah_l = ah_s / p.H_kv, ah_g = ah_s - ah_l * p.H_kv;
     if (ah_ph < 0) {
       w.template issue_queries<false>(ah_l, ah_g, slot, 0);
     } else {
@@ -108,16 +110,12 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
     }
     if (++ah_ph == 2 * ahu.nt) {
       ah_ph = -1;
-      if (++ah_g == p.H_kv) {
-        ah_g = 0;
-        if (++ah_l == ahu.l1) {
-          if (ah_live && seq_next_unit<MAXT>(p, w.wave, ahu.k + 1, &ahu)) {
-            ah_l = ahu.l0;
-          } else {
-            ah_live = false;
-            ah_l = ahu.l1 - 1;
-            ah_g = p.H_kv - 1;
-          }
+      if (++ah_s == ahu.s1) {
+        if (ah_live && seq_next_unit<MAXT>(p, w.wave, ahu.k + 1, &ahu)) {
+          ah_s = ahu.s0;
+        } else {
+          ah_live = false;
+          ah_s = ahu.s1 - 1;
         }
       }
     }
@@ -140,11 +138,9 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
       smax[t][n] = -INFINITY;
       if (MEAN) tot[MEAN ? t : 0][n] = 0.f;
     }
-  int l = cur.l0, g = 0;
-  const int n_slabs = (cur.l1 - cur.l0) * p.H_kv;
-
 #pragma unroll 1
-  for (int s = 0; s < n_slabs; ++s) {
+  for (int s = cur.s0; s < cur.s1; ++s) {
+    const int l = s / p.H_kv, g = s - l * p.H_kv;
     {
       const int slot = pos & 1;
       w.wait_tile(slot);
@@ -252,7 +248,6 @@ __global__ __launch_bounds__(kTiledThreads) void seq_score_kernel(const TiledDev
           smax[t][n] = -INFINITY;
         }
     }
-    if (++g == p.H_kv) { g = 0; ++l; }
   }
 
   // the unit's result.  (These stores are left out of the count of vector-memory instructions in
@@ -301,6 +296,48 @@ __global__ __launch_bounds__(1024) void seq_order_kernel(int B, const int32_t* _
   }
 }
 
+// Merge of the units' partial results and the average over the valid queries (Sec. 3.2.2): a workgroup takes 64
+// tokens, each of its 16 waves every sixteenth slab group (one 256-byte read per group and query), the waves'
+// results meet in LDS.  Sequences the scoring kernel left out (longer than promised) get NaN.
+constexpr int kSeqFinishParts = 16;
+__global__ __launch_bounds__(64 * kSeqFinishParts) void seq_finish_kernel(const TiledDev p) {
+  __shared__ float red[kSeqFinishParts][2][64];
+  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int64_t tok = (int64_t)blockIdx.x * 64 + lane;
+  const bool inside = tok < p.T;
+  const bool mean = p.layer_reduce != SP_LAYER_MAX;
+  float v[2] = {mean ? 0.f : -INFINITY, mean ? 0.f : -INFINITY};  // (this path has at most two queries per sequence)
+  if (inside) {
+    for (int g = part; g < p.n_groups; g += kSeqFinishParts)
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+        if (n < p.N) {
+          const float x = p.group_scores[((int64_t)g * p.N + n) * p.T + tok];
+          v[n] = mean ? v[n] + x : fmaxf(v[n], x);
+        }
+  }
+  red[part][0][lane] = v[0];
+  red[part][1][lane] = v[1];
+  __syncthreads();
+  if (part != 0 || !inside) return;
+  const int b = upper_segment(p.cu, p.B, (int)tok);
+  if (p.cu[b + 1] - p.cu[b] > p.seq_limit) {
+    p.scores[tok] = __uint_as_float(0x7FC00000u);
+    return;
+  }
+  int nv = p.n_valid ? p.n_valid[b] : p.N;
+  nv = max(1, min(nv, p.N));
+  float sum = 0.f;
+#pragma unroll
+  for (int n = 0; n < 2; ++n)
+    if (n < nv) {
+      float x = red[0][n][lane];
+      for (int q = 1; q < kSeqFinishParts; ++q) x = mean ? x + red[q][n][lane] : fmaxf(x, red[q][n][lane]);
+      sum += mean ? x : fast_exp2(x);
+    }
+  p.scores[tok] = sum / (mean ? (float)nv * (float)p.L : (float)nv);
+}
+
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
@@ -317,21 +354,30 @@ int seq_max_keys(const sp_score_args* a) {
   return R == 0 ? 0 : kWaveKeys * kTiledWaves * (R == 4 ? SeqLimits<4>::kMaxTiles : SeqLimits<8>::kMaxTiles);
 }
 
-// the cut along the layers: about kTiledTargetWGs workgroups
-void seq_grouping(const sp_score_args* a, int* layers_per_group, int* n_groups) {
-  int groups = std::min(a->L, (kTiledTargetWGs + a->B - 1) / a->B);
+// The cut along the (layer, KV head) slabs into about kTiledTargetWGs units.  With the maximum over layers a
+// group may be any run of slabs (a maximum can be completed in any order); with the mean over layers a group
+// holds whole layers (a layer's maximum over heads must be complete before it joins the sum).
+void seq_grouping(const sp_score_args* a, int* slabs_per_group, int* n_groups) {
+  const int step = a->layer_reduce == SP_LAYER_MEAN ? a->H_kv : 1;
+  const int slabs = a->L * a->H_kv;
+  int groups = std::min(slabs / step, (kTiledTargetWGs + a->B - 1) / a->B);
   groups = std::max(groups, 1);
-  *layers_per_group = (a->L + groups - 1) / groups;
-  *n_groups = (a->L + *layers_per_group - 1) / *layers_per_group;
+  int per = (slabs + groups - 1) / groups;
+  per = (per + step - 1) / step * step;
+  *slabs_per_group = per;
+  *n_groups = (slabs + per - 1) / per;
 }
+// the longest sequence the caller vouches for (one sequence: its length is the host's to see)
+static int64_t seq_stated_max(const sp_score_args* a) { return a->max_seqlen > 0 ? a->max_seqlen : (a->B == 1 ? a->T : 0); }
 
 bool seq_supported(const sp_score_args* a) {
-  if (a->rope_theta > 0.f || a->max_seqlen <= 0) return false;
+  if (a->rope_theta > 0.f || seq_stated_max(a) <= 0) return false;
   if (a->k_dtype == SP_K_FP8_E4M3 && a->d_block_table && a->page_size < (a->d == 64 ? 16 : 8)) return false;
   const int R = seq_rows(a), Gp = seq_padded_group(a);
-  if (R == 0 || a->max_seqlen > seq_max_keys(a)) return false;
+  if (R == 0 || seq_stated_max(a) > seq_max_keys(a)) return false;
   if (Gp < 4) return false;                                 // instantiated: groups of 3..8 heads
-  if ((int64_t)a->B * a->L < 512) return false;             // too few (sequence, layer) units to fill the device
+  // too few units to fill the device?
+  if ((int64_t)a->B * (a->layer_reduce == SP_LAYER_MEAN ? a->L : a->L * a->H_kv) < 256) return false;
   return true;
 }
 
@@ -394,8 +440,8 @@ static sp_status seq_by_mode(const TiledDev& dev, int R, bool mean, hipStream_t 
   return mean ? seq_by_rows<D, true, FP8>(dev, R, stream) : seq_by_rows<D, false, FP8>(dev, R, stream);
 }
 
-// `dev` as the tiled kernels fill it in, with group_scores, layers_per_group, n_groups and
-// seq_limit set for this path; the caller runs the finish kernel afterwards
+// `dev` as the tiled kernels fill it in, with group_scores, slabs_per_group, n_groups and
+// seq_limit set for this path
 sp_status seq_score(const sp_score_args* a, const TiledDev& dev_, hipStream_t stream) {
   TiledDev dev = dev_;
   int32_t* order = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(dev.group_scores) + seq_scores_bytes(a));
@@ -405,8 +451,11 @@ sp_status seq_score(const sp_score_args* a, const TiledDev& dev_, hipStream_t st
   const int R = seq_rows(a);
   const bool mean = a->layer_reduce == SP_LAYER_MEAN;
   const bool fp8 = a->k_dtype == SP_K_FP8_E4M3;
-  if (a->d == 64) return fp8 ? seq_by_mode<64, true>(dev, R, mean, stream) : seq_by_mode<64, false>(dev, R, mean, stream);
-  return fp8 ? seq_by_mode<128, true>(dev, R, mean, stream) : seq_by_mode<128, false>(dev, R, mean, stream);
+  const sp_status st = a->d == 64 ? (fp8 ? seq_by_mode<64, true>(dev, R, mean, stream) : seq_by_mode<64, false>(dev, R, mean, stream))
+                                  : (fp8 ? seq_by_mode<128, true>(dev, R, mean, stream) : seq_by_mode<128, false>(dev, R, mean, stream));
+  if (st != SP_OK) return st;
+  hipLaunchKernelGGL(seq_finish_kernel, dim3((unsigned)((dev.T + 63) / 64)), dim3(64 * kSeqFinishParts), 0, stream, dev);
+  return launch_status();
 }
 
 }  // namespace sp

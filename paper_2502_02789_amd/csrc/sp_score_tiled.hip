@@ -294,10 +294,6 @@ __global__ __launch_bounds__(256) void tiled_finish_kernel(const TiledDev p) {
   const int64_t tok = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (tok >= p.T) return;
   const int b = upper_segment(p.cu, p.B, (int)tok);
-  if (p.seq_limit > 0 && p.cu[b + 1] - p.cu[b] > p.seq_limit) {  // longer than the caller promised: not scored
-    p.scores[tok] = __uint_as_float(0x7FC00000u);
-    return;
-  }
   int nv = p.n_valid ? p.n_valid[b] : p.N;
   nv = max(1, min(nv, p.N));
   float sum = 0.f;
@@ -433,7 +429,8 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
   dev.seq_limit = 0;
   dev.seq_order = nullptr;
   if (seq_supported(a)) {  // one pass over K, a workgroup per (sequence, layer group)
-    seq_grouping(a, &dev.layers_per_group, &dev.n_groups);
+    seq_grouping(a, &dev.slabs_per_group, &dev.n_groups);
+    dev.layers_per_group = 0;
     dev.group_scores = static_cast<float*>(extra);
     dev.logits = nullptr;
     dev.keep_units = 0;
@@ -443,10 +440,7 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
     for (int l = 0; l < SP_MAX_LAYERS; ++l) dev.k[l] = gen.k[l];
     dev.rope_tiles = nullptr;
     dev.seq_limit = seq_max_keys(a);
-    const sp_status st = seq_score(a, dev, stream);
-    if (st != SP_OK) return st;
-    hipLaunchKernelGGL(tiled_finish_kernel, dim3((unsigned)((dev.T + 255) / 256)), dim3(256), 0, stream, dev);
-    return launch_status();
+    return seq_score(a, dev, stream);
   }
   const bool keep = keep_mode(a);
   dev.group_scores = keep ? nullptr : static_cast<float*>(extra);

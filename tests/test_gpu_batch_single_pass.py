@@ -104,3 +104,23 @@ def test_without_the_promise_the_two_pass_kernels_give_the_same_scores():
     a, _ = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, scale, orc.LAYER_MAX, max_seqlen=900)
     b, _ = hp.gpu_score(inp["q"], inp["k"], inp["cu_seqlens"], w.H_kv, scale, orc.LAYER_MAX)
     np.testing.assert_allclose(a, b, rtol=1e-4, atol=0)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("n_keys", [1, 777, 4097, 8192, 8193])
+def test_one_prompt_without_look_ahead(n_keys, mode):
+    """One sequence: its length is the host's to see, so no promise is needed; the (layer, KV head) slabs are
+    dealt out as units of their own (maximum over layers) or layer by layer (mean).  8193 keys are one more
+    than the registers hold: the other kernels take over."""
+    w = synth.scaled(synth.workload(3), seqlens=(n_keys,), L=4, N=1)
+    inp = synth.make_qk(w)
+    _check(w, inp, mode, max_seqlen=0, exclusive_device=True)
+    _check(w, inp, mode, max_seqlen=0, exclusive_device=False, paged=16 if n_keys == 4097 else 0)
+
+
+def test_one_prompt_two_queries_and_valid_count():
+    w = synth.scaled(synth.workload(3), seqlens=(3000,), L=4, N=2)
+    inp = synth.make_qk(w)
+    for mode in MODES:
+        _check(w, inp, mode, max_seqlen=0, n_valid=np.array([1], dtype=np.int32))
+        _check(w, inp, mode, max_seqlen=0)
