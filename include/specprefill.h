@@ -156,7 +156,8 @@ typedef struct {
   uint32_t flags;            /* SP_SCORE_* bits, 0 = none                                     */
   int32_t max_seqlen;        /* 0: nothing stated.  > 0: the caller's promise that no sequence has more
                                 prompt tokens than this (the lengths themselves live on the device, where
-                                the host side of sp_score cannot see them).  With it sp_score can take, for
+                                the host side of sp_score cannot see them; with B == 1 the length is T and
+                                nothing need be stated).  With it sp_score can take, for
                                 batches of prompts of up to 8192 keys (4096 with 5..8 query rows per KV
                                 head) whose KV heads carry at most eight query rows, a kernel that reads
                                 the K cache once and keeps all logits of a sequence on chip.  A sequence
