@@ -492,7 +492,7 @@ def main():
         other = "mean" if args.layer_reduce == "max" else "max"
         # (workload, layer reduction, also as an 8-bit cache); the last entry is the headline workload again, for
         # its 8-bit figures
-        for number, mode, fp8 in ((3, other, False), (2, "max", False), (5, "max", False), (4, "max", True),
+        for number, mode, fp8 in ((3, other, False), (2, "max", False), (5, "max", True), (4, "max", True),
                                   (3, args.layer_reduce, True)):
             m = side_measurement(number, mode, steps=20, warmup=40 if number != 4 else 10,
                                  raw_cache_too=(number == 4), fp8_too=fp8)

@@ -288,8 +288,7 @@ bool single_pass_wanted(const sp_score_args* a) {
   // on chip and needs no exchange between workgroups: measured faster than the all-workgroup kernel up to 8K
   // keys (one query, 32 layers, head dim 128; us): 2K keys 64 against 135, 4K 100 against 137.
   if (tiled_supported(a) && seq_supported(a)) return false;
-  // (an 8-bit cache: the team kernel only)
-  return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && (team_supported(a) || (a->k_dtype == SP_K_BF16 && stream_supported(a)));
+  return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && (team_supported(a) || stream_supported(a));
 }
 // where the single-pass kernel that sp_score would pick keeps its "a wait expired" word
 static size_t single_pass_status_offset(const sp_score_args* a) {

@@ -73,9 +73,9 @@ __device__ __forceinline__ uint64_t pack_stat(float m, float s) {
   return ((uint64_t)__float_as_uint(s) << 32) | __float_as_uint(m);
 }
 
-template <int D, int TPW, bool PAGED = false>
-struct Streamer : StreamCore<D, TPW, PAGED> {
-  using Core = StreamCore<D, TPW, PAGED>;
+template <int D, int TPW, bool PAGED = false, bool FP8 = false>
+struct Streamer : StreamCore<D, TPW, PAGED, FP8> {
+  using Core = StreamCore<D, TPW, PAGED, FP8>;
   using Core::NSETS; using Core::TILE_B; using Core::RING_BYTES;
   using Core::wave; using Core::lane; using Core::half; using Core::col; using Core::kvh_local;
   using Core::budget; using Core::issued; using Core::run_m; using Core::run_s;
@@ -336,10 +336,10 @@ struct Streamer : StreamCore<D, TPW, PAGED> {
   }
 };
 
-template <int D, int TPW, bool MEAN, bool PAGED>
+template <int D, int TPW, bool MEAN, bool PAGED, bool FP8>
 __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev p) {
   extern __shared__ __align__(1024) unsigned char smem[];
-  using St = Streamer<D, TPW, PAGED>;
+  using St = Streamer<D, TPW, PAGED, FP8>;
   constexpr int NSETS = St::NSETS, TPS = St::TPS;
   St st(p, smem);
   const int cells = p.N * p.KPW;  // (query, key) cells of this workgroup
@@ -394,6 +394,7 @@ __global__ __launch_bounds__(kThreads) void stream_score_kernel(const StreamDev 
     // prefers; left alone it favours the older wave throughout, and the slab is only published
     // when the slowest wave is done with it.
     if ((slab ^ (st.wave >> 2)) & 1) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(0);
+    st.slab_scale(slab);
     st.wait_tile(SLOT0);
     st.read_queries(SLOT0);
     st.template issue_stream<2>(slab, SLOT0);
@@ -529,6 +530,7 @@ static StreamPlan make_plan(const sp_score_args* a, int nwg) {
   const int G = a->H / a->H_kv;
   if (a->B != 1 || a->H_kv != 8 || a->T < 1) return pl;
   if (a->rope_theta != 0.f) return pl;  // un-rotated caches take the general kernels
+  if (a->k_dtype == SP_K_FP8_E4M3 && (a->d != 128 || a->d_block_table)) return pl;  // 8-bit caches: head dim 128, contiguous
   if (G != 1 && G != 2 && G != 4 && G != 8) return pl;
   if (G * a->N > 32 || a->N > 8) return pl;
   nwg = std::min(nwg, kMaxWG);
@@ -576,9 +578,9 @@ size_t stream_status_offset(const sp_score_args* a) {
   return pl.ok ? pl.partial_bytes + pl.lse_bytes : 0;
 }
 
-template <int D, int TPW, bool MEAN, bool PAGED = false>
+template <int D, int TPW, bool MEAN, bool PAGED = false, bool FP8 = false>
 static sp_status launch_stream(const StreamDev& dev, const StreamPlan& pl, hipStream_t stream) {
-  auto kernel = stream_score_kernel<D, TPW, MEAN, PAGED>;
+  auto kernel = stream_score_kernel<D, TPW, MEAN, PAGED, FP8>;
   // once per kernel and device, under a lock: allow the large dynamic LDS size and make sure a
   // workgroup fits on a compute unit (the grid is one workgroup per unit; the plan has already
   // bounded the LDS size by what a unit has)
@@ -634,6 +636,8 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
   dev.lg_page = 0;
   while (a->d_block_table && (1 << dev.lg_page) < a->page_size) ++dev.lg_page;
   dev.page_stride = a->k_page_stride;
+  dev.k_scale = a->d_k_scale;
+  dev.H_kv = a->H_kv;
   for (int l = 0; l < SP_MAX_LAYERS; ++l)
     dev.k[l] = l < a->L ? static_cast<const uint16_t*>(a->k_layers[l]) : nullptr;
 
@@ -643,6 +647,10 @@ sp_status stream_score(const sp_score_args* a, hipStream_t stream) {
                      n_vec, dev.status);
   if (hipGetLastError() != hipSuccess) return SP_ELAUNCH;
   const bool mean = a->layer_reduce == SP_LAYER_MEAN;
+  if (a->k_dtype == SP_K_FP8_E4M3) {  // (head dim 128, contiguous: make_plan takes nothing else)
+    if (pl.TPW == 1) return mean ? launch_stream<128, 1, true, false, true>(dev, pl, stream) : launch_stream<128, 1, false, false, true>(dev, pl, stream);
+    return mean ? launch_stream<128, 2, true, false, true>(dev, pl, stream) : launch_stream<128, 2, false, false, true>(dev, pl, stream);
+  }
   if (a->d_block_table) {
     if (a->d == 128) {
       if (pl.TPW == 1) return mean ? launch_stream<128, 1, true, true>(dev, pl, stream) : launch_stream<128, 1, false, true>(dev, pl, stream);

@@ -135,9 +135,9 @@ def test_batch_of_short_prompts_in_one_pass(shape, mode):
 
 
 @pytest.mark.parametrize("mode", MODES)
-@pytest.mark.parametrize("n_keys", [9000 + 13, 16384, 30001])
+@pytest.mark.parametrize("n_keys", [5003, 9000 + 13, 16384, 30001, 40000])
 def test_one_long_prompt_on_the_single_pass_kernel(n_keys, mode):
-    """The 8B shape with more than 8K keys and the device promised exclusive: sp_score takes the team kernel,
-    which streams the 8-bit keys once."""
+    """The 8B shape with the device promised exclusive: sp_score takes the team kernel (more than 8K and up to
+    32K keys) or the all-workgroup kernel, which stream the 8-bit keys once."""
     w = synth.scaled(synth.workload(3), seqlens=(n_keys,), L=4 if n_keys < 20000 else 2)
     _check(w, mode, False, n_valid=np.array([5], dtype=np.int32) if n_keys == 16384 else None)
