@@ -492,10 +492,10 @@ def main():
         other = "mean" if args.layer_reduce == "max" else "max"
         # (workload, layer reduction, also as an 8-bit cache); the last entry is the headline workload again, for
         # its 8-bit figures
-        for number, mode, fp8 in ((3, other, False), (2, "max", False), (5, "max", True), (4, "max", True),
+        for number, mode, fp8 in ((3, other, False), (2, "max", False), (5, "max", True), (4, "max", True), (4, other, False),
                                   (3, args.layer_reduce, True)):
             m = side_measurement(number, mode, steps=20, warmup=40 if number != 4 else 10,
-                                 raw_cache_too=(number == 4), fp8_too=fp8)
+                                 raw_cache_too=(number == 4 and fp8), fp8_too=fp8)
             if number == args.workload and mode == args.layer_reduce:
                 # the headline workload again, for its 8-bit figures only (its bf16 figures are the line's own)
                 m = {k: v for k, v in m.items() if k in ("workload", "layer_reduce", "ok") or k.startswith("fp8_")}

@@ -114,3 +114,34 @@ def test_keep_upper_bound_follows_the_chunk_ratio_rule():
     assert sp.sp_keep_upper_bound([10, 0, 5], 4, 1.0) == 15
     assert sp.sp_keep_upper_bound([10], 0, 0.3) == -1
     assert sp.sp_keep_upper_bound([10], 4, 0.0) == -1
+
+
+def test_rules_of_the_later_fields_need_no_gpu():
+    """max_seqlen, k_dtype and d_k_scale: what the header promises about them is checked on the host."""
+    lib = sp.load_library()
+    a = _fake_score_args()
+    a.max_seqlen = -1
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EINVAL
+    a = _fake_score_args()
+    a.k_dtype = 7
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EINVAL
+    assert lib.sp_score_workspace_bytes(C.byref(a)) == 0
+    a = _fake_score_args()
+    a.d_k_scale = 0x7000_3000_0000                      # scales with a bf16 cache
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EINVAL
+    a = _fake_score_args()
+    a.k_dtype = sp.SP_K_FP8_E4M3
+    a.d_k_scale = 0x7000_3000_0000
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EWORKSPACE          # acceptable apart from the workspace
+    a.k_token_stride = 1032                             # a multiple of 8, not of 16
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EALIGN
+    a.k_token_stride = 1024
+    a.rope_theta, a.d_q_pos = 10000.0, 0x7000_4000_0000
+    assert lib.sp_score(C.byref(a), None) == sp.SP_EUNSUPPORTED
+    # the workspace query follows the kernels the fields select
+    b = _fake_score_args()
+    b.B, b.N, b.T = 64, 1, 4096 * 64
+    without = lib.sp_score_workspace_bytes(C.byref(b))
+    b.max_seqlen = 4096
+    with_promise = lib.sp_score_workspace_bytes(C.byref(b))
+    assert 0 < with_promise < without                   # no kept-logits buffer once the batch kernel applies
