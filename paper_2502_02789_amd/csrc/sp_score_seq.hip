@@ -376,6 +376,7 @@ bool seq_supported(const sp_score_args* a) {
   const int R = seq_rows(a), Gp = seq_padded_group(a);
   if (R == 0 || seq_stated_max(a) > seq_max_keys(a)) return false;
   if (Gp < 4) return false;                                 // instantiated: groups of 3..8 heads
+  if (a->B > 8192) return false;                            // (the sequences are ranked by counting: quadratic in B)
   // too few units to fill the device?
   if ((int64_t)a->B * (a->layer_reduce == SP_LAYER_MEAN ? a->L : a->L * a->H_kv) < 256) return false;
   return true;

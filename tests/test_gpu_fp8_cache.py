@@ -141,3 +141,61 @@ def test_one_long_prompt_on_the_single_pass_kernel(n_keys, mode):
     32K keys) or the all-workgroup kernel, which stream the 8-bit keys once."""
     w = synth.scaled(synth.workload(3), seqlens=(n_keys,), L=4 if n_keys < 20000 else 2)
     _check(w, mode, False, n_valid=np.array([5], dtype=np.int32) if n_keys == 16384 else None)
+
+
+def test_seeded_sweep_of_batch_shapes_bf16_and_8bit_against_the_plain_kernels():
+    """Thirty seeded batches that the single-pass batch kernel takes (three to eight heads per KV head, one or two
+    queries, both head dims, both layer reductions, contiguous, head-major and paged caches, valid-row counts,
+    bf16 and 8-bit keys): sp_score with the longest prompt stated must agree with the plain two-pass kernels on
+    the same buffers, which the other tests pin to the oracle."""
+    import torch
+    from paper_2502_02789_amd import binding as sp_binding, device as dev
+    rng = np.random.default_rng(20250208)
+    for case in range(30):
+        G = int(rng.choice([3, 4, 5, 8]))
+        N = int(rng.integers(1, 3)) if G <= 4 else 1
+        H_kv = int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([64, 128]))
+        B = int(rng.integers(2, 70))
+        L = max(1, -(-256 // (B * H_kv)) + int(rng.integers(0, 3)))      # enough units for the batch kernel
+        lens = tuple(int(x) for x in rng.choice([0, 1, 31, 64, 65, 200, 513, 777, 1500, 2100], size=B))
+        if sum(lens) == 0:
+            lens = lens[:-1] + (97,)
+        mode = MODES[case % 2]
+        layout = ("contiguous", "paged", "head_major")[case % 3]
+        fp8 = case % 5 in (1, 2)
+        w = synth.scaled(synth.workload(4), seqlens=lens, L=L, N=N, H=G * H_kv, H_kv=H_kv, d=d,
+                         salient_frac=0.02, salient_run=1)
+        inp = synth.make_qk(w)
+        cu = inp["cu_seqlens"]
+        nv = None if case % 4 == 3 else rng.integers(1, N + 1, size=B).astype(np.int32)
+        what = f"case {case}: B={B} G={G} H_kv={H_kv} N={N} d={d} L={L} mode={mode} {layout} fp8={fp8}"
+        keys, k_scale = (synth.quantize_k_fp8(inp["k"]) if fp8 else (inp["k"], None))
+        kw = {}
+        if layout == "paged":
+            page = int(rng.choice([16, 32]))
+            pools, table = hp.paged_copy(keys, cu, page, seed=case, fill=0x7E if fp8 else 0x7F00)
+            ks = [torch.from_numpy(p.view(np.int16) if not fp8 else p).cuda() for p in pools]
+            kw = dict(block_table=torch.from_numpy(np.ascontiguousarray(table, dtype=np.int32)).cuda(), page_size=page,
+                      total_tokens=int(cu[-1]))
+        elif layout == "head_major":
+            ks = [torch.from_numpy(np.ascontiguousarray((k.view(np.int16) if not fp8 else k).transpose(1, 0, 2))).cuda().permute(1, 0, 2)
+                  for k in keys]
+        else:
+            ks = [torch.from_numpy(k.view(np.int16) if not fp8 else k).cuda() for k in keys]
+        if not fp8:
+            ks = [k.view(torch.bfloat16) for k in ks]
+        s = dev.Scorer(dev.bf16_from_bits(inp["q"]), ks, torch.from_numpy(np.asarray(cu, dtype=np.int32)).cuda(), H_kv=H_kv,
+                       scale=1.0 / math.sqrt(d), layer_reduce=mode, want_lse=True, exclusive_device=bool(case & 1),
+                       n_valid=None if nv is None else torch.from_numpy(nv).cuda(), max_seqlen=max(lens),
+                       k_scale=None if k_scale is None else torch.from_numpy(k_scale).cuda(), **kw)
+        s.scores.fill_(float("nan"))
+        s.run()
+        sp_binding.sp_score_check(s.args)
+        a, la = s.scores.cpu().numpy(), s.lse.cpu().numpy()
+        s.scores.fill_(float("nan"))
+        s.run(general=True)
+        torch.cuda.synchronize()
+        g, lg = s.scores.cpu().numpy(), s.lse.cpu().numpy()
+        np.testing.assert_allclose(a, g, rtol=2e-3, atol=1e-30, err_msg=what)
+        np.testing.assert_allclose(la, lg, rtol=1e-6, atol=2e-4, err_msg=what)
