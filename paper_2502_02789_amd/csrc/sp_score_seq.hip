@@ -307,7 +307,19 @@ __global__ __launch_bounds__(64 * kSeqFinishParts) void seq_finish_kernel(const 
   const bool inside = tok < p.T;
   const bool mean = p.layer_reduce != SP_LAYER_MAX;
   float v[2] = {mean ? 0.f : -INFINITY, mean ? 0.f : -INFINITY};  // (this path has at most two queries per sequence)
-  if (inside) {
+  if (inside && mean && p.groups_per_layer > 0) {
+    // mean over layers from units smaller than a layer: the groups of a layer hold the log2 of its maxima over
+    // their KV heads; the layer's maximum over all heads is their maximum, and the layers' maxima add up
+    for (int l = part; l < p.L; l += kSeqFinishParts)
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+        if (n < p.N) {
+          float m = -INFINITY;
+          for (int j = 0; j < p.groups_per_layer; ++j)
+            m = fmaxf(m, p.group_scores[((int64_t)(l * p.groups_per_layer + j) * p.N + n) * p.T + tok]);
+          v[n] += fast_exp2(m);
+        }
+  } else if (inside) {
     for (int g = part; g < p.n_groups; g += kSeqFinishParts)
 #pragma unroll
       for (int n = 0; n < 2; ++n)
@@ -357,7 +369,21 @@ int seq_max_keys(const sp_score_args* a) {
 // The cut along the (layer, KV head) slabs into about kTiledTargetWGs units.  With the maximum over layers a
 // group may be any run of slabs (a maximum can be completed in any order); with the mean over layers a group
 // holds whole layers (a layer's maximum over heads must be complete before it joins the sum).
-void seq_grouping(const sp_score_args* a, int* slabs_per_group, int* n_groups) {
+void seq_grouping(const sp_score_args* a, int* slabs_per_group, int* n_groups, int* groups_per_layer) {
+  *groups_per_layer = 0;
+  if (a->layer_reduce == SP_LAYER_MEAN && (int64_t)a->B * a->L < 256) {
+    // too few whole layers to fill the device: units of a part of a layer's KV heads (the scoring kernel then
+    // hands on maxima, as for the maximum over layers, and the merge adds the layers up)
+    int per = 1;
+    for (int cand = a->H_kv; cand >= 1; --cand)
+      if (a->H_kv % cand == 0 && (int64_t)a->B * a->L * (a->H_kv / cand) >= 256) { per = cand; break; }
+    if (per < a->H_kv) {
+      *slabs_per_group = per;
+      *groups_per_layer = a->H_kv / per;
+      *n_groups = a->L * *groups_per_layer;
+      return;
+    }
+  }
   const int step = a->layer_reduce == SP_LAYER_MEAN ? a->H_kv : 1;
   const int slabs = a->L * a->H_kv;
   int groups = std::min(slabs / step, (kTiledTargetWGs + a->B - 1) / a->B);
@@ -378,13 +404,13 @@ bool seq_supported(const sp_score_args* a) {
   if (Gp < 4) return false;                                 // instantiated: groups of 3..8 heads
   if (a->B > 8192) return false;                            // (the sequences are ranked by counting: quadratic in B)
   // too few units to fill the device?
-  if ((int64_t)a->B * (a->layer_reduce == SP_LAYER_MEAN ? a->L : a->L * a->H_kv) < 256) return false;
+  if ((int64_t)a->B * a->L * a->H_kv < 256) return false;
   return true;
 }
 
 static size_t seq_scores_bytes(const sp_score_args* a) {
-  int lpg, groups;
-  seq_grouping(a, &lpg, &groups);
+  int lpg, groups, gpl;
+  seq_grouping(a, &lpg, &groups, &gpl);
   return align_up(sizeof(float) * (size_t)groups * a->N * (size_t)a->T, 256);
 }
 
@@ -450,7 +476,8 @@ sp_status seq_score(const sp_score_args* a, const TiledDev& dev_, hipStream_t st
                      seq_max_keys(a), a->L, a->N * a->H);
   dev.seq_order = order;
   const int R = seq_rows(a);
-  const bool mean = a->layer_reduce == SP_LAYER_MEAN;
+  // (units smaller than a layer: the kernel variant that hands on maxima, whatever the layer reduction)
+  const bool mean = a->layer_reduce == SP_LAYER_MEAN && dev.groups_per_layer == 0;
   const bool fp8 = a->k_dtype == SP_K_FP8_E4M3;
   const sp_status st = a->d == 64 ? (fp8 ? seq_by_mode<64, true>(dev, R, mean, stream) : seq_by_mode<64, false>(dev, R, mean, stream))
                                   : (fp8 ? seq_by_mode<128, true>(dev, R, mean, stream) : seq_by_mode<128, false>(dev, R, mean, stream));

@@ -429,7 +429,7 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
   dev.seq_limit = 0;
   dev.seq_order = nullptr;
   if (seq_supported(a)) {  // one pass over K, a workgroup per (sequence, layer group)
-    seq_grouping(a, &dev.slabs_per_group, &dev.n_groups);
+    seq_grouping(a, &dev.slabs_per_group, &dev.n_groups, &dev.groups_per_layer);
     dev.layers_per_group = 0;
     dev.group_scores = static_cast<float*>(extra);
     dev.logits = nullptr;

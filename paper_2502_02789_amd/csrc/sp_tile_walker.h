@@ -41,6 +41,7 @@ struct TiledDev {
   float* lse_out;        // optional [L][B][N][H] natural-log row log-sum-exps (written by the single-pass batch kernel itself)
   const int32_t* seq_order;  // single-pass batch kernel: sequence numbers, longest first
   int slabs_per_group;   // single-pass batch kernel: (layer, KV head) slabs per unit (n_groups of them cover the L * H_kv slabs)
+  int groups_per_layer;  // single-pass batch kernel, mean over layers with units smaller than a layer: slab groups per layer, else 0
   int seq_limit;         // single-pass batch kernel: sequences longer than this many keys are not scored (NaN), 0 = no limit
   const int32_t* block_table;  // paged cache: [B][blocks_per_seq] page numbers, else null
   int lg_page, blocks_per_seq;
@@ -496,7 +497,7 @@ struct TileWalker {
 // single-pass kernel for batches of short prompts (sp_score_seq.hip)
 bool seq_supported(const sp_score_args* a);
 int seq_max_keys(const sp_score_args* a);
-void seq_grouping(const sp_score_args* a, int* slabs_per_group, int* n_groups);
+void seq_grouping(const sp_score_args* a, int* slabs_per_group, int* n_groups, int* groups_per_layer);
 size_t seq_workspace_bytes(const sp_score_args* a);
 sp_status seq_score(const sp_score_args* a, const TiledDev& dev, hipStream_t stream);
 
