@@ -34,12 +34,20 @@ __global__ __launch_bounds__(256) void gather_meta_kernel(const GatherDev p) {
   }
 }
 
-// one workgroup per kept row, 16 bytes per lane per step
+// one workgroup per kept row, 16 bytes per lane per step; the row's position and token id and the
+// sequences' decode positions are written here too (one launch instead of two)
 __global__ __launch_bounds__(256) void gather_rows_kernel(const GatherDev p) {
   const int64_t n_keep = min((int64_t)p.cu_keep[p.B], p.capacity);
   const int vec_per_row = p.D / 8;
+  for (int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x; b < p.B; b += (int64_t)gridDim.x * 256)
+    p.decode_pos[b] = p.cu[b + 1] - p.cu[b];
   for (int64_t s = blockIdx.x; s < n_keep; s += gridDim.x) {
-    const int64_t id = p.token_ids[p.kept_idx[s]];
+    const int idx = p.kept_idx[s];
+    const int64_t id = p.token_ids[idx];
+    if (threadIdx.x == 0) {
+      p.kept_pos[s] = idx - p.cu[upper_segment(p.cu_keep, p.B, (int)s)];
+      p.kept_ids[s] = (int32_t)id;
+    }
     const u32x4* src = p.embed + id * vec_per_row;
     u32x4* dst = p.out_embed + s * vec_per_row;
     for (int v = threadIdx.x; v < vec_per_row; v += 256) dst[v] = __builtin_nontemporal_load(src + v);
@@ -70,10 +78,11 @@ extern "C" sp_status sp_gather(const sp_gather_args* a, void* hip_stream) {
   p.out_embed = static_cast<u32x4*>(a->d_out_embed);
   const int64_t work = std::max<int64_t>(a->kept_capacity, a->B);
   const int meta_blocks = (int)std::min<int64_t>((work + 255) / 256, 4096);
-  hipLaunchKernelGGL(gather_meta_kernel, dim3(std::max(meta_blocks, 1)), dim3(256), 0, stream, p);
   if (rows && a->kept_capacity > 0) {
     const int row_blocks = (int)std::min<int64_t>(a->kept_capacity, 16384);
     hipLaunchKernelGGL(gather_rows_kernel, dim3(row_blocks), dim3(256), 0, stream, p);
+  } else {
+    hipLaunchKernelGGL(gather_meta_kernel, dim3(std::max(meta_blocks, 1)), dim3(256), 0, stream, p);
   }
   return launch_status();
 }
