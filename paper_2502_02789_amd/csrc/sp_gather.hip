@@ -101,4 +101,4 @@ extern "C" const char* sp_strerror(sp_status status) {
   return "unknown status";
 }
 
-extern "C" int32_t sp_version(void) { return 101; }
+extern "C" int32_t sp_version(void) { return 200; }
