@@ -79,8 +79,16 @@ __device__ __forceinline__ void lds_fmax_tile(uint32_t lds_addr, const float (&x
 // registers (exact), and the query operand is read in the matching order (k-step 2j + e of half-wave h
 // multiplies elements 16 (2j + h) + 8e ... + 7: any order will do as long as both operands agree).  The
 // key scale is applied to the products' sums right after the matrix instructions.
+// per-lane state only the 8-bit form has (an empty base otherwise, so the bf16 kernels carry nothing of it)
+template <bool FP8> struct Fp8Lane {};
+template <> struct Fp8Lane<true> {
+  uint32_t krd0, qrd0;   // where this lane reads its key units / its query units from (ring slot 0)
+  uint32_t kunit;        // the 16-byte unit of a key row this lane fetches in every load
+  float ks;              // the key scale of the slab at hand
+};
+
 template <int D, int TPW, bool PAGED, bool FP8 = false>
-struct StreamCore {
+struct StreamCore : Fp8Lane<FP8> {
   static_assert(!(PAGED && FP8), "8-bit caches behind a block table take the two-pass kernels");
   static constexpr int NSETS = 8 / TPW;        // slabs of logits alive in registers
   static constexpr int TPS = TPW + 1;          // stream tiles per slab: query tile + key tiles
@@ -111,9 +119,6 @@ struct StreamCore {
   uint32_t ring_lds;     // LDS byte address of this wave's two-slot ring
   uint32_t rd0;          // LDS byte address of this lane's operand unit for k-step 0 in slot 0
   uint32_t ld_off[4];    // per-lane global byte offset of key load j (depends on j & 3 only)
-  uint32_t krd0, qrd0;   // FP8: where this lane reads its key units / its query units from (ring slot 0)
-  uint32_t kunit;        // FP8: the 16-byte unit of a key row this lane fetches in every load
-  float ks;              // FP8: the key scale of the slab at hand
   bf16x8 qf[KS];
   f32x16 acc[NSETS][TPW];
   float run_m, run_s;    // running (max of raw logits, sum of 2^((x-max)*c)) of this lane's row
@@ -149,22 +154,24 @@ struct StreamCore {
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj)
       ld_off[jj] = (uint32_t)((int64_t)i * p.ts * 2) + (uint32_t)((u0 ^ ((4 * jj) & (UNITS - 1))) << 4);
-    krd0 = qrd0 = kunit = 0;
-    ks = 1.f;
     if constexpr (FP8) {
+      this->ks = 1.f;
       // key tile: row r at r*KROW_B, unit u at position u ^ (r & (KUNITS - 1)); the lane of a wave-wide load
       // that fills row lane / KUNITS of its KRPI rows, position lane % KUNITS, fetches that unit
       const int ki = lane / KUNITS;
-      kunit = (uint32_t)(((lane % KUNITS) ^ (ki & (KUNITS - 1))) << 4);
-      ld_off[0] = (uint32_t)((int64_t)ki * p.ts) + kunit;
-      krd0 = ring_lds + col * KROW_B + ((half ^ (col & (KUNITS - 1))) << 4);
-      qrd0 = ring_lds + col * ROW_B + (((2 * half) ^ key) << 4);
+      this->kunit = (uint32_t)(((lane % KUNITS) ^ (ki & (KUNITS - 1))) << 4);
+      ld_off[0] = (uint32_t)((int64_t)ki * p.ts) + this->kunit;
+      this->krd0 = ring_lds + col * KROW_B + ((half ^ (col & (KUNITS - 1))) << 4);
+      this->qrd0 = ring_lds + col * ROW_B + (((2 * half) ^ key) << 4);
     }
+  }
+  __device__ __forceinline__ uint32_t fallback_unit(uint32_t lo) const {
+    if constexpr (FP8) return this->kunit; else return lo & (uint32_t)(ROW_B - 1);
   }
   // FP8: the scale of the keys of slab `slab` (this wave's KV head)
   __device__ __forceinline__ void slab_scale(int slab) {
     if constexpr (FP8) {
-      if (p.k_scale) ks = p.k_scale[layer_of(slab) * p.H_kv + kvh_of(slab)];
+      if (p.k_scale) this->ks = p.k_scale[layer_of(slab) * p.H_kv + kvh_of(slab)];
     }
   }
 
@@ -253,7 +260,7 @@ struct StreamCore {
         const bool in = j * KRPI + i < rows_in;
         const uint32_t lo = ld_off[FP8 ? 0 : (j & 3)];
         const int64_t row_off = in ? (int64_t)(j * KRPI) * p.ts * ESZ + (int64_t)lo
-                                   : (int64_t)(FP8 ? kunit : (lo & (uint32_t)(ROW_B - 1)));  // same unit of row 0
+                                   : (int64_t)fallback_unit(lo);  // same unit of row 0
         __builtin_amdgcn_global_load_lds(base + row_off, lds_ptr(dst + j * 1024), 16, 0, 0);
       }
     }
@@ -312,7 +319,8 @@ struct StreamCore {
 
   __device__ __forceinline__ void read_queries(int slot) {
     if constexpr (FP8) {  // k-step 2j + e of this half-wave: query elements 16 (2j + h) + 8e ... = unit 4j + 2h + e
-      uint32_t base = qrd0;
+      uint32_t base = 0;
+      if constexpr (FP8) base = this->qrd0;
       asm volatile("" : "+v"(base));
 #pragma unroll
       for (int t = 0; t < KS; ++t)
@@ -325,7 +333,8 @@ struct StreamCore {
   }
   // FP8: the key operand of all k-steps: unit 2j + h of the lane's key, its 16 bytes widened to bf16 (exact)
   __device__ __forceinline__ void read_keys_fp8(bf16x8 (&kf)[KS], int slot) {
-    uint32_t base = krd0;
+    uint32_t base = 0;
+    if constexpr (FP8) base = this->krd0;
     asm volatile("" : "+v"(base));
 #pragma unroll
     for (int j = 0; j < KS / 2; ++j) {
@@ -352,7 +361,8 @@ struct StreamCore {
       read_keys_fp8(kf, slot);
 #pragma unroll
       for (int t = 0; t < KS; ++t) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], a, 0, 0, 0);
-      const float k = ks;
+      float k = 1.f;
+      if constexpr (FP8) k = this->ks;
 #pragma unroll
       for (int i = 0; i < 16; ++i) a[i] *= k;
       acc[SET][kb] = a;
