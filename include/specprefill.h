@@ -161,8 +161,9 @@ typedef struct {
                                 batches of prompts of up to 8192 keys (4096 with 5..8 query rows per KV
                                 head) whose KV heads carry at most eight query rows, a kernel that reads
                                 the K cache once and keeps all logits of a sequence on chip.  A sequence
-                                longer than promised is not scored: all of its scores are NaN (which
-                                sp_pool_select reports in band), never silently wrong.                  */
+                                longer than promised is not scored: all of its scores (and its rows of
+                                d_lse) are NaN, which sp_pool_select reports in band; never silently
+                                wrong.  Nothing else depends on the promise.                            */
   int32_t k_dtype;           /* sp_k_dtype, 0 = bf16.  With SP_K_FP8_E4M3 the layers hold bytes: the strides
                                 (token, head, page) still count ELEMENTS and must then be multiples of 16;
                                 rope_theta must be 0 (SP_EUNSUPPORTED otherwise), and sp_score runs its
