@@ -2,9 +2,9 @@
 
 Workload 3 (the one bench.py times) runs in full -- every layer, every token -- against
 the full fp64 oracle, through the same entry points and launch configuration as the
-benchmark.  Workloads 2, 4 and 5 keep their full token axis, batch structure, head layout
-and (for 5) the full 128256 x 8192 embedding table, with the layer count cut to keep the
-oracle within seconds; the kernels' tiling over tokens is the same as at full depth.
+benchmark.  Workloads 4 and 5 run in full as well (one layer reduction each); their other
+cases keep the full token axis, batch structure, head layout and (for 5) the full
+128256 x 8192 embedding table with the layer count cut to keep the oracle within seconds.
 
 End-to-end selection (GPU scores -> GPU selection vs oracle scores -> oracle selection):
 any chunk kept by one side only must lie within the score tolerance (2e-3 relative) of the
@@ -94,6 +94,22 @@ def test_workload_4_ragged_batch_full_tokens_in_one_pass(mode):
     (eight layers: enough (sequence, layer) units for that kernel to be taken)."""
     w = synth.scaled(synth.workload(4), L=8)
     _run_whole_path(w, mode, max_seqlen=max(w.seqlens))
+
+
+def test_workload_4_full_depth_in_one_pass():
+    """All 32 layers of the 64-prompt workload, exactly what bench.py times on it, against the oracle."""
+    w = synth.workload(4)
+    _run_whole_path(w, orc.LAYER_MAX, max_seqlen=max(w.seqlens))
+
+
+def test_workload_4_full_depth_logits_kept_between_two_passes():
+    """The same without the longest prompt stated: the MFMA pass that keeps the logits and the pass over those."""
+    _run_whole_path(synth.workload(4), orc.LAYER_MEAN)
+
+
+def test_workload_5_full_depth():
+    """All 32 layers of the 128K-token workload (the embedding rows are covered by the four-layer test below)."""
+    _run_whole_path(synth.workload(5), orc.LAYER_MAX)
 
 
 def test_workload_5_full_tokens_and_full_embedding_table():
