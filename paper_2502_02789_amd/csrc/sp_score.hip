@@ -286,7 +286,7 @@ static int general_max_tiles(const sp_score_args* a) { return (int)(a->T / kTile
 bool single_pass_wanted(const sp_score_args* a) {
   // Few query rows per KV head and a prompt short enough for the batch kernel, which keeps a sequence's logits
   // on chip and needs no exchange between workgroups: measured faster than the all-workgroup kernel up to 8K
-  // keys (one query, 32 layers, head dim 128; us): 2K keys 64 against 135, 4K 100 against 137.
+  // keys (one query, 32 layers, head dim 128; us): 2K keys 38 against 135, 4K 57 against 137, 8K 127 against 159.
   if (tiled_supported(a) && seq_supported(a)) return false;
   return (a->flags & SP_SCORE_EXCLUSIVE_DEVICE) != 0 && (team_supported(a) || stream_supported(a));
 }
@@ -348,7 +348,9 @@ sp_status general_score(const sp_score_args* a, hipStream_t stream, bool allow_m
     p.q = q_rot;
   }
 
-  hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(1024), 0, stream, p.B, p.cu, p.tile_cu);
+  // (the single-pass batch kernel does not look at the tile table)
+  if (!(allow_mfma && tiled_supported(a) && seq_supported(a)))
+    hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(1024), 0, stream, p.B, p.cu, p.tile_cu);
   if (allow_mfma && tiled_supported(a)) {
     const sp_status st = tiled_score(a, p, ws, stream);
     clear_stream_status(a, stream);

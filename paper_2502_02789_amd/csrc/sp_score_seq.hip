@@ -66,7 +66,7 @@ __device__ __forceinline__ bool seq_next_unit(const TiledDev& p, int wave, int k
     const int idx = k * W + ((k & 1) ? W - 1 - (int)blockIdx.x : (int)blockIdx.x);
     if (idx >= n_units) return false;
     const int grp = idx % p.n_groups;
-    const int b = p.seq_order[idx / p.n_groups];
+    const int b = p.seq_order ? p.seq_order[idx / p.n_groups] : idx / p.n_groups;  // (no table: batch order)
     const int seq0 = p.cu[b];
     const int M = p.cu[b + 1] - seq0;
     const int n_tiles = (M + kWaveKeys - 1) / kWaveKeys;
@@ -394,7 +394,7 @@ void seq_grouping(const sp_score_args* a, int* slabs_per_group, int* n_groups, i
   *n_groups = (slabs + per - 1) / per;
 }
 // the longest sequence the caller vouches for (one sequence: its length is the host's to see)
-static int64_t seq_stated_max(const sp_score_args* a) { return a->max_seqlen > 0 ? a->max_seqlen : (a->B == 1 ? a->T : 0); }
+static int64_t seq_stated_max(const sp_score_args* a) { return a->B == 1 ? a->T : a->max_seqlen; }
 
 bool seq_supported(const sp_score_args* a) {
   if (a->rope_theta > 0.f || seq_stated_max(a) <= 0) return false;
@@ -471,10 +471,13 @@ static sp_status seq_by_mode(const TiledDev& dev, int R, bool mean, hipStream_t 
 // seq_limit set for this path
 sp_status seq_score(const sp_score_args* a, const TiledDev& dev_, hipStream_t stream) {
   TiledDev dev = dev_;
-  int32_t* order = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(dev.group_scores) + seq_scores_bytes(a));
-  hipLaunchKernelGGL(seq_order_kernel, dim3(1), dim3(1024), 0, stream, a->B, a->d_cu_seqlens, order, a->d_lse,
-                     seq_max_keys(a), a->L, a->N * a->H);
-  dev.seq_order = order;
+  dev.seq_order = nullptr;
+  if (a->B > 1) {  // (one sequence: nothing to order, and the host has seen that its length fits)
+    int32_t* order = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(dev.group_scores) + seq_scores_bytes(a));
+    hipLaunchKernelGGL(seq_order_kernel, dim3(1), dim3(1024), 0, stream, a->B, a->d_cu_seqlens, order, a->d_lse,
+                       seq_max_keys(a), a->L, a->N * a->H);
+    dev.seq_order = order;
+  }
   const int R = seq_rows(a);
   // (units smaller than a layer: the kernel variant that hands on maxima, whatever the layer reduction)
   const bool mean = a->layer_reduce == SP_LAYER_MEAN && dev.groups_per_layer == 0;
