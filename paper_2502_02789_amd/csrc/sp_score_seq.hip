@@ -1,12 +1,12 @@
 // Single-pass MFMA scorer for batches of short prompts whose KV heads carry few query rows (the
-// paper's variants without look-ahead, Sec. 4.3, served many prompts at a time).
+// paper's variants without look-ahead, Sec. 4.3): many prompts at a time, or one prompt of a few thousand tokens.
 //
 // Same quantity as the other scoring kernels: row softmax of the stored queries against the
 // prompt keys (Sec. 3.2 equation of arXiv 2502.02789), max over heads, max/mean over layers,
 // mean over queries (Sec. 3.2.2).  The K cache is read ONCE and no logit ever leaves the chip:
 //
-//   * The work is cut into units (one whole sequence, one group of layers), numbered with the
-//     longest sequences first, and dealt out to one workgroup per compute unit in rounds whose
+//   * The work is cut into units (one whole sequence, one run of (layer, KV head) slabs), numbered with
+//     the longest sequences first, and dealt out to one workgroup per compute unit in rounds whose
 //     direction alternates: every workgroup gets nearly the same number of keys without any shared
 //     counter, and nobody ever waits for another workgroup.
 //   * A workgroup walks over the (layer, KV head) slabs of its unit.  Inside a slab its eight waves
@@ -24,12 +24,12 @@
 //   * The stream of tiles never stops, neither at a slab's end nor between units: the loads run two
 //     tiles ahead of the arithmetic straight into the next slab or unit, and the barrier is a bare
 //     s_barrier (no vector-memory wait in front of it).
-//   * Each unit writes its [N][M] partial result; the tiled kernels' finish kernel merges the
-//     layer groups and averages over the valid queries.
+//   * Each unit writes its [N][M] partial result; seq_finish_kernel merges the units of a sequence and
+//     averages over the valid queries.
 //
 // A sequence must fit the registers: 64 * 8 * SeqLimits<R>::kMaxTiles keys.  The host cannot see the
-// sequence lengths (they live on the device), so this path is taken only on the caller's promise
-// sp_score_args.max_seqlen; a sequence that breaks the promise gets NaN scores (finish kernel).
+// sequence lengths of a batch (they live on the device), so for B > 1 this path is taken only on the caller's
+// promise sp_score_args.max_seqlen; a sequence that breaks the promise gets NaN scores (seq_finish_kernel).
 #include <mutex>
 
 #include "sp_tile_walker.h"
@@ -72,7 +72,7 @@ __device__ __forceinline__ bool seq_next_unit(const TiledDev& p, int wave, int k
     const int n_tiles = (M + kWaveKeys - 1) / kWaveKeys;
     const int s0 = grp * p.slabs_per_group;
     const int s1 = min(p.L * p.H_kv, s0 + p.slabs_per_group);
-    // (no keys, or more than the registers hold: nothing to do here, see seq_order_kernel and the finish kernel)
+    // (no keys, or more than the registers hold: nothing to do here, see seq_order_kernel and seq_finish_kernel)
     if (M <= 0 || n_tiles > MAXT * kTiledWaves || s0 >= s1) continue;
     u->k = k; u->b = b; u->grp = grp; u->seq0 = seq0; u->M = M; u->s0 = s0; u->s1 = s1;
     u->nt = __builtin_amdgcn_readfirstlane((n_tiles - wave + kTiledWaves - 1) / kTiledWaves);  // this wave's tiles
