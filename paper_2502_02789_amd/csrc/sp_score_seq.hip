@@ -353,9 +353,12 @@ __global__ __launch_bounds__(64 * kSeqFinishParts) void seq_finish_kernel(const 
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
+// heads per KV head as this path lays them out: padded to four or eight (columns of padding heads repeat head
+// 0, which changes neither a maximum nor a row's own statistics; one or two heads per KV head are padded to four
+// as well, so that the same kernel variants serve them)
 static int seq_padded_group(const sp_score_args* a) {
   const int G = a->H / a->H_kv;
-  return G <= 2 ? G : G <= 4 ? 4 : 8;
+  return G <= 4 ? 4 : 8;
 }
 static int seq_rows(const sp_score_args* a) {  // held rows per key: 4 or 8 (0: too many)
   const int rows = seq_padded_group(a) * a->N;
@@ -399,9 +402,8 @@ static int64_t seq_stated_max(const sp_score_args* a) { return a->B == 1 ? a->T 
 bool seq_supported(const sp_score_args* a) {
   if (a->rope_theta > 0.f || seq_stated_max(a) <= 0) return false;
   if (a->k_dtype == SP_K_FP8_E4M3 && a->d_block_table && a->page_size < (a->d == 64 ? 16 : 8)) return false;
-  const int R = seq_rows(a), Gp = seq_padded_group(a);
+  const int R = seq_rows(a);
   if (R == 0 || seq_stated_max(a) > seq_max_keys(a)) return false;
-  if (Gp < 4) return false;                                 // instantiated: groups of 3..8 heads
   if (a->B > 8192) return false;                            // (the sequences are ranked by counting: quadratic in B)
   // too few units to fill the device?
   if ((int64_t)a->B * a->L * a->H_kv < 256) return false;

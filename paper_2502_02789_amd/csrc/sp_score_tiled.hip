@@ -430,6 +430,7 @@ sp_status tiled_score(const sp_score_args* a, const ScoreDev& gen, void* extra, 
   dev.seq_order = nullptr;
   if (seq_supported(a)) {  // one pass over K, a workgroup per (sequence, layer group)
     seq_grouping(a, &dev.slabs_per_group, &dev.n_groups, &dev.groups_per_layer);
+    if (dev.lgG < 2) { dev.lgG = 2; dev.Gp = 4; }  // (one or two heads per KV head: padded to four on this path)
     dev.layers_per_group = 0;
     dev.group_scores = static_cast<float*>(extra);
     dev.logits = nullptr;

@@ -45,6 +45,8 @@ def _check(w, inp, mode, max_seqlen, n_valid=None, paged=0, exclusive_device=Fal
     dict(H=16, H_kv=2, N=1, d=64),      # eight heads per KV head
     dict(H=6, H_kv=2, N=1, d=64),       # three heads, padded to four
     dict(H=10, H_kv=2, N=1, d=128),     # five heads, padded to eight
+    dict(H=4, H_kv=4, N=2, d=64),       # one head per KV head (padded to four), two queries
+    dict(H=4, H_kv=2, N=1, d=128),      # two heads per KV head (padded to four)
 ])
 def test_batch_of_short_prompts(shape, mode):
     w = synth.scaled(synth.workload(4), seqlens=LENS_64, L=8, salient_frac=0.02, salient_run=1, **shape)
