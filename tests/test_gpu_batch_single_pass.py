@@ -126,3 +126,43 @@ def test_one_prompt_two_queries_and_valid_count():
     for mode in MODES:
         _check(w, inp, mode, max_seqlen=0, n_valid=np.array([1], dtype=np.int32))
         _check(w, inp, mode, max_seqlen=0)
+
+
+def test_batch_step_replays_from_a_hip_graph():
+    """The batch path only enqueues kernels (ordering, scoring, merge; then selection and gather): captured once
+    and replayed three times, with eager work and synchronisations in between, it must reproduce the eager
+    result bit for bit."""
+    import torch
+    from paper_2502_02789_amd import device as dev
+    w = synth.scaled(synth.workload(4), seqlens=_lens(12, 64, 1, 1200), L=8, H=8, H_kv=2)
+    inp = synth.make_qk(w)
+    cu = torch.from_numpy(inp["cu_seqlens"]).cuda()
+    scorer = dev.Scorer(dev.bf16_from_bits(inp["q"]), [dev.bf16_from_bits(k) for k in inp["k"]], cu, H_kv=w.H_kv,
+                        scale=1.0 / math.sqrt(w.d), max_seqlen=1200, exclusive_device=False)
+    sel = dev.Selector(scorer.scores, cu, chunk=w.chunk, pool_window=w.pool_window, keep_rate=w.keep_rate)
+    gat = dev.Gatherer(sel)
+
+    def step():
+        scorer.run()
+        sel.run()
+        gat.run()
+
+    step()                                  # eager: also does the one-time kernel set-up
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (scorer.scores, sel.kept_idx, sel.cu_keep, gat.kept_pos)]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in (scorer.scores, sel.kept_idx, gat.kept_pos):
+            t.fill_(-3)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        n = int(sel.cu_keep[-1])
+        got = (scorer.scores, sel.kept_idx[:n], sel.cu_keep, gat.kept_pos[:n])
+        for a, b in zip(got, (want[0], want[1][:n], want[2], want[3][:n])):
+            assert torch.equal(a, b), f"replay {replay}"
