@@ -369,7 +369,7 @@ int seq_max_keys(const sp_score_args* a) {
   return R == 0 ? 0 : kWaveKeys * kTiledWaves * (R == 4 ? SeqLimits<4>::kMaxTiles : SeqLimits<8>::kMaxTiles);
 }
 
-// The cut along the (layer, KV head) slabs into about kTiledTargetWGs units.  With the maximum over layers a
+// The cut along the (layer, KV head) slabs into units.  With the maximum over layers a
 // group may be any run of slabs (a maximum can be completed in any order); with the mean over layers a group
 // holds whole layers (a layer's maximum over heads must be complete before it joins the sum).
 void seq_grouping(const sp_score_args* a, int* slabs_per_group, int* n_groups, int* groups_per_layer) {
@@ -389,7 +389,13 @@ void seq_grouping(const sp_score_args* a, int* slabs_per_group, int* n_groups, i
   }
   const int step = a->layer_reduce == SP_LAYER_MEAN ? a->H_kv : 1;
   const int slabs = a->L * a->H_kv;
-  int groups = std::min(slabs / step, (kTiledTargetWGs + a->B - 1) / a->B);
+  // Units per workgroup (of 256): a unit's end costs several microseconds (its results go out, the next unit's
+  // table entries come in), so few large units are better as long as the workgroups' shares stay even, which
+  // takes more units the more sequences of different lengths there are.  Measured best (32 layers, 8 KV
+  // heads, prompts of 1K to 4K keys): 2 per workgroup for 16 prompts, 2 to 4 for 64, 8 for 256.
+  const int per_wg = std::min(8, std::max(2, a->B / 32));
+  const int target = 256 * per_wg;
+  int groups = std::min(slabs / step, (target + a->B - 1) / a->B);
   groups = std::max(groups, 1);
   int per = (slabs + groups - 1) / groups;
   per = (per + step - 1) / step * step;
