@@ -235,7 +235,7 @@ struct StreamCore : Fp8Lane<FP8> {
         uint32_t lane_off = ld_off[j & 3];
         asm volatile("" : "+v"(lane_off));
         if (j * RPI + i >= rows) lane_off -= row_part;  // this lane's row is beyond the prompt: the load's first row instead
-        __builtin_amdgcn_global_load_lds(base + (size_t)lane_off, lds_ptr(dst + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(base + (size_t)lane_off, lds_ptr(dst + j * 1024), 16, 0, kKeyLoadPolicy);
       }
       return;
     }
@@ -248,7 +248,7 @@ struct StreamCore : Fp8Lane<FP8> {
         uint32_t lane_off = ld_off[FP8 ? 0 : (j & 3)];
         asm volatile("" : "+v"(lane_off));  // scalar row base + 32-bit lane offset; nothing 64-bit per lane to keep around
         const unsigned char* src = base + (int64_t)(j * KRPI) * p.ts * ESZ + (size_t)lane_off;
-        __builtin_amdgcn_global_load_lds(src, lds_ptr(dst + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(src, lds_ptr(dst + j * 1024), 16, 0, kKeyLoadPolicy);
       }
     } else {
       const int rows_in = p.M - start_eff;  // 1..31
@@ -261,7 +261,7 @@ struct StreamCore : Fp8Lane<FP8> {
         const uint32_t lo = ld_off[FP8 ? 0 : (j & 3)];
         const int64_t row_off = in ? (int64_t)(j * KRPI) * p.ts * ESZ + (int64_t)lo
                                    : (int64_t)fallback_unit(lo);  // same unit of row 0
-        __builtin_amdgcn_global_load_lds(base + row_off, lds_ptr(dst + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(base + row_off, lds_ptr(dst + j * 1024), 16, 0, kKeyLoadPolicy);
       }
     }
   }

@@ -238,7 +238,7 @@ struct TileWalker {
         uint32_t lane_off = ld_off[FP8 ? 0 : (j & 3)];
         asm volatile("" : "+v"(lane_off));
         __builtin_amdgcn_global_load_lds(base + (int64_t)(j * KRPI) * p.ts * ESZ + (size_t)lane_off, lds_ptr(dst + j * 1024),
-                                         16, 0, 0);
+                                         16, 0, kKeyLoadPolicy);
       }
     } else {
       int ln = lane;
@@ -249,7 +249,7 @@ struct TileWalker {
         const int r = j * KRPI + i;
         const int64_t row_off = r < rows ? (int64_t)r * p.ts * ESZ : 0;
         const uint32_t unit = FP8 ? u0 : (u0 ^ ((4 * j) & (UNITS - 1)));
-        __builtin_amdgcn_global_load_lds(base + row_off + (unit << 4), lds_ptr(dst + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(base + row_off + (unit << 4), lds_ptr(dst + j * 1024), 16, 0, kKeyLoadPolicy);
       }
     }
     note_issued(KLOADS);
@@ -278,7 +278,7 @@ struct TileWalker {
         base += (int64_t)KRPI * p.ts * ESZ;
       const int64_t row_off = (j * KRPI + i < rows) ? (int64_t)i * p.ts * ESZ : 0;
       const uint32_t unit = FP8 ? u0 : (u0 ^ ((4 * j) & (UNITS - 1)));
-      __builtin_amdgcn_global_load_lds(base + row_off + (unit << 4), lds_ptr(dst + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(base + row_off + (unit << 4), lds_ptr(dst + j * 1024), 16, 0, kKeyLoadPolicy);
     }
   }
 
