@@ -30,7 +30,7 @@ SP_PROBE_API int sp_probe_read(const void* const* h_layers, int32_t L, size_t by
 
 /* The single-pass scorer's own access pattern without its arithmetic: one persistent workgroup
  * of eight waves per compute unit (256 of them), every wave pulling 32-key x d tiles of ONE KV
- * head (256-byte pieces, k_token_stride apart) through a two-slot LDS ring with direct
+ * head (256-byte pieces, k_token_stride apart) through a two-slot LDS ring with direct, non-temporal
  * global->LDS loads, layer by layer, four teams of 64 workgroups on two KV heads each -- the order in
  * which the team kernel of sp_score walks a 32K-token, 8-KV-head, head-dim-128 cache.
  * Only that shape is accepted: T = 32768, H_kv = 8, d = 128 (else -1). */

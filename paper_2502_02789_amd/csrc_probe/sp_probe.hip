@@ -53,7 +53,7 @@ __global__ __launch_bounds__(512) void tiled_kernel(const Layers layers, int L, 
     const unsigned char* src = layers.p[layer] + kvh * hs_bytes + (int64_t)(((wave * 2 + kb) * 64 + j) * 32) * ts_bytes + lane_off;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      __builtin_amdgcn_global_load_lds(src + (int64_t)(4 * i) * ts_bytes, lds_ptr(ring + slot * kTile + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(src + (int64_t)(4 * i) * ts_bytes, lds_ptr(ring + slot * kTile + i * 1024), 16, 0, /*nt, as the scorer's key loads*/ 2);
   };
   u32x4 acc = {0, 0, 0, 0};
   issue(0, 0);
