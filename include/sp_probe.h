@@ -37,6 +37,12 @@ SP_PROBE_API int sp_probe_read(const void* const* h_layers, int32_t L, size_t by
 SP_PROBE_API int sp_probe_tiled(const void* const* h_layers, int32_t L, int32_t T, int32_t H_kv, int32_t d,
                                 int64_t k_token_stride, int64_t k_head_stride, void* d_sink, void* hip_stream);
 
+/* The same read with the loads' default cache policy instead of the non-temporal one: the difference between
+ * the two is what the policy of the scorer's key loads is worth on this device.  Same arguments and errors. */
+SP_PROBE_API int sp_probe_tiled_default_policy(const void* const* h_layers, int32_t L, int32_t T, int32_t H_kv, int32_t d,
+                                               int64_t k_token_stride, int64_t k_head_stride, void* d_sink,
+                                               void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

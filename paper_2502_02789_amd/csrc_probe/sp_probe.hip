@@ -39,9 +39,10 @@ constexpr int kTile = 32 * 256;  // 32 keys x 128 bf16
 // 2t + s) slabs; the prompt's 32-key tiles are dealt out to the 64 workgroups of a team in turn: wave
 // w of workgroup j reads tiles (2w + kb) * 64 + j, kb = 0, 1, of the slab, 8 KiB each, as 8 wave-wide
 // loads of 4 keys x 256 bytes.
-__global__ __launch_bounds__(512) void tiled_kernel(const Layers layers, int L, int64_t ts_bytes, int64_t hs_bytes,
-                                                    unsigned* sink) {
-  extern __shared__ __align__(1024) unsigned char smem[];
+// POLICY: cache-policy bits of the loads (0 = default, 2 = non-temporal, what the scorer's key loads use).
+template <int POLICY>
+__device__ __forceinline__ void tiled_body(const Layers& layers, int L, int64_t ts_bytes, int64_t hs_bytes, unsigned* sink,
+                                           unsigned char* smem) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int team = blockIdx.x & 3, j = blockIdx.x >> 2;
   const uint32_t ring = (uint32_t)reinterpret_cast<uintptr_t>(smem) + wave * 2 * kTile;
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(512) void tiled_kernel(const Layers layers, int L, 
     const unsigned char* src = layers.p[layer] + kvh * hs_bytes + (int64_t)(((wave * 2 + kb) * 64 + j) * 32) * ts_bytes + lane_off;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      __builtin_amdgcn_global_load_lds(src + (int64_t)(4 * i) * ts_bytes, lds_ptr(ring + slot * kTile + i * 1024), 16, 0, /*nt, as the scorer's key loads*/ 2);
+      __builtin_amdgcn_global_load_lds(src + (int64_t)(4 * i) * ts_bytes, lds_ptr(ring + slot * kTile + i * 1024), 16, 0, POLICY);
   };
   u32x4 acc = {0, 0, 0, 0};
   issue(0, 0);
@@ -67,6 +68,16 @@ __global__ __launch_bounds__(512) void tiled_kernel(const Layers layers, int L, 
   }
   const unsigned r = acc.x ^ acc.y ^ acc.z ^ acc.w;
   if (r == 0x9e3779b9u) sink[lane] = r;
+}
+
+extern __shared__ __align__(1024) unsigned char tile_ring[];
+__global__ __launch_bounds__(512) void tiled_kernel(const Layers layers, int L, int64_t ts_bytes, int64_t hs_bytes,
+                                                    unsigned* sink) {
+  tiled_body<2>(layers, L, ts_bytes, hs_bytes, sink, tile_ring);
+}
+__global__ __launch_bounds__(512) void tiled_default_policy_kernel(const Layers layers, int L, int64_t ts_bytes,
+                                                                   int64_t hs_bytes, unsigned* sink) {
+  tiled_body<0>(layers, L, ts_bytes, hs_bytes, sink, tile_ring);
 }
 
 }  // namespace
@@ -84,8 +95,10 @@ extern "C" int sp_probe_read(const void* const* h_layers, int32_t L, size_t byte
   return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-extern "C" int sp_probe_tiled(const void* const* h_layers, int32_t L, int32_t T, int32_t H_kv, int32_t d,
-                              int64_t k_token_stride, int64_t k_head_stride, void* d_sink, void* hip_stream) {
+typedef void (*tiled_kernel_t)(const Layers, int, int64_t, int64_t, unsigned*);
+
+static int launch_tiled(tiled_kernel_t kernel, bool* prepared, const void* const* h_layers, int32_t L, int32_t T, int32_t H_kv,
+                        int32_t d, int64_t k_token_stride, int64_t k_head_stride, void* d_sink, void* hip_stream) {
   if (!h_layers || !d_sink || L < 1 || L > SP_PROBE_MAX_LAYERS) return -1;
   if (T != 32768 || H_kv != 8 || d != 128 || k_token_stride < 128 || k_head_stride < 128) return -1;
   Layers ls{};
@@ -93,15 +106,27 @@ extern "C" int sp_probe_tiled(const void* const* h_layers, int32_t L, int32_t T,
     if (!h_layers[l]) return -1;
     ls.p[l] = static_cast<const unsigned char*>(h_layers[l]);
   }
-  static bool prepared = false;  // (benchmark helper: single-threaded use)
   const int smem = 8 * 2 * kTile;
-  if (!prepared) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(tiled_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+  if (!*prepared) {  // (benchmark helper: single-threaded use)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
         hipSuccess)
       return -6;
-    prepared = true;
+    *prepared = true;
   }
-  hipLaunchKernelGGL(tiled_kernel, dim3(256), dim3(512), smem, static_cast<hipStream_t>(hip_stream), ls, L,
-                     k_token_stride * 2, k_head_stride * 2, static_cast<unsigned*>(d_sink));
+  hipLaunchKernelGGL(kernel, dim3(256), dim3(512), smem, static_cast<hipStream_t>(hip_stream), ls, L, k_token_stride * 2,
+                     k_head_stride * 2, static_cast<unsigned*>(d_sink));
   return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+extern "C" int sp_probe_tiled(const void* const* h_layers, int32_t L, int32_t T, int32_t H_kv, int32_t d,
+                              int64_t k_token_stride, int64_t k_head_stride, void* d_sink, void* hip_stream) {
+  static bool prepared = false;
+  return launch_tiled(tiled_kernel, &prepared, h_layers, L, T, H_kv, d, k_token_stride, k_head_stride, d_sink, hip_stream);
+}
+
+extern "C" int sp_probe_tiled_default_policy(const void* const* h_layers, int32_t L, int32_t T, int32_t H_kv, int32_t d,
+                                             int64_t k_token_stride, int64_t k_head_stride, void* d_sink, void* hip_stream) {
+  static bool prepared = false;
+  return launch_tiled(tiled_default_policy_kernel, &prepared, h_layers, L, T, H_kv, d, k_token_stride, k_head_stride, d_sink,
+                      hip_stream);
 }

@@ -6,7 +6,7 @@ import ctypes as C
 import os
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspprobe.so")
-EXPORTS = ("sp_probe_read", "sp_probe_tiled")
+EXPORTS = ("sp_probe_read", "sp_probe_tiled", "sp_probe_tiled_default_policy")
 _lib = None
 
 
@@ -18,9 +18,10 @@ def load_library() -> C.CDLL:
         lib = C.CDLL(LIB_PATH)
         lib.sp_probe_read.restype = C.c_int
         lib.sp_probe_read.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
-        lib.sp_probe_tiled.restype = C.c_int
-        lib.sp_probe_tiled.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
-                                       C.c_int64, C.c_void_p, C.c_void_p]
+        for fn in (lib.sp_probe_tiled, lib.sp_probe_tiled_default_policy):
+            fn.restype = C.c_int
+            fn.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
+                           C.c_void_p]
         _lib = lib
     return _lib
 
@@ -66,4 +67,6 @@ def stream_ceiling(k_layers, reps: int = 30, warmup: int = 30) -> dict:
     if (T, H_kv, d) == (32768, 8, 128) and all(k.is_contiguous() for k in k_layers):
         ms = timed(lambda: check(lib.sp_probe_tiled(arr, L, T, H_kv, d, H_kv * d, d, sink.data_ptr(), handle)))
         out["scorer_pattern_read_gbps"] = total / (ms * 1e-3) / 1e9
+        ms = timed(lambda: check(lib.sp_probe_tiled_default_policy(arr, L, T, H_kv, d, H_kv * d, d, sink.data_ptr(), handle)))
+        out["scorer_pattern_read_default_cache_policy_gbps"] = total / (ms * 1e-3) / 1e9
     return out

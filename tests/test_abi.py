@@ -33,6 +33,7 @@ def test_probe_library_exports_what_its_header_declares():
     lib = probe.load_library()
     assert lib.sp_probe_read(None, 1, 16, 1, None, None) == -1          # argument checks need no GPU
     assert lib.sp_probe_tiled(None, 1, 32768, 8, 128, 1024, 128, None, None) == -1
+    assert lib.sp_probe_tiled_default_policy(None, 1, 32768, 8, 128, 1024, 128, None, None) == -1
 
 
 def test_struct_layouts_match_the_header_field_order():
